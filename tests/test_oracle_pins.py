@@ -1,0 +1,338 @@
+"""Pins for the CPU oracle: every check compares it with something that is NOT the oracle --
+values the paper prints, closed forms, hand-worked cases, textbook special cases, or a direct
+element-by-element evaluation of the definition written here in the test."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import apb_oracle as o
+from oracle import capi
+
+rng = np.random.default_rng(20230608)
+
+
+# ----------------------------------------------------------------------------- Table of T
+def _read_T(golden_dir):
+    rows = []
+    with open(os.path.join(golden_dir, "T_table.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            a, t, h, m = line.split()
+            num, den = a.split("/")
+            rows.append((int(num) / int(den), int(t), int(h), int(m)))
+    return rows
+
+
+def test_T_matches_printed_table(golden_dir):
+    rows = _read_T(golden_dir)
+    assert len(rows) == 4
+    for a_bar, t, h, m in rows:
+        p = int(a_bar + 1.5)
+        tt, hh, mm = o.T_transform(np.array([p]))
+        assert (int(tt[0]), int(hh[0]), int(mm[0])) == (t, h, m)
+
+
+def test_T_bijective_and_decoding_rules(golden_dir):
+    triples = {(t, h, m) for _, t, h, m in _read_T(golden_dir)}
+    assert len(triples) == 4                               # injective on the four levels
+    p = rng.integers(0, 4, 1000)
+    t, h, m = o.T_transform(p)
+    assert np.array_equal(o.T_inverse(t, h, m), p)
+    # decoding rules: t=1 -> 3/2, h=1 -> 1/2, m=1 & t=0 -> -3/2, m=0 & h=0 -> -1/2
+    assert np.all(p[t] == 3) and np.all(p[h] == 2)
+    assert np.all(p[m & ~t] == 0) and np.all(p[~m & ~h] == 1)
+
+
+def test_bitplanes_reproduce_T(golden_dir):
+    """The stored planes P0 (low bit of p) and P1 (high bit) give t, h, m by pure logic."""
+    for a_bar, t, h, m in _read_T(golden_dir):
+        p = int(a_bar + 1.5)
+        P0, P1 = p & 1, (p >> 1) & 1
+        assert (P1 & P0, P1 & (1 - P0), 1 - (P1 ^ P0)) == (t, h, m)
+
+
+# ----------------------------------------------------------------------------- Eq. 16 / 18 / 19
+def test_eq16_all_lengths():
+    for n in range(1, 131):
+        u = rng.integers(0, 2, n)
+        v = rng.integers(0, 2, n)
+        direct = int(np.sum((2 * u - 1) * (2 * v - 1)))
+        assert o.dot_1_1_xor(u, v) == direct
+        assert o.dot_1_1_xor(u, u) == n
+        assert o.dot_1_1_xor(u, 1 - u) == -n
+
+
+def test_mbm_is_masked_signed_agreement():
+    for n in (1, 2, 31, 32, 33, 100):
+        x, y, z = (rng.integers(0, 2, n) for _ in range(3))
+        direct = int(np.sum(((2 * x - 1) * (2 * y - 1))[z == 1]))
+        assert o.mbm(x, y, z) == direct
+
+
+def test_one_two_routine_equals_direct_sum():
+    for n in list(range(1, 70)) + [127, 128, 129, 500]:
+        w = rng.integers(0, 2, n)
+        p = rng.integers(0, 4, n)
+        direct = int(np.sum((2 * w - 1) * p))
+        assert o.dot_1_2_mbm_twice(w, p) == 2 * direct
+
+
+def test_printed_eq19_needs_level_weights():
+    """n=1, w=+1, a_bar=3/2: the printed sum of the two mbm terms gives 1, the true product is 3/2."""
+    w, p = np.array([1]), np.array([3])
+    t, h, m = o.T_transform(p)
+    assert o.mbm(w, t, m) + o.mbm(w, h, ~m) == 1
+    assert o.dot_1_2_mbm_twice(w, p) == 2 * 3              # (3/2 + 3/2) * 2 in units of s
+
+
+# ----------------------------------------------------------------------------- compress
+def test_partition_boundaries_and_sign_convention():
+    delta = np.float32(0.5)
+    W = np.array([[0.5, -0.5, np.nextafter(np.float32(0.5), np.float32(1)), -0.0, 0.0, -0.75, 2.0, -1e-30]],
+                 dtype=np.float32)
+    L = o.compress(W, delta, alpha=np.float32(0.25))
+    assert L["out"].tolist() == [[False, False, True, False, False, True, True, False]]
+    assert L["bit"].tolist() == [[True, False, True, True, True, False, True, False]]
+    assert L["row_ptr"].tolist() == [0, 3]
+    assert L["col_idx"].tolist() == [2, 5, 6]
+    # residuals w - alpha*sign(w), hand-computed (all exact in float32 here)
+    assert L["val"].tolist() == [float(np.float32(W[0, 2]) - np.float32(0.25)), -0.5, 1.75]
+    assert L["rowsum"].tolist() == [5 - 3]
+    assert int(L["sign_words"][0, 0]) == 0b01011101
+
+
+def test_sign_word_bit_order_and_padding():
+    W = -np.ones((2, 70), dtype=np.float32)
+    W[0, 0] = W[0, 33] = W[1, 69] = 1.0
+    L = o.compress(W, np.float32(10.0), alpha=np.float32(1.0))
+    sw = L["sign_words"]
+    assert sw.shape == (2, 3)
+    assert sw[0].tolist() == [1, 2, 0]
+    assert sw[1].tolist() == [0, 0, 1 << 5]
+
+
+def test_extreme_intervals_and_memory_formula():
+    N, K = 8, 128                                          # n = 1024 weights -> flat index needs 10 bits
+    W = rng.standard_normal((N, K)).astype(np.float32)
+    none = o.compress(W, np.float32(np.inf))
+    assert none["row_ptr"][-1] == 0 and none["val"].size == 0
+    allo = o.compress(W, np.float32(-1.0))
+    assert allo["row_ptr"][-1] == N * K
+    assert np.array_equal(allo["col_idx"].reshape(N, K), np.tile(np.arange(K), (N, 1)))
+    assert allo["alpha"] == 0.0                            # empty binarized set
+    assert np.array_equal(allo["val"].reshape(N, K), W)    # residual of alpha = 0 is w itself
+    assert o.position_bits(N, K) == 10
+    assert o.mem_bits(N, K, 0) == 1024
+    assert o.mem_bits(N, K, 7) == 1024 + 7 * (32 + 10)
+    assert o.position_bits(256, 256) == 16 and o.position_bits(4096, 4096) == 24
+
+
+def test_default_alpha_closed_forms():
+    W = np.full((4, 9), 0.125, dtype=np.float32)
+    W[::2] *= -1
+    assert o.default_alpha(W, np.float32(1.0)) == np.float32(0.125)
+    W[0, 0] = 50.0                                         # outlier: must not enter the mean
+    assert o.default_alpha(W, np.float32(1.0)) == np.float32(0.125)
+    W2 = np.array([[0.1, -0.3, 0.2, 7.0]], dtype=np.float32)
+    want = np.float32((np.float64(np.float32(0.1)) + np.float64(np.float32(0.3)) + np.float64(np.float32(0.2))) / 3)
+    assert o.default_alpha(W2, np.float32(1.0)) == want
+
+
+def test_reconstruction_matches_definition():
+    """alpha*sigma + scatter(val) must be Eq. 3's matrix: exact inside, within 1 ulp outside."""
+    W = (rng.standard_normal((13, 77)) * 0.05).astype(np.float32)
+    delta = np.float32(0.08)
+    L = o.compress(W, delta)
+    a = np.float64(L["alpha"])
+    rec = np.where(L["bit"], a, -a)
+    for n in range(13):
+        for j in range(L["row_ptr"][n], L["row_ptr"][n + 1]):
+            rec[n, L["col_idx"][j]] += np.float64(L["val"][j])
+    want = np.empty_like(rec)                              # Eq. 3, element by element
+    for n in range(13):
+        for k in range(77):
+            w = W[n, k]
+            want[n, k] = (a if w >= 0 else -a) if abs(w) <= delta else np.float64(w)
+    inside = np.abs(W) <= delta
+    assert np.array_equal(rec[inside], want[inside])
+    ulp = np.spacing(np.abs(W[~inside]).astype(np.float32)).astype(np.float64)
+    assert np.all(np.abs(rec[~inside] - want[~inside]) <= ulp)
+    assert L["row_ptr"][-1] == np.count_nonzero(~inside) > 0
+    assert np.array_equal(o.apb_dense(W, delta, L["alpha"]), want)
+
+
+# ----------------------------------------------------------------------------- quantizer
+def test_two_bit_quantizer_hand_cases():
+    s = np.float32(0.5)                                    # 1/s = 2 exactly
+    x = np.array([[-3.0, -0.0, 0.0, 0.24, 0.25, 0.26, 0.5, 0.75, 1.0, 1.25, 1.4, 1.5, 9.0, np.nan]],
+                 dtype=np.float32).T
+    #  x/s:          -6    0    0   .48  .5->0 .52  1   1.5->2  2  2.5->2 2.8   3    18   nan->0
+    want = [0, 0, 0, 0, 0, 1, 1, 2, 2, 2, 3, 3, 3, 0]
+    assert o.quantize(x, 2, s)[:, 0].tolist() == want
+    assert np.array_equal(o.dequantize(o.quantize(x, 2, s), s)[:, 0], np.array(want) * 0.5)
+
+
+def test_one_bit_quantizer_hand_cases():
+    x = np.array([[-1.0, -0.0, 0.0, 1e-30, -1e-30]], dtype=np.float32)
+    c = o.quantize(x, 1, np.float32(2.0))
+    assert c.tolist() == [[-1, 1, 1, 1, -1]]
+    assert o.dequantize(c, np.float32(2.0)).tolist() == [[-2.0, 2.0, 2.0, 2.0, -2.0]]
+    assert o.codes_of(c, 1).tolist() == [[0, 1, 1, 1, 0]]
+
+
+def test_pack_acts_layout():
+    c = np.zeros((40, 3), dtype=np.int8)
+    c[0, 0] = 1
+    c[33, 1] = 3
+    c[39, 2] = 2
+    buf = o.pack_acts(c, 2)
+    Kw, Mp = 2, 64
+    assert buf.size == o.acts_words(40, 3, 2) == Mp * (2 * Kw + 1)
+    planes = buf[: 2 * Kw * Mp].reshape(2, Kw, Mp)
+    want = np.zeros((2, Kw, Mp), dtype=np.uint32)
+    want[0, 0, 0] = 1
+    want[0, 1, 1] = 2
+    want[1, 1, 1] = 2
+    want[1, 1, 2] = 1 << 7
+    assert np.array_equal(planes, want)
+    assert buf[2 * Kw * Mp:].view(np.int32)[:4].tolist() == [1, 3, 2, 0]
+
+
+# ----------------------------------------------------------------------------- integer part
+SHAPES = [(1, 1, 1), (3, 5, 2), (7, 31, 9), (5, 32, 64), (4, 33, 65), (9, 100, 70), (2, 130, 1), (1, 64, 129)]
+
+
+@pytest.mark.parametrize("bits", [1, 2])
+@pytest.mark.parametrize("N,K,M", SHAPES)
+def test_integer_part_three_ways(N, K, M, bits):
+    bit = rng.integers(0, 2, (N, K)).astype(bool)
+    c = (rng.integers(0, 2, (K, M)) * 2 - 1 if bits == 1 else rng.integers(0, 4, (K, M))).astype(np.int8)
+    D = o.int_part_unpacked(bit, c)
+    direct = np.zeros((N, M), dtype=np.int64)              # the definition, element by element
+    for n in range(N):
+        for m in range(M):
+            direct[n, m] = sum((1 if bit[n, k] else -1) * int(c[k, m]) for k in range(K))
+    assert np.array_equal(D, direct)
+    sw = o.pack_bits_rows(bit)
+    packed = o.pack_acts(c, bits)
+    assert np.array_equal(o.int_part_packed(sw, packed, K, M, bits), direct)
+    assert np.array_equal(capi.int_packed(sw, packed, K, M, bits), direct)
+    assert np.array_equal(capi.int_packed(sw, packed, K, M, bits, threads=3), direct)
+    assert np.array_equal(capi.int_unpacked(bit, c), direct)
+    assert np.all(np.abs(direct) <= (3 if bits == 2 else 1) * K)
+    if bits == 2:                                          # the paper's T / mbm route, one column
+        for n in range(N):
+            assert o.dot_1_2_mbm_twice(bit[n], c[:, 0]) == 2 * direct[n, 0]
+    else:
+        for n in range(N):
+            assert o.dot_1_1_xor(bit[n], c[:, 0] > 0) == direct[n, 0]
+
+
+def test_integer_part_closed_forms():
+    N, K, M = 6, 75, 5
+    bit = rng.integers(0, 2, (N, K)).astype(bool)
+    rowsum = np.where(bit, 1, -1).sum(axis=1)
+    c3 = np.full((K, M), 3, dtype=np.int8)
+    assert np.array_equal(o.int_part_unpacked(bit, c3), np.repeat(3 * rowsum[:, None], M, 1))
+    sw, pk = o.pack_bits_rows(bit), o.pack_acts(c3, 2)
+    assert np.array_equal(capi.int_packed(sw, pk, K, M, 2), np.repeat(3 * rowsum[:, None], M, 1))
+    c0 = np.zeros((K, M), dtype=np.int8)
+    assert not capi.int_packed(sw, o.pack_acts(c0, 2), K, M, 2).any()
+    cs = np.where(bit[2], 1, -1).astype(np.int8)[:, None].repeat(M, 1)      # x = row 2 of sigma
+    D = capi.int_packed(sw, o.pack_acts(cs, 1), K, M, 1)
+    assert np.all(D[2] == K)
+
+
+# ----------------------------------------------------------------------------- decomposition (Eq. 13)
+def _case(N, K, M, bits, rho, seed):
+    g = np.random.default_rng(seed)
+    W = (g.standard_normal((N, K)) * 0.05).astype(np.float32)
+    a = np.sort(np.abs(W).ravel())
+    delta = np.float32(a[min(a.size - 1, int((1 - rho) * a.size))])
+    X = g.standard_normal((K, M)).astype(np.float32)
+    if bits == 2:
+        X = np.maximum(X, 0)
+    return W, delta, X, np.float32(1.0 if bits == 1 else 0.75)
+
+
+@pytest.mark.parametrize("bits", [1, 2])
+@pytest.mark.parametrize("N,K,M", [(1, 1, 1), (4, 37, 3), (16, 64, 5), (11, 100, 66), (3, 257, 2)])
+def test_forward_equals_dense_definition(N, K, M, bits):
+    W, delta, X, step = _case(N, K, M, bits, 0.1, N * 1000 + K + bits)
+    L = o.compress(W, delta)
+    c = o.quantize(X, bits, step)
+    F = o.forward(L, c, step)
+    # (i) exact algebra: alpha*sigma + residual, as one dense float64 matrix, times X_hat
+    a = np.float64(L["alpha"])
+    What = np.where(L["bit"], a, -a)
+    for n in range(N):
+        for j in range(L["row_ptr"][n], L["row_ptr"][n + 1]):
+            What[n, L["col_idx"][j]] += np.float64(L["val"][j])
+    xhat = o.dequantize(c, step)
+    Y1 = What @ xhat
+    mag = np.abs(What) @ np.abs(xhat) + 1e-300
+    assert np.max(np.abs(F["Y"].astype(np.float64) - Y1) / mag) < 2.0 ** -23   # one float32 rounding + fp64 noise
+    Yd = a * np.float64(step) * F["D"] + F["R"]
+    assert np.max(np.abs(Yd - Y1) / mag) < 1e-13
+    # (ii) against the definition (Eq. 3 matrix): differs only by the float32 rounding of each residual
+    Y2 = o.brute_force(W, delta, L["alpha"], X, bits, step)
+    slack = np.zeros((N, M))
+    for n in range(N):
+        for j in range(L["row_ptr"][n], L["row_ptr"][n + 1]):
+            k = L["col_idx"][j]
+            slack[n] += np.spacing(np.float32(abs(W[n, k]))) * np.abs(xhat[k])
+    assert np.all(np.abs(Yd - Y2) <= slack + 1e-13 * mag)
+    # the C loops agree with numpy bit for bit (same order of operations)
+    Fc = capi.forward(L, o.pack_acts(c, bits), c, bits, step, threads=2)
+    assert np.array_equal(Fc["D"], F["D"]) and np.array_equal(Fc["R"], F["R"]) and np.array_equal(Fc["Y"], F["Y"])
+
+
+def test_special_cases_reduce_to_textbook_products():
+    W, _, X, step = _case(9, 70, 12, 2, 0.1, 5)
+    c = o.quantize(X, 2, step)
+    xhat = c.astype(np.float64) * 0.75
+    # every weight an outlier, alpha = 0: a plain dense product W @ X_hat
+    L = o.compress(W, np.float32(-1.0))
+    Y = o.forward(L, c, step)["Y"]
+    assert np.allclose(Y, W.astype(np.float64) @ xhat, rtol=1e-6, atol=1e-9)
+    # no outliers: XNOR-Net style layer alpha * sign(W) @ X_hat
+    L = o.compress(W, np.float32(np.inf), alpha=np.float32(0.03))
+    Y = o.forward(L, c, step)["Y"]
+    want = np.float64(np.float32(0.03)) * (np.where(W >= 0, 1.0, -1.0) @ xhat)
+    assert np.allclose(Y, want, rtol=1e-6, atol=1e-9)
+    # 1-bit activations, no outliers: alpha * beta * (K - 2 popcount(xor))
+    X1 = rng.standard_normal((70, 12)).astype(np.float32)
+    c1 = o.quantize(X1, 1, np.float32(0.5))
+    Y = o.forward(L, c1, np.float32(0.5))["Y"]
+    n, m = 4, 7
+    pc = np.count_nonzero((W[n] >= 0) != (X1[:, m] >= 0))
+    assert Y[n, m] == np.float32(np.float64(np.float32(0.03)) * 0.5 * (70 - 2 * pc))
+
+
+def test_additivity_of_the_two_parts():
+    W, delta, X, step = _case(8, 90, 10, 2, 0.1, 11)
+    c = o.quantize(X, 2, step)
+    L = o.compress(W, delta)
+    full = o.forward(L, c, step)
+    only_bin = dict(L, row_ptr=np.zeros(9, np.int32), col_idx=L["col_idx"][:0], val=L["val"][:0])
+    only_sp = dict(L, alpha=np.float32(0.0))
+    yb = o.forward(only_bin, c, step)
+    ys = o.forward(only_sp, c, step)
+    assert not yb["R"].any()
+    tot = np.float64(L["alpha"]) * 0.75 * yb["D"] + ys["R"]
+    assert np.array_equal(tot.astype(np.float32), full["Y"])
+
+
+def test_empty_and_full_rows():
+    W = (rng.standard_normal((5, 40)) * 0.01).astype(np.float32)
+    W[1] = 5.0                                             # a row made of outliers only
+    W[3, 7] = -4.0
+    X = np.maximum(rng.standard_normal((40, 6)), 0).astype(np.float32)
+    L = o.compress(W, np.float32(1.0))
+    assert np.diff(L["row_ptr"]).tolist() == [0, 40, 0, 1, 0]
+    c = o.quantize(X, 2, np.float32(0.75))
+    F = o.forward(L, c, np.float32(0.75))
+    Yb = o.brute_force(W, np.float32(1.0), L["alpha"], X, 2, np.float32(0.75))
+    assert np.allclose(F["Y"], Yb, rtol=1e-6, atol=1e-7)
