@@ -1,0 +1,126 @@
+/* apb.h -- C ABI of the MI355X (gfx950) library for the forward pass of an
+ * Automatic Prune Binarization (APB) layer, arXiv 2306.08960.
+ *
+ * The layer computes (Sec. III, "Inference Considerations", Eqs. 11-13)
+ *
+ *      Y = A^bin * X^ + A^full * X^ ,
+ *
+ * where A^bin = alpha * sign(W) holds ONE BIT FOR EVERY weight (the binary
+ * matrix is fully represented, Sec. III "Memory Impact"), A^full is the sparse
+ * matrix of the residuals w - alpha*sign(w) of the few weights whose magnitude
+ * lies outside the binarization interval (Eq. 3), and X^ are the activations
+ * quantized to 1 bit (+-beta, Sec. IV "1/1") or 2 bits (p*s, p in 0..3,
+ * Sec. IV "1/2").  The binary product runs on packed words with
+ * logic + popcount (Eqs. 16, 18, 19); the sparse product reads the same packed
+ * activations.
+ *
+ * Shapes and names: W is N x K row-major (N output channels, K = C_in*kh*kw),
+ * X is K x M row-major (column m = one im2col patch), Y is N x M row-major.
+ *
+ * Conventions
+ *  - Every function returns APB_OK (0) or a negative apb_status; nothing throws
+ *    and nothing aborts.  apb_strerror() names a code; after APB_ERR_HIP,
+ *    apb_last_hip_error() returns the hipError_t of the calling thread.
+ *  - "DEVICE" pointers are HIP device memory of the current device and must be
+ *    4-byte aligned; the caller owns them.  The library owns only what lives
+ *    inside an apb_layer.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    apb_quantize_acts / apb_forward / apb_forward_int only enqueue work and
+ *    return; apb_compress and apb_layer_export synchronize the stream.
+ *  - Non-finite values in W or X give unspecified numbers but never touch
+ *    memory out of bounds (a NaN activation quantizes to code 0 / sign -).
+ *  - Distinct layers and buffers may be used from distinct host threads.
+ */
+#ifndef APB_H_
+#define APB_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum apb_status {
+    APB_OK = 0,
+    APB_ERR_NULL = -1,     /* a required pointer is NULL                                   */
+    APB_ERR_SHAPE = -2,    /* N, K or M <= 0, or too large (N*K >= 2^31, 3*K >= 2^31, ...)  */
+    APB_ERR_BITS = -3,     /* bits is not 1 or 2                                           */
+    APB_ERR_VALUE = -4,    /* delta is NaN; alpha negative or infinite; step not finite or <= 0 */
+    APB_ERR_NOMEM = -5,    /* host or device allocation failed                             */
+    APB_ERR_HIP = -6       /* a HIP call failed; see apb_last_hip_error()                  */
+} apb_status;
+
+/* Opaque compressed layer.  Holds, in device memory: the sign words, the CSR of
+ * residuals, per-row sign sums and a launch-order row permutation. */
+typedef struct apb_layer apb_layer;
+
+/* Sec. III Eq. 1 (sign(0) = +), Eq. 3 (partition), Eqs. 11-12 (A^bin, A^full).
+ *   W      DEVICE, N*K floats, row-major, read-only.
+ *   delta  half-width of the binarization interval: weight w is binarized iff
+ *          |w| <= delta (exact float compare).  This is the paper's alpha + delta.
+ *          +inf keeps no residuals; a negative value makes every weight a residual.
+ *   alpha  the layer scale.  A finite value >= 0 is used as given (a learned
+ *          scale); NaN asks for the default: the mean of |w| over the binarized
+ *          set (float64 sum, rounded to float), 0 if that set is empty.
+ *   out    receives a new layer on APB_OK (free with apb_layer_free), NULL otherwise.
+ * Per weight: sign bit = (w >= 0).  Per residual: val = w - (bit ? alpha : -alpha),
+ * a single float subtraction.  Synchronizes `stream`. */
+int apb_compress(const float* W, int N, int K, float delta, float alpha, void* stream, apb_layer** out);
+
+/* Sizes and scalars of a layer; any output pointer may be NULL.
+ *   mem_bits  Sec. III Eq. 10 in its fully represented form, N*K + nnz*(32 + b_p),
+ *             with b_p = floor(log2(N*K - 1)) + 1 (bits of a flat index; 1 if N*K <= 2). */
+int apb_layer_info(const apb_layer* layer, int* N, int* K, float* alpha, long long* nnz, long long* mem_bits);
+
+/* Copy the canonical representation out (each destination may be NULL to skip it;
+ * destinations may be device or host memory):
+ *   sign_words  N * ceil(K/32) uint32, row-major; bit i of word j of row n is 1 iff
+ *               W[n, 32*j+i] >= 0; bits beyond K are 0.
+ *   row_ptr     N+1 int32;  col_idx  nnz int32, ascending inside a row;  val  nnz floats.
+ *   rowsum      N int32, sum over k of (+1 | -1) of row n (the weight-only term of the
+ *               zero-centred form, Sec. IV "1/2").
+ * Synchronizes `stream`. */
+int apb_layer_export(const apb_layer* layer, uint32_t* sign_words, int32_t* row_ptr, int32_t* col_idx,
+                     float* val, int32_t* rowsum, void* stream);
+
+/* NULL-safe.  The caller makes sure no enqueued work still uses the layer. */
+void apb_layer_free(apb_layer* layer);
+
+/* Size in bytes of the packed activation buffer for a K x M matrix; 0 on bad arguments.
+ * Layout, with Kw = ceil(K/32) and Mp = 64*ceil(M/64):
+ *   uint32 planes[bits][Kw][Mp]   bit i of planes[b][j][m] = bit b of the code of X[32*j+i, m]
+ *   int32  colsum[Mp]             sum over k of code[k, m]
+ * Codes: 1-bit, code = (x >= 0) and the value is (2*code-1)*step; 2-bit, code = the
+ * level index p and the value is p*step.  Columns m >= M and bits k >= K are zero. */
+size_t apb_acts_bytes(int K, int M, int bits);
+
+/* Sec. IV: quantize and pack the activations.
+ *   X       DEVICE, K*M floats row-major, read-only.
+ *   bits    1: sign, sign(0) = +.   2: p = clamp(rint(x * (1/step)), 0, 3), float
+ *           arithmetic, round-half-to-even, 1/step computed once in float.
+ *   step    beta (1 bit) or s (2 bits); finite and > 0.
+ *   packed  DEVICE, apb_acts_bytes(K, M, bits) bytes, fully overwritten.
+ * Asynchronous on `stream`. */
+int apb_quantize_acts(const float* X, int K, int M, int bits, float step, void* packed, void* stream);
+
+/* Sec. III Eq. 13 with the scalar multipliers of Sec. IV:
+ *      Y[n,m] = alpha*step * D[n,m] + sum_{j in row n} val_j * step * c[col_j, m]
+ * where c is the integer activation value (+-1 or p) and D = sum_k sign(W[n,k]) * c[k,m]
+ * is computed exactly in integers from the packed words.  The sparse sum and the
+ * combination are accumulated in float64 and rounded once to float.
+ *   packed  DEVICE buffer written by apb_quantize_acts with the SAME K (the layer's), M, bits.
+ *   Y       DEVICE, N*M floats row-major, fully overwritten.
+ * Asynchronous on `stream`. */
+int apb_forward(const apb_layer* layer, const void* packed, int M, int bits, float step, float* Y, void* stream);
+
+/* Test hook: the integer part D (N*M int32, row-major, DEVICE) alone. Asynchronous on `stream`. */
+int apb_forward_int(const apb_layer* layer, const void* packed, int M, int bits, int32_t* D, void* stream);
+
+const char* apb_strerror(int code);
+int apb_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* APB_H_ */

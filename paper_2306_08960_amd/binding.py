@@ -1,0 +1,216 @@
+"""Thin Python binding over libapb.so (argument marshalling only).
+
+Every step of the APB layer forward pass runs in the HIP kernels of the library; PyTorch is
+used for device memory and streams, nothing else.  There is no CPU fallback: if the library
+is missing or cannot be loaded, importing this module's functions raises.
+
+Function names and argument order follow include/apb.h.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libapb.so")
+
+EXPORTS = (
+    "apb_compress", "apb_layer_info", "apb_layer_export", "apb_layer_free", "apb_acts_bytes",
+    "apb_quantize_acts", "apb_forward", "apb_forward_int", "apb_strerror", "apb_last_hip_error",
+)
+
+APB_OK = 0
+APB_ERR_NULL, APB_ERR_SHAPE, APB_ERR_BITS, APB_ERR_VALUE, APB_ERR_NOMEM, APB_ERR_HIP = -1, -2, -3, -4, -5, -6
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+class ApbError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {strerror(code)} (status {code})")
+        self.code = code
+
+
+def load() -> ctypes.CDLL:
+    """Load libapb.so; raises if it has not been built (python paper_2306_08960_amd/build.py)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python {os.path.join(_HERE, 'build.py')}` "
+                           "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+    lib.apb_compress.argtypes = [vp, ci, ci, cf, cf, vp, ctypes.POINTER(vp)]
+    lib.apb_compress.restype = ci
+    lib.apb_layer_info.argtypes = [vp, ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(cf),
+                                   ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(ctypes.c_longlong)]
+    lib.apb_layer_info.restype = ci
+    lib.apb_layer_export.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.apb_layer_export.restype = ci
+    lib.apb_layer_free.argtypes = [vp]
+    lib.apb_layer_free.restype = None
+    lib.apb_acts_bytes.argtypes = [ci, ci, ci]
+    lib.apb_acts_bytes.restype = ctypes.c_size_t
+    lib.apb_quantize_acts.argtypes = [vp, ci, ci, ci, cf, vp, vp]
+    lib.apb_quantize_acts.restype = ci
+    lib.apb_forward.argtypes = [vp, vp, ci, ci, cf, vp, vp]
+    lib.apb_forward.restype = ci
+    lib.apb_forward_int.argtypes = [vp, vp, ci, ci, vp, vp]
+    lib.apb_forward_int.restype = ci
+    lib.apb_strerror.argtypes = [ci]
+    lib.apb_strerror.restype = ctypes.c_char_p
+    lib.apb_last_hip_error.argtypes = []
+    lib.apb_last_hip_error.restype = ci
+    _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load().apb_strerror(int(code)).decode()
+
+
+def _check(code: int, what: str) -> None:
+    if code != APB_OK:
+        extra = f" [hipError {load().apb_last_hip_error()}]" if code == APB_ERR_HIP else ""
+        raise ApbError(code, what + extra)
+
+
+def _stream(stream: Optional[torch.cuda.Stream]) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def _dev_ptr(t: torch.Tensor, dtype: torch.dtype, name: str) -> int:
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name} must be a contiguous {dtype} tensor on the GPU")
+    return t.data_ptr()
+
+
+class ApbLayer:
+    """Owner of one opaque apb_layer handle."""
+
+    def __init__(self, handle: int):
+        self._h = ctypes.c_void_p(handle)
+
+    @property
+    def handle(self) -> ctypes.c_void_p:
+        if not self._h:
+            raise RuntimeError("layer already freed")
+        return self._h
+
+    def info(self) -> dict:
+        return apb_layer_info(self)
+
+    def free(self) -> None:
+        if self._h:
+            load().apb_layer_free(self._h)
+            self._h = ctypes.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def apb_compress(W: torch.Tensor, delta: float, alpha: Optional[float] = None,
+                 stream: Optional[torch.cuda.Stream] = None) -> ApbLayer:
+    """W: [N,K] float32 on the GPU.  alpha=None asks the library for its default scale."""
+    if W.dim() != 2:
+        raise TypeError("W must be 2-D [N, K]")
+    ptr = _dev_ptr(W, torch.float32, "W")
+    N, K = W.shape
+    out = ctypes.c_void_p(None)
+    a = math.nan if alpha is None else float(alpha)
+    _check(load().apb_compress(ptr, N, K, float(delta), a, _stream(stream), ctypes.byref(out)), "apb_compress")
+    return ApbLayer(out.value)
+
+
+def apb_layer_info(layer: ApbLayer) -> dict:
+    N, K, a = ctypes.c_int(), ctypes.c_int(), ctypes.c_float()
+    nnz, bits = ctypes.c_longlong(), ctypes.c_longlong()
+    _check(load().apb_layer_info(layer.handle, ctypes.byref(N), ctypes.byref(K), ctypes.byref(a),
+                                 ctypes.byref(nnz), ctypes.byref(bits)), "apb_layer_info")
+    return {"N": N.value, "K": K.value, "alpha": a.value, "nnz": nnz.value, "mem_bits": bits.value}
+
+
+def apb_layer_export(layer: ApbLayer, stream: Optional[torch.cuda.Stream] = None) -> dict:
+    """Canonical representation as GPU tensors: sign_words uint32-as-int32 [N,Kw], CSR, rowsum."""
+    i = apb_layer_info(layer)
+    N, K, nnz = i["N"], i["K"], i["nnz"]
+    Kw = (K + 31) // 32
+    dev = torch.device("cuda", torch.cuda.current_device())
+    sign = torch.empty((N, Kw), dtype=torch.int32, device=dev)
+    row_ptr = torch.empty(N + 1, dtype=torch.int32, device=dev)
+    col = torch.empty(max(nnz, 1), dtype=torch.int32, device=dev)
+    val = torch.empty(max(nnz, 1), dtype=torch.float32, device=dev)
+    rowsum = torch.empty(N, dtype=torch.int32, device=dev)
+    _check(load().apb_layer_export(layer.handle, sign.data_ptr(), row_ptr.data_ptr(), col.data_ptr(),
+                                   val.data_ptr(), rowsum.data_ptr(), _stream(stream)), "apb_layer_export")
+    return {"sign_words": sign, "row_ptr": row_ptr, "col_idx": col[:nnz], "val": val[:nnz], "rowsum": rowsum,
+            **i}
+
+
+def apb_acts_bytes(K: int, M: int, bits: int) -> int:
+    return int(load().apb_acts_bytes(int(K), int(M), int(bits)))
+
+
+def alloc_packed(K: int, M: int, bits: int, device=None) -> torch.Tensor:
+    nbytes = apb_acts_bytes(K, M, bits)
+    if nbytes == 0:
+        raise ApbError(APB_ERR_SHAPE if bits in (1, 2) else APB_ERR_BITS, "apb_acts_bytes")
+    dev = device if device is not None else torch.device("cuda", torch.cuda.current_device())
+    return torch.empty(nbytes // 4, dtype=torch.int32, device=dev)
+
+
+def apb_quantize_acts(X: torch.Tensor, bits: int, step: float, packed: Optional[torch.Tensor] = None,
+                      stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """X: [K,M] float32 on the GPU -> packed int32 buffer (planes + column sums)."""
+    if X.dim() != 2:
+        raise TypeError("X must be 2-D [K, M]")
+    ptr = _dev_ptr(X, torch.float32, "X")
+    K, M = X.shape
+    if packed is None:
+        packed = alloc_packed(K, M, bits, X.device)
+    elif packed.numel() * packed.element_size() < apb_acts_bytes(K, M, bits):
+        raise ValueError("packed buffer too small")
+    _check(load().apb_quantize_acts(ptr, K, M, int(bits), float(step), _dev_ptr(packed, torch.int32, "packed"),
+                                    _stream(stream)), "apb_quantize_acts")
+    return packed
+
+
+def _check_packed(layer: ApbLayer, packed: torch.Tensor, M: int, bits: int) -> Tuple[int, int]:
+    i = apb_layer_info(layer)
+    need = apb_acts_bytes(i["K"], M, bits)
+    if need and packed.numel() * packed.element_size() < need:
+        raise ValueError("packed buffer smaller than apb_acts_bytes(K, M, bits)")
+    return i["N"], i["K"]
+
+
+def apb_forward(layer: ApbLayer, packed: torch.Tensor, M: int, bits: int, step: float,
+                Y: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    N, _ = _check_packed(layer, packed, M, bits)
+    if Y is None:
+        Y = torch.empty((N, M), dtype=torch.float32, device=packed.device)
+    elif tuple(Y.shape) != (N, M):
+        raise ValueError("Y must be [N, M]")
+    _check(load().apb_forward(layer.handle, _dev_ptr(packed, torch.int32, "packed"), int(M), int(bits),
+                              float(step), _dev_ptr(Y, torch.float32, "Y"), _stream(stream)), "apb_forward")
+    return Y
+
+
+def apb_forward_int(layer: ApbLayer, packed: torch.Tensor, M: int, bits: int,
+                    D: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    N, _ = _check_packed(layer, packed, M, bits)
+    if D is None:
+        D = torch.empty((N, M), dtype=torch.int32, device=packed.device)
+    elif tuple(D.shape) != (N, M):
+        raise ValueError("D must be [N, M]")
+    _check(load().apb_forward_int(layer.handle, _dev_ptr(packed, torch.int32, "packed"), int(M), int(bits),
+                                  _dev_ptr(D, torch.int32, "D"), _stream(stream)), "apb_forward_int")
+    return D

@@ -1,0 +1,271 @@
+// Host side of the C ABI: argument checks, layer ownership, launch-order row binning.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <numeric>
+#include <vector>
+
+#include "apb_internal.h"
+
+namespace apb {
+
+static thread_local int g_last_hip_error = 0;
+void set_last_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
+
+namespace {
+
+hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+void free_layer_buffers(LayerDev& d) {
+    void* ptrs[] = {d.sign, d.signT, d.perm, d.row_ptr, d.col_idx, d.val, d.rowsum};
+    for (void* p : ptrs)
+        if (p) (void)hipFree(p);
+    d = LayerDev{};
+}
+
+template <typename T>
+int dev_alloc(T** p, size_t count) {
+    *p = nullptr;
+    if (count == 0) count = 1;                       // keep pointers non-null for empty CSR
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(p), count * sizeof(T));
+    if (e == hipErrorOutOfMemory) return APB_ERR_NOMEM;
+    if (e != hipSuccess) {
+        set_last_hip_error(e);
+        return APB_ERR_HIP;
+    }
+    return APB_OK;
+}
+
+// Launch-order row binning for the skewed residual counts: rows sorted by decreasing residual
+// count are dealt to the row tiles like cards, forwards then backwards (a "snake"), so every
+// tile of kRowTile rows carries about the same number of residuals.
+std::vector<int32_t> balanced_slots(const std::vector<int32_t>& counts, int Np) {
+    const int N = (int)counts.size();
+    const int tiles = Np / kRowTile;
+    std::vector<int32_t> order(N);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return counts[a] > counts[b]; });
+    std::vector<int32_t> perm(Np, -1);
+    std::vector<int> fill(tiles, 0);
+    for (int i = 0; i < N; ++i) {
+        const int round = i / tiles, pos = i % tiles;
+        const int t = (round & 1) ? tiles - 1 - pos : pos;
+        perm[t * kRowTile + fill[t]++] = order[i];
+    }
+    return perm;
+}
+
+int compress_impl(const float* W, int N, int K, float delta, float alpha, hipStream_t s, LayerDev& d) {
+    d.N = N;
+    d.K = K;
+    d.Kw = (K + 31) / 32;
+    d.Np = kRowTile * ((N + kRowTile - 1) / kRowTile);
+    int rc;
+
+    if (std::isnan(alpha)) {                          // default scale: mean |w| over the binarized set
+        constexpr int kParts = 1024;
+        double* part_sum = nullptr;
+        long long* part_cnt = nullptr;
+        if ((rc = dev_alloc(&part_sum, kParts)) != APB_OK) return rc;
+        if ((rc = dev_alloc(&part_cnt, kParts)) != APB_OK) {
+            (void)hipFree(part_sum);
+            return rc;
+        }
+        std::vector<double> hs(kParts);
+        std::vector<long long> hc(kParts);
+        rc = launch_inlier_abs_sum(W, (long long)N * K, delta, part_sum, part_cnt, kParts, s);
+        hipError_t e = hipSuccess;
+        if (rc == APB_OK) e = hipMemcpyAsync(hs.data(), part_sum, kParts * sizeof(double), hipMemcpyDeviceToHost, s);
+        if (rc == APB_OK && e == hipSuccess)
+            e = hipMemcpyAsync(hc.data(), part_cnt, kParts * sizeof(long long), hipMemcpyDeviceToHost, s);
+        if (rc == APB_OK && e == hipSuccess) e = hipStreamSynchronize(s);
+        (void)hipFree(part_sum);
+        (void)hipFree(part_cnt);
+        if (rc != APB_OK) return rc;
+        APB_HIP(e);
+        double total = 0.0;
+        long long cnt = 0;
+        for (int i = 0; i < kParts; ++i) {
+            total += hs[i];
+            cnt += hc[i];
+        }
+        alpha = cnt > 0 ? (float)(total / (double)cnt) : 0.0f;
+    }
+    d.alpha = alpha;
+
+    int32_t* counts = nullptr;
+    if ((rc = dev_alloc(&d.sign, (size_t)N * d.Kw)) != APB_OK) return rc;
+    if ((rc = dev_alloc(&d.rowsum, (size_t)N)) != APB_OK) return rc;
+    if ((rc = dev_alloc(&d.row_ptr, (size_t)N + 1)) != APB_OK) return rc;
+    if ((rc = dev_alloc(&d.perm, (size_t)d.Np)) != APB_OK) return rc;
+    if ((rc = dev_alloc(&d.signT, (size_t)d.Np * d.Kw)) != APB_OK) return rc;
+    if ((rc = dev_alloc(&counts, (size_t)N)) != APB_OK) return rc;
+
+    std::vector<int32_t> hcounts(N);
+    rc = launch_sign_pack_count(W, N, K, d.Kw, delta, d.sign, counts, d.rowsum, s);
+    hipError_t e = hipSuccess;
+    if (rc == APB_OK) e = hipMemcpyAsync(hcounts.data(), counts, (size_t)N * sizeof(int32_t), hipMemcpyDeviceToHost, s);
+    if (rc == APB_OK && e == hipSuccess) e = hipStreamSynchronize(s);
+    (void)hipFree(counts);
+    if (rc != APB_OK) return rc;
+    APB_HIP(e);
+
+    std::vector<int32_t> hrow_ptr((size_t)N + 1, 0);
+    long long nnz = 0;
+    for (int n = 0; n < N; ++n) {
+        nnz += hcounts[n];
+        hrow_ptr[n + 1] = (int32_t)nnz;
+    }
+    d.nnz = nnz;
+    const std::vector<int32_t> hperm = balanced_slots(hcounts, d.Np);
+
+    if ((rc = dev_alloc(&d.col_idx, (size_t)nnz)) != APB_OK) return rc;
+    if ((rc = dev_alloc(&d.val, (size_t)nnz)) != APB_OK) return rc;
+    APB_HIP(hipMemcpyAsync(d.row_ptr, hrow_ptr.data(), ((size_t)N + 1) * sizeof(int32_t), hipMemcpyHostToDevice, s));
+    APB_HIP(hipMemcpyAsync(d.perm, hperm.data(), (size_t)d.Np * sizeof(int32_t), hipMemcpyHostToDevice, s));
+    if (nnz > 0 && (rc = launch_scatter_csr(W, N, K, delta, alpha, d.row_ptr, d.col_idx, d.val, s)) != APB_OK) return rc;
+    if ((rc = launch_slot_major_signs(d.sign, d.perm, d.Np, d.Kw, d.signT, s)) != APB_OK) return rc;
+    APB_HIP(hipStreamSynchronize(s));                 // host staging vectors go out of scope after this
+    return APB_OK;
+}
+
+int position_bits(long long n) {
+    if (n <= 2) return 1;
+    int b = 0;
+    for (long long v = n - 1; v > 0; v >>= 1) ++b;
+    return b;
+}
+
+bool bad_shape_acts(int K, int M) {
+    if (K <= 0 || M <= 0) return true;
+    if ((long long)K * 3 >= (1LL << 31)) return true;
+    if ((long long)M + kWave >= (1LL << 31)) return true;
+    return false;
+}
+
+}  // namespace
+}  // namespace apb
+
+using namespace apb;
+
+extern "C" {
+
+int apb_compress(const float* W, int N, int K, float delta, float alpha, void* stream, apb_layer** out) {
+    if (out) *out = nullptr;
+    if (!W || !out) return APB_ERR_NULL;
+    if (N <= 0 || K <= 0 || (long long)N * K >= (1LL << 31) || (long long)K * 3 >= (1LL << 31)) return APB_ERR_SHAPE;
+    if (std::isnan(delta)) return APB_ERR_VALUE;
+    if (!std::isnan(alpha) && (alpha < 0.0f || std::isinf(alpha))) return APB_ERR_VALUE;
+    apb_layer* L = new (std::nothrow) apb_layer();
+    if (!L) return APB_ERR_NOMEM;
+    int rc;
+    try {
+        rc = compress_impl(W, N, K, delta, alpha, as_stream(stream), L->d);
+    } catch (const std::bad_alloc&) {
+        rc = APB_ERR_NOMEM;
+    }
+    if (rc != APB_OK) {
+        free_layer_buffers(L->d);
+        delete L;
+        return rc;
+    }
+    *out = L;
+    return APB_OK;
+}
+
+int apb_layer_info(const apb_layer* layer, int* N, int* K, float* alpha, long long* nnz, long long* mem_bits) {
+    if (!layer) return APB_ERR_NULL;
+    const LayerDev& d = layer->d;
+    if (N) *N = d.N;
+    if (K) *K = d.K;
+    if (alpha) *alpha = d.alpha;
+    if (nnz) *nnz = d.nnz;
+    if (mem_bits) {
+        const long long n = (long long)d.N * d.K;
+        *mem_bits = n + d.nnz * (32 + position_bits(n));
+    }
+    return APB_OK;
+}
+
+int apb_layer_export(const apb_layer* layer, uint32_t* sign_words, int32_t* row_ptr, int32_t* col_idx, float* val,
+                     int32_t* rowsum, void* stream) {
+    if (!layer) return APB_ERR_NULL;
+    const LayerDev& d = layer->d;
+    hipStream_t s = as_stream(stream);
+    if (sign_words)
+        APB_HIP(hipMemcpyAsync(sign_words, d.sign, (size_t)d.N * d.Kw * sizeof(uint32_t), hipMemcpyDefault, s));
+    if (row_ptr) APB_HIP(hipMemcpyAsync(row_ptr, d.row_ptr, ((size_t)d.N + 1) * sizeof(int32_t), hipMemcpyDefault, s));
+    if (col_idx && d.nnz > 0)
+        APB_HIP(hipMemcpyAsync(col_idx, d.col_idx, (size_t)d.nnz * sizeof(int32_t), hipMemcpyDefault, s));
+    if (val && d.nnz > 0) APB_HIP(hipMemcpyAsync(val, d.val, (size_t)d.nnz * sizeof(float), hipMemcpyDefault, s));
+    if (rowsum) APB_HIP(hipMemcpyAsync(rowsum, d.rowsum, (size_t)d.N * sizeof(int32_t), hipMemcpyDefault, s));
+    APB_HIP(hipStreamSynchronize(s));
+    return APB_OK;
+}
+
+void apb_layer_free(apb_layer* layer) {
+    if (!layer) return;
+    free_layer_buffers(layer->d);
+    delete layer;
+}
+
+size_t apb_acts_bytes(int K, int M, int bits) {
+    if (bad_shape_acts(K, M) || (bits != 1 && bits != 2)) return 0;
+    const size_t Kw = ((size_t)K + 31) / 32;
+    const size_t Mp = (size_t)kWave * (((size_t)M + kWave - 1) / kWave);
+    return sizeof(uint32_t) * Mp * ((size_t)bits * Kw + 1);
+}
+
+int apb_quantize_acts(const float* X, int K, int M, int bits, float step, void* packed, void* stream) {
+    if (!X || !packed) return APB_ERR_NULL;
+    if (bad_shape_acts(K, M)) return APB_ERR_SHAPE;
+    if (bits != 1 && bits != 2) return APB_ERR_BITS;
+    if (!std::isfinite(step) || !(step > 0.0f)) return APB_ERR_VALUE;
+    const size_t Kw = ((size_t)K + 31) / 32;
+    const size_t Mp = (size_t)kWave * (((size_t)M + kWave - 1) / kWave);
+    uint32_t* planes = static_cast<uint32_t*>(packed);
+    int32_t* colsum = reinterpret_cast<int32_t*>(planes + (size_t)bits * Kw * Mp);
+    const float inv_step = 1.0f / step;
+    return launch_quantize(X, K, M, bits, inv_step, planes, colsum, as_stream(stream));
+}
+
+static int forward_common(const apb_layer* layer, const void* packed, int M, int bits, float step, float* Y,
+                          int32_t* D, void* stream) {
+    if (!layer || !packed || (!Y && !D)) return APB_ERR_NULL;
+    const LayerDev& d = layer->d;
+    if (bad_shape_acts(d.K, M) || (long long)d.N * M >= (1LL << 40)) return APB_ERR_SHAPE;
+    if (bits != 1 && bits != 2) return APB_ERR_BITS;
+    if (Y && (!std::isfinite(step) || !(step > 0.0f))) return APB_ERR_VALUE;
+    const size_t Mp = (size_t)kWave * (((size_t)M + kWave - 1) / kWave);
+    const uint32_t* planes = static_cast<const uint32_t*>(packed);
+    const int32_t* colsum = reinterpret_cast<const int32_t*>(planes + (size_t)bits * d.Kw * Mp);
+    return launch_forward(d, planes, colsum, M, bits, step, Y, D, as_stream(stream));
+}
+
+int apb_forward(const apb_layer* layer, const void* packed, int M, int bits, float step, float* Y, void* stream) {
+    if (!Y) return APB_ERR_NULL;
+    return forward_common(layer, packed, M, bits, step, Y, nullptr, stream);
+}
+
+int apb_forward_int(const apb_layer* layer, const void* packed, int M, int bits, int32_t* D, void* stream) {
+    if (!D) return APB_ERR_NULL;
+    return forward_common(layer, packed, M, bits, 1.0f, nullptr, D, stream);
+}
+
+const char* apb_strerror(int code) {
+    switch (code) {
+        case APB_OK: return "ok";
+        case APB_ERR_NULL: return "a required pointer is NULL";
+        case APB_ERR_SHAPE: return "bad shape (non-positive or too large)";
+        case APB_ERR_BITS: return "activation bits must be 1 or 2";
+        case APB_ERR_VALUE: return "bad scalar (delta NaN, alpha negative/infinite, or step not finite and > 0)";
+        case APB_ERR_NOMEM: return "out of memory";
+        case APB_ERR_HIP: return "a HIP call failed (see apb_last_hip_error)";
+        default: return "unknown apb status";
+    }
+}
+
+int apb_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,164 @@
+// Kernels behind apb_compress: the partition of Sec. III Eq. 3, the sign bits of Eq. 1 packed
+// for every weight ("fully represented" binary matrix), and the CSR of residuals of Eq. 12.
+#include "apb_internal.h"
+
+namespace apb {
+
+namespace {
+
+constexpr int kBlock = 256;
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+
+// Sum of |w| and count over the binarized set {|w| <= delta}; one (sum, count) pair per block.
+__global__ __launch_bounds__(kBlock) void k_inlier_abs_sum(const float* __restrict__ W, long long count,
+                                                           float delta, double* __restrict__ part_sum,
+                                                           long long* __restrict__ part_cnt) {
+    __shared__ double s_sum[kBlock / kWave];
+    __shared__ long long s_cnt[kBlock / kWave];
+    double sum = 0.0;
+    long long cnt = 0;
+    const long long stride = (long long)gridDim.x * kBlock;
+    for (long long i = (long long)blockIdx.x * kBlock + threadIdx.x; i < count; i += stride) {
+        const float a = fabsf(W[i]);
+        if (!(a > delta)) {
+            sum += (double)a;
+            ++cnt;
+        }
+    }
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        sum += __shfl_down(sum, off, kWave);
+        cnt += __shfl_down(cnt, off, kWave);
+    }
+    if (lane_id() == 0) {
+        s_sum[threadIdx.x / kWave] = sum;
+        s_cnt[threadIdx.x / kWave] = cnt;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+        long long c = 0;
+        for (int w = 0; w < kBlock / kWave; ++w) {
+            t += s_sum[w];
+            c += s_cnt[w];
+        }
+        part_sum[blockIdx.x] = t;
+        part_cnt[blockIdx.x] = c;
+    }
+}
+
+// One block per weight row: ballot-pack the sign bits (bit 1 <-> w >= 0), count the residuals
+// and sum the signs.  A wave's 64-bit ballot is exactly two output words.
+__global__ __launch_bounds__(kBlock) void k_sign_pack_count(const float* __restrict__ W, int K, int Kw,
+                                                            float delta, uint32_t* __restrict__ sign,
+                                                            int32_t* __restrict__ counts,
+                                                            int32_t* __restrict__ rowsum) {
+    __shared__ int s_out[kBlock / kWave];
+    __shared__ int s_pos[kBlock / kWave];
+    const int n = blockIdx.x;
+    const float* row = W + (size_t)n * K;
+    uint32_t* srow = sign + (size_t)n * Kw;
+    const int wave = threadIdx.x / kWave;
+    int n_out = 0, n_pos = 0;
+    for (int c0 = 0; c0 < K; c0 += kBlock) {
+        const int k = c0 + threadIdx.x;
+        const bool in = k < K;
+        const float w = in ? row[k] : -1.0f;
+        const unsigned long long pos = __ballot(in && w >= 0.0f);
+        const unsigned long long out = __ballot(in && fabsf(w) > delta);
+        n_pos += __popcll(pos);
+        n_out += __popcll(out);
+        if (lane_id() == 0) {
+            const int j = (c0 + wave * kWave) / 32;
+            if (j < Kw) srow[j] = (uint32_t)pos;
+            if (j + 1 < Kw) srow[j + 1] = (uint32_t)(pos >> 32);
+        }
+    }
+    if (lane_id() == 0) {
+        s_out[wave] = n_out;
+        s_pos[wave] = n_pos;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int o = 0, p = 0;
+        for (int w = 0; w < kBlock / kWave; ++w) {
+            o += s_out[w];
+            p += s_pos[w];
+        }
+        counts[n] = o;
+        rowsum[n] = 2 * p - K;
+    }
+}
+
+// One wave per row: residuals in ascending column order via ballot + lane prefix count.
+__global__ __launch_bounds__(kBlock) void k_scatter_csr(const float* __restrict__ W, int N, int K, float delta,
+                                                        float alpha, const int32_t* __restrict__ row_ptr,
+                                                        int32_t* __restrict__ col_idx, float* __restrict__ val) {
+    const int n = blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+    if (n >= N) return;
+    const float* row = W + (size_t)n * K;
+    const int lane = lane_id();
+    int base = row_ptr[n];
+    for (int c0 = 0; c0 < K; c0 += kWave) {
+        const int k = c0 + lane;
+        const bool in = k < K;
+        const float w = in ? row[k] : 0.0f;
+        const bool out = in && fabsf(w) > delta;
+        const unsigned long long mask = __ballot(out);
+        if (out) {
+            const int before = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                         __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+            const float signed_alpha = (w >= 0.0f) ? alpha : -alpha;
+            col_idx[base + before] = k;
+            val[base + before] = w - signed_alpha;          // one float subtraction (Eq. 12)
+        }
+        base += __popcll(mask);
+    }
+}
+
+// signT[j][i] = word j of the row served by launch slot i (0 for padding slots).
+__global__ __launch_bounds__(kBlock) void k_slot_major_signs(const uint32_t* __restrict__ sign,
+                                                             const int32_t* __restrict__ perm, int Np, int Kw,
+                                                             uint32_t* __restrict__ signT) {
+    const long long t = (long long)blockIdx.x * kBlock + threadIdx.x;
+    if (t >= (long long)Np * Kw) return;
+    const int j = (int)(t / Np), i = (int)(t % Np);
+    const int n = perm[i];
+    signT[t] = n >= 0 ? sign[(size_t)n * Kw + j] : 0u;
+}
+
+}  // namespace
+
+int launch_inlier_abs_sum(const float* W, long long count, float delta, double* part_sum, long long* part_cnt,
+                          int parts, hipStream_t s) {
+    hipLaunchKernelGGL(k_inlier_abs_sum, dim3(parts), dim3(kBlock), 0, s, W, count, delta, part_sum, part_cnt);
+    APB_HIP(hipGetLastError());
+    return APB_OK;
+}
+
+int launch_sign_pack_count(const float* W, int N, int K, int Kw, float delta, uint32_t* sign, int32_t* counts,
+                           int32_t* rowsum, hipStream_t s) {
+    hipLaunchKernelGGL(k_sign_pack_count, dim3(N), dim3(kBlock), 0, s, W, K, Kw, delta, sign, counts, rowsum);
+    APB_HIP(hipGetLastError());
+    return APB_OK;
+}
+
+int launch_scatter_csr(const float* W, int N, int K, float delta, float alpha, const int32_t* row_ptr,
+                       int32_t* col_idx, float* val, hipStream_t s) {
+    const int rows_per_block = kBlock / kWave;
+    hipLaunchKernelGGL(k_scatter_csr, dim3((N + rows_per_block - 1) / rows_per_block), dim3(kBlock), 0, s, W, N,
+                       K, delta, alpha, row_ptr, col_idx, val);
+    APB_HIP(hipGetLastError());
+    return APB_OK;
+}
+
+int launch_slot_major_signs(const uint32_t* sign, const int32_t* perm, int Np, int Kw, uint32_t* signT,
+                            hipStream_t s) {
+    const long long total = (long long)Np * Kw;
+    hipLaunchKernelGGL(k_slot_major_signs, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
+                       sign, perm, Np, Kw, signT);
+    APB_HIP(hipGetLastError());
+    return APB_OK;
+}
+
+}  // namespace apb

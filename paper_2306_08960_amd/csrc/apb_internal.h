@@ -1,0 +1,63 @@
+// Internal declarations shared by the host entry points and the gfx950 kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "apb.h"
+
+namespace apb {
+
+constexpr int kWave = 64;        // CDNA wavefront width
+constexpr int kRowTile = 32;     // weight rows one wave keeps in registers in the popcount GEMM
+
+struct LayerDev {
+    int N = 0, K = 0, Kw = 0;    // Kw = ceil(K/32)
+    int Np = 0;                  // launch slots: N rounded up to a multiple of kRowTile
+    long long nnz = 0;
+    float alpha = 0.f;
+    uint32_t* sign = nullptr;    // [N][Kw]   canonical sign words
+    uint32_t* signT = nullptr;   // [Kw][Np]  sign words, slot-major: word j of launch slot i
+    int32_t* perm = nullptr;     // [Np]      row index served by launch slot i, -1 for padding
+    int32_t* row_ptr = nullptr;  // [N+1]
+    int32_t* col_idx = nullptr;  // [nnz]
+    float* val = nullptr;        // [nnz]
+    int32_t* rowsum = nullptr;   // [N]
+};
+
+void set_last_hip_error(hipError_t e);
+
+#define APB_HIP(expr)                                 \
+    do {                                              \
+        hipError_t e_ = (expr);                       \
+        if (e_ != hipSuccess) {                       \
+            ::apb::set_last_hip_error(e_);            \
+            return APB_ERR_HIP;                       \
+        }                                             \
+    } while (0)
+
+// ---- kernel launchers (each returns an apb_status) ------------------------------------------
+
+// compress
+int launch_inlier_abs_sum(const float* W, long long count, float delta, double* part_sum, long long* part_cnt,
+                          int parts, hipStream_t s);
+int launch_sign_pack_count(const float* W, int N, int K, int Kw, float delta, uint32_t* sign, int32_t* counts,
+                           int32_t* rowsum, hipStream_t s);
+int launch_scatter_csr(const float* W, int N, int K, float delta, float alpha, const int32_t* row_ptr,
+                       int32_t* col_idx, float* val, hipStream_t s);
+int launch_slot_major_signs(const uint32_t* sign, const int32_t* perm, int Np, int Kw, uint32_t* signT,
+                            hipStream_t s);
+
+// activations
+int launch_quantize(const float* X, int K, int M, int bits, float inv_step, uint32_t* planes, int32_t* colsum,
+                    hipStream_t s);
+
+// forward
+int launch_forward(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
+                   float* Y, int32_t* D, hipStream_t s);
+
+}  // namespace apb
+
+struct apb_layer {
+    apb::LayerDev d;
+};
