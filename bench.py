@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark of the APB layer forward pass on one MI355X.
+
+One "step" = the whole per-batch hot path on inputs already resident in HBM:
+apb_quantize_acts (quantize + bit-plane packing) followed by apb_forward (popcount GEMM +
+CSR part + epilogue).  apb_compress is per-layer offline work and is not timed.
+
+Prints ONE JSON line.  `value` is (2*N*K*M + 2*nnz*M) / step time, in GOPS, for the workload
+named in config.workload; `roofline` describes the kernel that dominates the step and
+`roofline_forward` the forward kernel; `cpu_baseline` is the CPU oracle timed on a bounded
+column sample of the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0                  # MI355X HBM3E, published
+CUS, CLOCK_GHZ, LANES_PER_CU_CLK = 256, 2.4, 64
+VALU_LANE_OPS_PER_S = CUS * LANES_PER_CU_CLK * CLOCK_GHZ * 1e9     # 39.3e12 32-bit lane-ops/s
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="C2", help="name in paper_2306_08960_amd.synth.CONFIGS")
+    ap.add_argument("--all", action="store_true", help="also time every other benchmark layer (reported in 'others')")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def time_events(fn, iters):
+    import torch
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(iters):
+        fn()
+    stop.record()
+    stop.synchronize()
+    return start.elapsed_time(stop) / iters          # ms per launch, on the stream the kernels run on
+
+
+def forward_lane_ops(N, K, M, bits, nnz):
+    """Algorithmic 32-bit VALU lane-ops of the forward kernel: per weight word, plane and column one
+    logic op + one popcount-accumulate; per residual and column one fused multiply-add."""
+    Kw = (K + 31) // 32
+    return 2.0 * bits * N * Kw * M + float(nnz) * M
+
+
+def run_workload(name, steps, warmup):
+    import torch
+    from paper_2306_08960_amd import binding as b
+    from paper_2306_08960_amd import synth
+
+    cfg = synth.CONFIGS[name]
+    W, delta, X, step = synth.make_layer(cfg)
+    N, K, M, bits = cfg.N, cfg.K, cfg.M, cfg.bits
+    Wd = torch.from_numpy(W).cuda()
+    Xd = torch.from_numpy(X).cuda()
+    layer = b.apb_compress(Wd, float(delta))
+    nnz = layer.info()["nnz"]
+    packed = b.alloc_packed(K, M, bits)
+    Y = torch.empty((N, M), dtype=torch.float32, device="cuda")
+    s = float(step)
+
+    def quant():
+        b.apb_quantize_acts(Xd, bits, s, packed=packed)
+
+    def fwd():
+        b.apb_forward(layer, packed, M, bits, s, Y=Y)
+
+    def one_step():
+        quant()
+        fwd()
+
+    for _ in range(warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        one_step()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / steps
+
+    ms_quant = time_events(quant, steps)
+    ms_fwd = time_events(fwd, steps)
+
+    ops = 2.0 * N * K * M + 2.0 * nnz * M
+    Kw, Mp = (K + 31) // 32, 64 * ((M + 63) // 64)
+    quant_bytes = 4.0 * K * M + 4.0 * bits * Kw * Mp + 4.0 * Mp
+    fwd_bytes = 4.0 * N * Kw + 4.0 * bits * Kw * Mp + 4.0 * Mp + 8.0 * nnz + 4.0 * (N + 1) + 4.0 * N * M
+    lane_ops = forward_lane_ops(N, K, M, bits, nnz)
+    fwd_peak_tops = ops / (lane_ops / VALU_LANE_OPS_PER_S) / 1e12
+    roof_quant = {"kernel": "k_quantize_pack", "bound": "hbm", "achieved": quant_bytes / (ms_quant * 1e-3) / 1e9,
+                  "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": None, "ms": ms_quant}
+    roof_quant["frac"] = roof_quant["achieved"] / roof_quant["peak"]
+    roof_fwd = {"kernel": "k_forward_valu", "bound": "alu", "achieved": ops / (ms_fwd * 1e-3) / 1e12,
+                "peak": fwd_peak_tops, "unit": "TOP/s", "traffic": None, "ms": ms_fwd,
+                "hbm_frac": fwd_bytes / (ms_fwd * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    roof_fwd["frac"] = roof_fwd["achieved"] / roof_fwd["peak"]
+    res = {
+        "workload": name, "N": N, "K": K, "M": M, "act_bits": bits, "nnz": int(nnz),
+        "ms_per_step": ms_step, "gops_step": ops / (ms_step * 1e-3) / 1e9,
+        "ms_quantize": ms_quant, "ms_forward": ms_fwd, "gops_forward": ops / (ms_fwd * 1e-3) / 1e9,
+        "roofline": roof_quant if ms_quant >= ms_fwd else roof_fwd, "roofline_forward": roof_fwd,
+        "roofline_quantize": roof_quant,
+    }
+    layer.free()
+    del Wd, Xd, packed, Y
+    torch.cuda.empty_cache()
+    return res, (cfg, W, delta, X, step)
+
+
+def cpu_baseline(cfg, W, delta, X, step):
+    """The CPU oracle (quantize, pack, popcount integer part, CSR part, epilogue) on the first
+    columns of the same workload, all host cores this process may use."""
+    from oracle import apb_oracle as o
+    from oracle import capi
+    cores = max(1, min(len(os.sched_getaffinity(0)), capi.max_threads()))
+    L = o.compress(W, delta)
+    nnz = int(L["row_ptr"][-1])
+    per_col = 2.0 * cfg.N * cfg.K + 2.0 * nnz
+    target_ops = 60e9 * cores ** 0.5                 # sized for roughly 10-30 s of CPU work
+    m = int(max(64, min(cfg.M, target_ops / per_col)))
+    Xs = np.ascontiguousarray(X[:, :m])
+    t0 = time.perf_counter()
+    c = o.quantize(Xs, cfg.bits, step)
+    packed = o.pack_acts(c, cfg.bits)
+    capi.forward(L, packed, c, cfg.bits, step, threads=cores)
+    dt = time.perf_counter() - t0
+    return {"value": per_col * m / dt / 1e9, "unit": "GOPS", "cores": cores, "kind": "oracle",
+            "sample": f"first {m} of {cfg.M} columns of {cfg.name}, one pass (quantize+pack+forward), {dt:.2f} s"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path shards over M with no exchange; "
+              "see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2306_08960_amd import binding as b
+    from paper_2306_08960_amd import synth
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    b.load()
+    if args.workload not in synth.CONFIGS:
+        print(f"bench.py: unknown workload {args.workload}; choose from {sorted(synth.CONFIGS)}", file=sys.stderr)
+        sys.exit(2)
+
+    res, inputs = run_workload(args.workload, args.steps, args.warmup)
+    cfg = inputs[0]
+    out = {
+        "metric": "APB layer forward GOPS (binary+sparse) and % of MI355X roofline",
+        "value": res["gops_step"], "unit": "GOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32 popcount + f64 accumulate (f32 in/out)", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.note}", "N": cfg.N, "K": cfg.K, "M": cfg.M,
+                   "act_bits": cfg.bits, "outlier_rate": cfg.rho, "nnz": res["nnz"],
+                   "step": "apb_quantize_acts + apb_forward, inputs resident in HBM"},
+        "ms_quantize": res["ms_quantize"], "ms_forward": res["ms_forward"],
+        "gops_forward_only": res["gops_forward"],
+        "roofline": res["roofline"], "roofline_forward": res["roofline_forward"],
+        "roofline_quantize": res["roofline_quantize"],
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(*inputs)
+    del inputs
+    if args.all:
+        others = []
+        for name in synth.CONFIGS:
+            if name == args.workload:
+                continue
+            r, _ = run_workload(name, max(20, args.steps // 4), max(5, args.warmup // 4))
+            others.append({k: r[k] for k in ("workload", "N", "K", "M", "act_bits", "nnz", "ms_per_step", "gops_step",
+                                             "ms_quantize", "ms_forward", "gops_forward")}
+                          | {"forward_frac_of_valu_roof": r["roofline_forward"]["frac"],
+                             "quantize_frac_of_hbm_roof": r["roofline_quantize"]["frac"]})
+        out["others"] = others
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
