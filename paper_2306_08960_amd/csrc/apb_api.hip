@@ -18,7 +18,7 @@ namespace {
 hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 void free_layer_buffers(LayerDev& d) {
-    void* ptrs[] = {d.sign, d.signT, d.perm, d.row_ptr, d.col_idx, d.val, d.rowsum};
+    void* ptrs[] = {d.sign, d.signT, d.perm, d.row_ptr, d.col_idx, d.val, d.rowsum, d.chunk_ptr, d.slot_valsum, d.vald};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     d = LayerDev{};
@@ -60,7 +60,11 @@ int compress_impl(const float* W, int N, int K, float delta, float alpha, hipStr
     d.N = N;
     d.K = K;
     d.Kw = (K + 31) / 32;
-    d.Np = kRowTile * ((N + kRowTile - 1) / kRowTile);
+    d.waves = 1;                                       // workgroup = up to 8 waves of kRowTile rows each
+    while (d.waves < kMaxWavesPerBlock && d.waves * kRowTile < N) d.waves *= 2;
+    const int rows_per_block = kRowTile * d.waves;
+    d.Np = rows_per_block * ((N + rows_per_block - 1) / rows_per_block);
+    d.nchunks = (d.Kw + kChunkWords - 1) / kChunkWords;
     int rc;
 
     if (std::isnan(alpha)) {                          // default scale: mean |w| over the binarized set
@@ -100,6 +104,8 @@ int compress_impl(const float* W, int N, int K, float delta, float alpha, hipStr
     if ((rc = dev_alloc(&d.row_ptr, (size_t)N + 1)) != APB_OK) return rc;
     if ((rc = dev_alloc(&d.perm, (size_t)d.Np)) != APB_OK) return rc;
     if ((rc = dev_alloc(&d.signT, (size_t)d.Np * d.Kw)) != APB_OK) return rc;
+    if ((rc = dev_alloc(&d.chunk_ptr, (size_t)d.Np * (d.nchunks + 1))) != APB_OK) return rc;
+    if ((rc = dev_alloc(&d.slot_valsum, (size_t)d.Np)) != APB_OK) return rc;
     if ((rc = dev_alloc(&counts, (size_t)N)) != APB_OK) return rc;
 
     std::vector<int32_t> hcounts(N);
@@ -122,10 +128,14 @@ int compress_impl(const float* W, int N, int K, float delta, float alpha, hipStr
 
     if ((rc = dev_alloc(&d.col_idx, (size_t)nnz)) != APB_OK) return rc;
     if ((rc = dev_alloc(&d.val, (size_t)nnz)) != APB_OK) return rc;
+    if ((rc = dev_alloc(&d.vald, (size_t)nnz)) != APB_OK) return rc;
     APB_HIP(hipMemcpyAsync(d.row_ptr, hrow_ptr.data(), ((size_t)N + 1) * sizeof(int32_t), hipMemcpyHostToDevice, s));
     APB_HIP(hipMemcpyAsync(d.perm, hperm.data(), (size_t)d.Np * sizeof(int32_t), hipMemcpyHostToDevice, s));
-    if (nnz > 0 && (rc = launch_scatter_csr(W, N, K, delta, alpha, d.row_ptr, d.col_idx, d.val, s)) != APB_OK) return rc;
+    if (nnz > 0 && (rc = launch_scatter_csr(W, N, K, delta, alpha, d.row_ptr, d.col_idx, d.val, d.vald, s)) != APB_OK) return rc;
     if ((rc = launch_slot_major_signs(d.sign, d.perm, d.Np, d.Kw, d.signT, s)) != APB_OK) return rc;
+    if ((rc = launch_slot_tables(d.perm, d.row_ptr, d.col_idx, d.val, d.Np, d.nchunks, d.chunk_ptr, d.slot_valsum,
+                                 s)) != APB_OK)
+        return rc;
     APB_HIP(hipStreamSynchronize(s));                 // host staging vectors go out of scope after this
     return APB_OK;
 }

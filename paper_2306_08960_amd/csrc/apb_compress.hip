@@ -93,7 +93,8 @@ __global__ __launch_bounds__(kBlock) void k_sign_pack_count(const float* __restr
 // One wave per row: residuals in ascending column order via ballot + lane prefix count.
 __global__ __launch_bounds__(kBlock) void k_scatter_csr(const float* __restrict__ W, int N, int K, float delta,
                                                         float alpha, const int32_t* __restrict__ row_ptr,
-                                                        int32_t* __restrict__ col_idx, float* __restrict__ val) {
+                                                        int32_t* __restrict__ col_idx, float* __restrict__ val,
+                                                        double* __restrict__ vald) {
     const int n = blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
     if (n >= N) return;
     const float* row = W + (size_t)n * K;
@@ -110,7 +111,9 @@ __global__ __launch_bounds__(kBlock) void k_scatter_csr(const float* __restrict_
                                                          __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
             const float signed_alpha = (w >= 0.0f) ? alpha : -alpha;
             col_idx[base + before] = k;
-            val[base + before] = w - signed_alpha;          // one float subtraction (Eq. 12)
+            const float residual = w - signed_alpha;        // one float subtraction (Eq. 12)
+            val[base + before] = residual;
+            vald[base + before] = (double)residual;
         }
         base += __popcll(mask);
     }
@@ -127,7 +130,47 @@ __global__ __launch_bounds__(kBlock) void k_slot_major_signs(const uint32_t* __r
     signT[t] = n >= 0 ? sign[(size_t)n * Kw + j] : 0u;
 }
 
+// chunk_ptr[c][i]: index of the first residual of the row in slot i whose column is >= 256*c
+// (lower bound in the ascending column list); slot_valsum[i]: float64 sum of that row's residuals.
+__global__ __launch_bounds__(kBlock) void k_slot_tables(const int32_t* __restrict__ perm,
+                                                        const int32_t* __restrict__ row_ptr,
+                                                        const int32_t* __restrict__ col_idx,
+                                                        const float* __restrict__ val, int Np, int nchunks,
+                                                        int32_t* __restrict__ chunk_ptr,
+                                                        double* __restrict__ slot_valsum) {
+    const long long t = (long long)blockIdx.x * kBlock + threadIdx.x;
+    if (t >= (long long)Np * (nchunks + 1)) return;
+    const int c = (int)(t / Np), i = (int)(t % Np);
+    const int n = perm[i];
+    if (n < 0) {
+        chunk_ptr[t] = 0;
+        if (c == 0) slot_valsum[i] = 0.0;
+        return;
+    }
+    int lo = row_ptr[n], hi = row_ptr[n + 1];
+    if (c == 0) {
+        double sum = 0.0;
+        for (int q = lo; q < hi; ++q) sum += (double)val[q];
+        slot_valsum[i] = sum;
+    }
+    const int bound = c * kChunkK;
+    while (lo < hi) {
+        const int mid = lo + (hi - lo) / 2;
+        if (col_idx[mid] < bound) lo = mid + 1; else hi = mid;
+    }
+    chunk_ptr[t] = lo;
+}
+
 }  // namespace
+
+int launch_slot_tables(const int32_t* perm, const int32_t* row_ptr, const int32_t* col_idx, const float* val, int Np,
+                       int nchunks, int32_t* chunk_ptr, double* slot_valsum, hipStream_t s) {
+    const long long total = (long long)Np * (nchunks + 1);
+    hipLaunchKernelGGL(k_slot_tables, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, perm,
+                       row_ptr, col_idx, val, Np, nchunks, chunk_ptr, slot_valsum);
+    APB_HIP(hipGetLastError());
+    return APB_OK;
+}
 
 int launch_inlier_abs_sum(const float* W, long long count, float delta, double* part_sum, long long* part_cnt,
                           int parts, hipStream_t s) {
@@ -144,10 +187,10 @@ int launch_sign_pack_count(const float* W, int N, int K, int Kw, float delta, ui
 }
 
 int launch_scatter_csr(const float* W, int N, int K, float delta, float alpha, const int32_t* row_ptr,
-                       int32_t* col_idx, float* val, hipStream_t s) {
+                       int32_t* col_idx, float* val, double* vald, hipStream_t s) {
     const int rows_per_block = kBlock / kWave;
     hipLaunchKernelGGL(k_scatter_csr, dim3((N + rows_per_block - 1) / rows_per_block), dim3(kBlock), 0, s, W, N,
-                       K, delta, alpha, row_ptr, col_idx, val);
+                       K, delta, alpha, row_ptr, col_idx, val, vald);
     APB_HIP(hipGetLastError());
     return APB_OK;
 }

@@ -1,4 +1,4 @@
-// apb_forward: Y = alpha*s*D + s * sum_j val_j * c[col_j, :]   (Sec. III Eq. 13)
+// apb_forward: Y = s * (alpha*D + sum_j val_j * c[col_j, :])   (Sec. III Eq. 13, one fused kernel)
 //
 // Integer part D (Sec. IV Eq. 16 for 1-bit activations; for 2-bit ones the two stored bit-planes
 // P0, P1 of the level index p stand in for the paper's (t, h, m) vectors of Eqs. 18-19:
@@ -6,86 +6,178 @@
 //
 // Mapping: lanes run along m (one output column per lane), so a wave's activation word load is one
 // contiguous 256-byte segment of a plane row, and the weight words of the kRowTile rows a wave owns
-// are wave-uniform -> they travel through the scalar path and feed v_and/v_xor as SGPR operands.
-// Per 32 binary multiply-adds the inner loop issues one logic op and one v_bcnt_u32_b32 (popcount
-// with accumulate), the CDNA counterpart of the paper's xor/popcount/add port analysis.
+// are wave-uniform: they travel through the scalar path and feed v_and/v_xor as SGPR operands.  Per
+// 32 binary multiply-adds the inner loop issues one logic op and one v_bcnt_u32_b32 (popcount with
+// accumulate), the CDNA counterpart of the paper's xor/popcount/add port analysis.
+//
+// Sparse part: a workgroup (up to 8 waves = 128 weight rows, one 64-column strip) walks K in chunks
+// of 256.  While a wave has the chunk's plane words in registers for the popcounts, it also expands
+// them into a byte-per-activation code table in LDS (row = output column, 256 codes + pad; the
+// 260-byte row pitch keeps the 64 lanes of a wave on distinct banks).  After a barrier every wave
+// adds the residuals of its rows whose column falls in the chunk: one ds_read_u8, one convert and
+// one float64 fused multiply-add per residual and lane; residual column/value pairs are wave-uniform
+// scalar loads, found through per-(row, chunk) offsets prepared at compress time.
 #include "apb_internal.h"
 
 namespace apb {
 
 namespace {
 
-constexpr int kBlock = 256;
-constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int TN = kRowTile;
+constexpr int kTablePitch = kChunkK + 4;                       // bytes per column row of the code table
+constexpr int kTableBytes = kWave * kTablePitch;               // one buffer; two are used alternately
+
+struct FwdParams {
+    const uint32_t* __restrict__ signT;
+    const uint32_t* __restrict__ planes;
+    const int32_t* __restrict__ colsum;
+    const int32_t* __restrict__ perm;
+    const int32_t* __restrict__ chunk_ptr;
+    const int32_t* __restrict__ col_idx;
+    const double* __restrict__ vald;
+    const double* __restrict__ slot_valsum;
+    float* __restrict__ Y;
+    int32_t* __restrict__ D;
+    double alpha, step;
+    int Np, Kw, K, Mp, M, nchunks;
+    int row_groups;              // Np / (TN * waves)
+    int blocks;                  // row_groups * strips
+};
+
+// Spread the 4 low bits of `nib` to the least significant bits of the 4 bytes of a word.
+__device__ __forceinline__ uint32_t spread4(uint32_t nib) { return (nib * 0x00204081u) & 0x01010101u; }
 
 template <int BITS, bool INT_ONLY>
-__global__ __launch_bounds__(kBlock) void k_forward_valu(
-    const uint32_t* __restrict__ signT, int Np, int Kw, int K, const uint32_t* __restrict__ planes,
-    const int32_t* __restrict__ colsum, int Mp, int M, const int32_t* __restrict__ perm,
-    const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx, const float* __restrict__ val,
-    double alpha, double step, int row_tiles, long long tasks, float* __restrict__ Y, int32_t* __restrict__ D) {
-    constexpr int TN = kRowTile;
+__global__ __launch_bounds__(kWave* kMaxWavesPerBlock) void k_forward_fused(const FwdParams p) {
+    extern __shared__ __align__(16) uint8_t lds[];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const long long task = (long long)blockIdx.x * kWavesPerBlock + wave;
-    if (task >= tasks) return;
-    const int tile = (int)(task % row_tiles);                  // waves of a block share the column strip
-    const int strip = (int)(task / row_tiles);
-    const int slot0 = tile * TN;
+    const int waves = blockDim.x / kWave;
+
+    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of tasks so
+    // that the row groups sharing one activation strip also share one L2.
+    int task = blockIdx.x;
+    if ((p.blocks & 7) == 0) task = (blockIdx.x & 7) * (p.blocks >> 3) + (blockIdx.x >> 3);
+    const int rg = task % p.row_groups;
+    const int strip = task / p.row_groups;
+    const int slot0 = (rg * waves + wave) * TN;
     const int m = strip * kWave + lane;
 
     int acc[BITS][TN];
-#pragma unroll
-    for (int b = 0; b < BITS; ++b)
-#pragma unroll
-        for (int r = 0; r < TN; ++r) acc[b][r] = 0;
-
-    const uint32_t* wp = signT + slot0;
-    const uint32_t* xp = planes + m;
-    const size_t plane_stride = (size_t)Kw * Mp;
-    for (int j = 0; j < Kw; ++j) {
-        const uint32_t x0 = xp[(size_t)j * Mp];
-        const uint32_t x1 = BITS == 2 ? xp[plane_stride + (size_t)j * Mp] : 0u;
-        const uint32_t* w = wp + (size_t)j * Np;
-#pragma unroll
-        for (int r = 0; r < TN; ++r) {
-            const uint32_t wr = w[r];
-            if (BITS == 1) {
-                acc[0][r] += __builtin_popcount(wr ^ x0);
-            } else {
-                acc[0][r] += __builtin_popcount(wr & x0);
-                acc[1][r] += __builtin_popcount(wr & x1);
-            }
-        }
-    }
-
-    const int cs = BITS == 2 ? colsum[m] : 0;
-    const bool col_ok = m < M;
+    double accd[TN];
 #pragma unroll
     for (int r = 0; r < TN; ++r) {
-        const int n = perm[slot0 + r];
+        acc[0][r] = 0;
+        acc[BITS - 1][r] = 0;
+        accd[r] = 0.0;
+    }
+
+    const uint32_t* wp = p.signT + slot0;
+    const uint32_t* xp = p.planes + m;
+    const size_t plane_stride = (size_t)p.Kw * p.Mp;
+    uint8_t* my_row = lds + lane * kTablePitch;
+
+    // Activation words of one whole chunk live in registers and are fetched one chunk ahead; the
+    // weight words (scalar loads) are fetched one word ahead.
+    uint32_t xcur[BITS][kChunkWords], xnext[BITS][kChunkWords];
+#pragma unroll
+    for (int jj = 0; jj < kChunkWords; ++jj)
+#pragma unroll
+        for (int b = 0; b < BITS; ++b)
+            xnext[b][jj] = jj < p.Kw ? xp[b * plane_stride + (size_t)jj * p.Mp] : 0u;
+    uint32_t wnext[TN];
+#pragma unroll
+    for (int r = 0; r < TN; ++r) wnext[r] = wp[r];
+
+    for (int c = 0; c < p.nchunks; ++c) {
+        const int j0 = c * kChunkWords;
+        uint8_t* table_row = my_row + (c & 1) * kTableBytes;
+#pragma unroll
+        for (int jj = 0; jj < kChunkWords; ++jj)
+#pragma unroll
+            for (int b = 0; b < BITS; ++b) {
+                xcur[b][jj] = xnext[b][jj];
+                const int jn = j0 + kChunkWords + jj;               // words past the end read as zero
+                xnext[b][jj] = jn < p.Kw ? xp[b * plane_stride + (size_t)jn * p.Mp] : 0u;
+            }
+#pragma unroll
+        for (int jj = 0; jj < kChunkWords; ++jj) {
+            const int j = j0 + jj;
+            if (j >= p.Kw) break;
+            uint32_t wcur[TN];
+#pragma unroll
+            for (int r = 0; r < TN; ++r) wcur[r] = wnext[r];
+            if (j + 1 < p.Kw) {
+                const uint32_t* w = wp + (size_t)(j + 1) * p.Np;
+#pragma unroll
+                for (int r = 0; r < TN; ++r) wnext[r] = w[r];
+            }
+            const uint32_t x0 = xcur[0][jj];
+            const uint32_t x1 = xcur[BITS - 1][jj];
+#pragma unroll
+            for (int r = 0; r < TN; ++r) {
+                if (BITS == 1) {
+                    acc[0][r] += __builtin_popcount(wcur[r] ^ x0);
+                } else {
+                    acc[0][r] += __builtin_popcount(wcur[r] & x0);
+                    acc[1][r] += __builtin_popcount(wcur[r] & x1);
+                }
+            }
+            if (!INT_ONLY && (jj % waves) == wave) {           // this wave expands word jj of the chunk
+                uint32_t* dst = reinterpret_cast<uint32_t*>(table_row + 32 * jj);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    uint32_t t = spread4((x0 >> (4 * i)) & 0xFu);
+                    if (BITS == 2) t |= spread4((x1 >> (4 * i)) & 0xFu) << 1;
+                    dst[i] = t;                                 // bytes: codes of k = 32*j + 4*i + 0..3
+                }
+            }
+        }
+        if (INT_ONLY) continue;
+        __syncthreads();                                        // the chunk's code table is complete
+        const int kbase = c * kChunkK;
+        const int32_t* cur_ptr = p.chunk_ptr + (size_t)c * p.Np + slot0;
+        const int32_t* next_ptr = cur_ptr + p.Np;
+#pragma unroll
+        for (int r = 0; r < TN; ++r) {
+            int q = cur_ptr[r];
+            const int q1 = next_ptr[r];
+            double a = accd[r];
+            for (; q + 4 <= q1; q += 4) {
+                const int c0 = p.col_idx[q] - kbase, c1 = p.col_idx[q + 1] - kbase;
+                const int c2 = p.col_idx[q + 2] - kbase, c3 = p.col_idx[q + 3] - kbase;
+                const double v0 = p.vald[q], v1 = p.vald[q + 1], v2 = p.vald[q + 2], v3 = p.vald[q + 3];
+                const uint32_t e0 = table_row[c0], e1 = table_row[c1], e2 = table_row[c2], e3 = table_row[c3];
+                a = fma(v0, (double)e0, a);
+                a = fma(v1, (double)e1, a);
+                a = fma(v2, (double)e2, a);
+                a = fma(v3, (double)e3, a);
+            }
+            for (; q < q1; ++q) {
+                const uint32_t e = table_row[p.col_idx[q] - kbase];
+                a = fma(p.vald[q], (double)e, a);
+            }
+            accd[r] = a;
+        }
+        // The next chunk writes the other buffer; this one is rewritten two chunks from now, after
+        // every wave has passed the next barrier, i.e. has finished reading it.
+    }
+
+    const int cs = BITS == 2 ? p.colsum[m] : 0;
+    const bool col_ok = m < p.M;
+#pragma unroll
+    for (int r = 0; r < TN; ++r) {
+        const int n = p.perm[slot0 + r];
         if (n < 0) continue;
-        const int d = BITS == 1 ? K - 2 * acc[0][r] : 2 * (acc[0][r] + 2 * acc[BITS - 1][r]) - cs;
+        const int d = BITS == 1 ? p.K - 2 * acc[0][r] : 2 * (acc[0][r] + 2 * acc[BITS - 1][r]) - cs;
         if (INT_ONLY) {
-            if (col_ok) D[(size_t)n * M + m] = d;
+            if (col_ok) p.D[(size_t)n * p.M + m] = d;
             continue;
         }
-        double a = alpha * (double)d;
-        const int q1 = row_ptr[n + 1];
-        for (int q = row_ptr[n]; q < q1; ++q) {
-            const int c = col_idx[q];
-            const double v = (double)val[q];
-            const size_t off = (size_t)(c >> 5) * Mp;
-            const int bit = c & 31;
-            int code;
-            if (BITS == 1) {
-                code = 2 * (int)((xp[off] >> bit) & 1u) - 1;
-            } else {
-                code = (int)((xp[off] >> bit) & 1u) + 2 * (int)((xp[plane_stride + off] >> bit) & 1u);
-            }
-            a = fma(v, (double)code, a);
-        }
-        if (col_ok) Y[(size_t)n * M + m] = (float)(a * step);
+        // 1-bit activations: the table holds (c+1)/2 in {0,1}, so sum val*c = 2*sum val*code - sum val.
+        const double sparse = BITS == 1 ? 2.0 * accd[r] - p.slot_valsum[slot0 + r] : accd[r];
+        const double y = fma(p.alpha, (double)d, sparse) * p.step;
+        if (col_ok) p.Y[(size_t)n * p.M + m] = (float)y;
     }
 }
 
@@ -94,15 +186,32 @@ __global__ __launch_bounds__(kBlock) void k_forward_valu(
 int launch_forward(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                    float* Y, int32_t* D, hipStream_t s) {
     const int Mp = kWave * ((M + kWave - 1) / kWave);
-    const int row_tiles = L.Np / kRowTile;
-    const long long tasks = (long long)row_tiles * (Mp / kWave);
-    const long long blocks = (tasks + kWavesPerBlock - 1) / kWavesPerBlock;
+    FwdParams p;
+    p.signT = L.signT;
+    p.planes = planes;
+    p.colsum = colsum;
+    p.perm = L.perm;
+    p.chunk_ptr = L.chunk_ptr;
+    p.col_idx = L.col_idx;
+    p.vald = L.vald;
+    p.slot_valsum = L.slot_valsum;
+    p.Y = Y;
+    p.D = D;
+    p.alpha = (double)L.alpha;
+    p.step = (double)step;
+    p.Np = L.Np;
+    p.Kw = L.Kw;
+    p.K = L.K;
+    p.Mp = Mp;
+    p.M = M;
+    p.nchunks = L.nchunks;
+    p.row_groups = L.Np / (TN * L.waves);
+    const long long blocks = (long long)p.row_groups * (Mp / kWave);
     if (blocks > 0x7fffffffLL) return APB_ERR_SHAPE;
-    const dim3 grid((unsigned)blocks), block(kBlock);
-    const double a = (double)L.alpha, st = (double)step;
-#define APB_FWD(B, I)                                                                                          \
-    hipLaunchKernelGGL((k_forward_valu<B, I>), grid, block, 0, s, L.signT, L.Np, L.Kw, L.K, planes, colsum, Mp, \
-                       M, L.perm, L.row_ptr, L.col_idx, L.val, a, st, row_tiles, tasks, Y, D)
+    p.blocks = (int)blocks;
+    const dim3 grid((unsigned)blocks), block(kWave * L.waves);
+    const size_t lds_bytes = D ? 0 : 2 * kTableBytes;
+#define APB_FWD(B, I) hipLaunchKernelGGL((k_forward_fused<B, I>), grid, block, lds_bytes, s, p)
     if (D != nullptr) {
         if (bits == 1) APB_FWD(1, true); else APB_FWD(2, true);
     } else {

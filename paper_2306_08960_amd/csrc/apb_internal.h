@@ -9,11 +9,16 @@
 namespace apb {
 
 constexpr int kWave = 64;        // CDNA wavefront width
-constexpr int kRowTile = 32;     // weight rows one wave keeps in registers in the popcount GEMM
+constexpr int kRowTile = 16;     // weight rows one wave keeps in registers in the popcount GEMM
+constexpr int kChunkWords = 8;   // K is walked in chunks of 8 words = 256 weights (one LDS code table each)
+constexpr int kChunkK = 32 * kChunkWords;
+constexpr int kMaxWavesPerBlock = 8;
 
 struct LayerDev {
     int N = 0, K = 0, Kw = 0;    // Kw = ceil(K/32)
-    int Np = 0;                  // launch slots: N rounded up to a multiple of kRowTile
+    int Np = 0;                  // launch slots: N rounded up to a multiple of kRowTile * waves
+    int waves = 1;               // waves per workgroup of the forward kernel (1, 2, 4 or 8)
+    int nchunks = 0;             // ceil(Kw / kChunkWords)
     long long nnz = 0;
     float alpha = 0.f;
     uint32_t* sign = nullptr;    // [N][Kw]   canonical sign words
@@ -22,7 +27,10 @@ struct LayerDev {
     int32_t* row_ptr = nullptr;  // [N+1]
     int32_t* col_idx = nullptr;  // [nnz]
     float* val = nullptr;        // [nnz]
+    double* vald = nullptr;      // [nnz]     the same residuals widened to float64 (exact), for the kernel
     int32_t* rowsum = nullptr;   // [N]
+    int32_t* chunk_ptr = nullptr;  // [nchunks+1][Np]  first residual of slot i with column >= 256*c
+    double* slot_valsum = nullptr; // [Np]             sum of the residuals of slot i (float64)
 };
 
 void set_last_hip_error(hipError_t e);
@@ -44,9 +52,11 @@ int launch_inlier_abs_sum(const float* W, long long count, float delta, double* 
 int launch_sign_pack_count(const float* W, int N, int K, int Kw, float delta, uint32_t* sign, int32_t* counts,
                            int32_t* rowsum, hipStream_t s);
 int launch_scatter_csr(const float* W, int N, int K, float delta, float alpha, const int32_t* row_ptr,
-                       int32_t* col_idx, float* val, hipStream_t s);
+                       int32_t* col_idx, float* val, double* vald, hipStream_t s);
 int launch_slot_major_signs(const uint32_t* sign, const int32_t* perm, int Np, int Kw, uint32_t* signT,
                             hipStream_t s);
+int launch_slot_tables(const int32_t* perm, const int32_t* row_ptr, const int32_t* col_idx, const float* val, int Np,
+                       int nchunks, int32_t* chunk_ptr, double* slot_valsum, hipStream_t s);
 
 // activations
 int launch_quantize(const float* X, int K, int M, int bits, float inv_step, uint32_t* planes, int32_t* colsum,
