@@ -114,8 +114,21 @@ int apb_quantize_acts(const float* X, int K, int M, int bits, float step, void* 
  * Asynchronous on `stream`. */
 int apb_forward(const apb_layer* layer, const void* packed, int M, int bits, float step, float* Y, void* stream);
 
-/* Test hook: the integer part D (N*M int32, row-major, DEVICE) alone. Asynchronous on `stream`. */
+/* Test hook: the integer part D (N*M int32, row-major, DEVICE) alone, computed by the same
+ * matrix-core kernel apb_forward uses. Asynchronous on `stream`. */
 int apb_forward_int(const apb_layer* layer, const void* packed, int M, int bits, int32_t* D, void* stream);
+
+/* The same D through the paper's own formulation: xor/and + popcount over packed words
+ * (Sec. IV Eq. 16 and Eqs. 18-19) on the vector ALU.  Kept as the measured comparison for the
+ * matrix-core kernel and as a second, independent route to D in the tests. */
+int apb_forward_int_popcount(const apb_layer* layer, const void* packed, int M, int bits, int32_t* D,
+                             void* stream);
+
+/* apb_forward with the binary part computed by the popcount formulation above, fused with the
+ * sparse part in one vector-ALU kernel.  Same arguments, same result as apb_forward; exists so
+ * that the two formulations can be timed against each other. */
+int apb_forward_popcount(const apb_layer* layer, const void* packed, int M, int bits, float step, float* Y,
+                         void* stream);
 
 const char* apb_strerror(int code);
 int apb_last_hip_error(void);

@@ -20,7 +20,8 @@ LIB_PATH = os.path.join(_HERE, "libapb.so")
 
 EXPORTS = (
     "apb_compress", "apb_layer_info", "apb_layer_export", "apb_layer_free", "apb_acts_bytes",
-    "apb_quantize_acts", "apb_forward", "apb_forward_int", "apb_strerror", "apb_last_hip_error",
+    "apb_quantize_acts", "apb_forward", "apb_forward_int", "apb_forward_int_popcount", "apb_forward_popcount", "apb_strerror",
+    "apb_last_hip_error",
 )
 
 APB_OK = 0
@@ -62,6 +63,10 @@ def load() -> ctypes.CDLL:
     lib.apb_forward.restype = ci
     lib.apb_forward_int.argtypes = [vp, vp, ci, ci, vp, vp]
     lib.apb_forward_int.restype = ci
+    lib.apb_forward_int_popcount.argtypes = [vp, vp, ci, ci, vp, vp]
+    lib.apb_forward_int_popcount.restype = ci
+    lib.apb_forward_popcount.argtypes = [vp, vp, ci, ci, cf, vp, vp]
+    lib.apb_forward_popcount.restype = ci
     lib.apb_strerror.argtypes = [ci]
     lib.apb_strerror.restype = ctypes.c_char_p
     lib.apb_last_hip_error.argtypes = []
@@ -214,3 +219,31 @@ def apb_forward_int(layer: ApbLayer, packed: torch.Tensor, M: int, bits: int,
     _check(load().apb_forward_int(layer.handle, _dev_ptr(packed, torch.int32, "packed"), int(M), int(bits),
                                   _dev_ptr(D, torch.int32, "D"), _stream(stream)), "apb_forward_int")
     return D
+
+
+def apb_forward_int_popcount(layer: ApbLayer, packed: torch.Tensor, M: int, bits: int,
+                             D: Optional[torch.Tensor] = None,
+                             stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    N, _ = _check_packed(layer, packed, M, bits)
+    if D is None:
+        D = torch.empty((N, M), dtype=torch.int32, device=packed.device)
+    elif tuple(D.shape) != (N, M):
+        raise ValueError("D must be [N, M]")
+    _check(load().apb_forward_int_popcount(layer.handle, _dev_ptr(packed, torch.int32, "packed"), int(M), int(bits),
+                                           _dev_ptr(D, torch.int32, "D"), _stream(stream)),
+           "apb_forward_int_popcount")
+    return D
+
+
+def apb_forward_popcount(layer: ApbLayer, packed: torch.Tensor, M: int, bits: int, step: float,
+                         Y: Optional[torch.Tensor] = None,
+                         stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    N, _ = _check_packed(layer, packed, M, bits)
+    if Y is None:
+        Y = torch.empty((N, M), dtype=torch.float32, device=packed.device)
+    elif tuple(Y.shape) != (N, M):
+        raise ValueError("Y must be [N, M]")
+    _check(load().apb_forward_popcount(layer.handle, _dev_ptr(packed, torch.int32, "packed"), int(M), int(bits),
+                                       float(step), _dev_ptr(Y, torch.float32, "Y"), _stream(stream)),
+           "apb_forward_popcount")
+    return Y

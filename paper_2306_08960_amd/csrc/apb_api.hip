@@ -18,7 +18,7 @@ namespace {
 hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 void free_layer_buffers(LayerDev& d) {
-    void* ptrs[] = {d.sign, d.signT, d.perm, d.row_ptr, d.col_idx, d.val, d.rowsum, d.chunk_ptr, d.slot_valsum, d.vald};
+    void* ptrs[] = {d.sign, d.signT, d.perm, d.row_ptr, d.col_idx, d.val, d.rowsum, d.chunk_ptr, d.slot_valsum, d.vald, d.signC};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     d = LayerDev{};
@@ -104,6 +104,7 @@ int compress_impl(const float* W, int N, int K, float delta, float alpha, hipStr
     if ((rc = dev_alloc(&d.row_ptr, (size_t)N + 1)) != APB_OK) return rc;
     if ((rc = dev_alloc(&d.perm, (size_t)d.Np)) != APB_OK) return rc;
     if ((rc = dev_alloc(&d.signT, (size_t)d.Np * d.Kw)) != APB_OK) return rc;
+    if ((rc = dev_alloc(&d.signC, (size_t)N * (2 * ((d.Kw + 1) / 2)))) != APB_OK) return rc;
     if ((rc = dev_alloc(&d.chunk_ptr, (size_t)d.Np * (d.nchunks + 1))) != APB_OK) return rc;
     if ((rc = dev_alloc(&d.slot_valsum, (size_t)d.Np)) != APB_OK) return rc;
     if ((rc = dev_alloc(&counts, (size_t)N)) != APB_OK) return rc;
@@ -132,7 +133,8 @@ int compress_impl(const float* W, int N, int K, float delta, float alpha, hipStr
     APB_HIP(hipMemcpyAsync(d.row_ptr, hrow_ptr.data(), ((size_t)N + 1) * sizeof(int32_t), hipMemcpyHostToDevice, s));
     APB_HIP(hipMemcpyAsync(d.perm, hperm.data(), (size_t)d.Np * sizeof(int32_t), hipMemcpyHostToDevice, s));
     if (nnz > 0 && (rc = launch_scatter_csr(W, N, K, delta, alpha, d.row_ptr, d.col_idx, d.val, d.vald, s)) != APB_OK) return rc;
-    if ((rc = launch_slot_major_signs(d.sign, d.perm, d.Np, d.Kw, d.signT, s)) != APB_OK) return rc;
+    if ((rc = launch_slot_major_signs(d.sign, d.perm, d.Np, d.Kw, d.Kw, d.signT, s)) != APB_OK) return rc;
+    if ((rc = launch_slot_major_signs(d.sign, nullptr, N, d.Kw, 2 * ((d.Kw + 1) / 2), d.signC, s)) != APB_OK) return rc;
     if ((rc = launch_slot_tables(d.perm, d.row_ptr, d.col_idx, d.val, d.Np, d.nchunks, d.chunk_ptr, d.slot_valsum,
                                  s)) != APB_OK)
         return rc;
@@ -240,8 +242,10 @@ int apb_quantize_acts(const float* X, int K, int M, int bits, float step, void* 
     return launch_quantize(X, K, M, bits, inv_step, planes, colsum, as_stream(stream));
 }
 
+enum FwdKind { kFwdFull, kFwdFullPopcount, kFwdIntPopcount, kFwdIntMfma };
+
 static int forward_common(const apb_layer* layer, const void* packed, int M, int bits, float step, float* Y,
-                          int32_t* D, void* stream) {
+                          int32_t* D, void* stream, FwdKind kind) {
     if (!layer || !packed || (!Y && !D)) return APB_ERR_NULL;
     const LayerDev& d = layer->d;
     if (bad_shape_acts(d.K, M) || (long long)d.N * M >= (1LL << 40)) return APB_ERR_SHAPE;
@@ -250,17 +254,39 @@ static int forward_common(const apb_layer* layer, const void* packed, int M, int
     const size_t Mp = (size_t)kWave * (((size_t)M + kWave - 1) / kWave);
     const uint32_t* planes = static_cast<const uint32_t*>(packed);
     const int32_t* colsum = reinterpret_cast<const int32_t*>(planes + (size_t)bits * d.Kw * Mp);
-    return launch_forward(d, planes, colsum, M, bits, step, Y, D, as_stream(stream));
+    hipStream_t s = as_stream(stream);
+    if (kind == kFwdIntMfma) {
+        const int rc = launch_binary_mfma(d, planes, M, bits, D, s);
+        return rc != APB_OK ? rc : launch_finalize_int(d, colsum, M, bits, D, s);
+    }
+    if (kind == kFwdFull) {
+        // The raw binary product is left in the output buffer itself (same size, int32 bits) and
+        // turned into Y in place by the sparse/epilogue kernel: no workspace, no allocation.
+        const int rc = launch_binary_mfma(d, planes, M, bits, reinterpret_cast<int32_t*>(Y), s);
+        return rc != APB_OK ? rc : launch_sparse_epilogue(d, planes, colsum, M, bits, step, Y, s);
+    }
+    return launch_forward_popcount(d, planes, colsum, M, bits, step, Y, D, s);
 }
 
 int apb_forward(const apb_layer* layer, const void* packed, int M, int bits, float step, float* Y, void* stream) {
     if (!Y) return APB_ERR_NULL;
-    return forward_common(layer, packed, M, bits, step, Y, nullptr, stream);
+    return forward_common(layer, packed, M, bits, step, Y, nullptr, stream, kFwdFull);
+}
+
+int apb_forward_popcount(const apb_layer* layer, const void* packed, int M, int bits, float step, float* Y,
+                         void* stream) {
+    if (!Y) return APB_ERR_NULL;
+    return forward_common(layer, packed, M, bits, step, Y, nullptr, stream, kFwdFullPopcount);
 }
 
 int apb_forward_int(const apb_layer* layer, const void* packed, int M, int bits, int32_t* D, void* stream) {
     if (!D) return APB_ERR_NULL;
-    return forward_common(layer, packed, M, bits, 1.0f, nullptr, D, stream);
+    return forward_common(layer, packed, M, bits, 1.0f, nullptr, D, stream, kFwdIntMfma);
+}
+
+int apb_forward_int_popcount(const apb_layer* layer, const void* packed, int M, int bits, int32_t* D, void* stream) {
+    if (!D) return APB_ERR_NULL;
+    return forward_common(layer, packed, M, bits, 1.0f, nullptr, D, stream, kFwdIntPopcount);
 }
 
 const char* apb_strerror(int code) {

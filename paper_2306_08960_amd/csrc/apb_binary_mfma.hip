@@ -1,0 +1,275 @@
+// Binary part on the matrix cores: P[n,m] = sum_k b[n,k] * code[k,m] with b = sign bit in {0,1} and
+// code = stored activation code (0..3 for 2-bit, 0/1 for 1-bit), from which
+//   2-bit:  D = sum_k sigma*p       = 2*P - colsum[m]
+//   1-bit:  D = sum_k sigma*(2c-1)  = 4*P - rowsum[n] - 2*colsum[m]
+// (sigma = 2b-1; the same algebra that turns Sec. IV Eq. 16 / Eqs. 18-19 into and+popcount forms).
+//
+// The operands stay packed (one bit per weight, one bit per activation plane) all the way into
+// registers.  There each lane spreads the 32 bits it owns into the 32 four-bit operand slots of one
+// v_mfma_scale_f32_32x32x64_f8f6f4 in FP4 (E2M1) format with shift+and: a weight bit becomes the
+// nibble 0b0001 (= 0.5), the two plane bits of an activation become the nibble p0 | p1<<1
+// (= 0.5, 1.0, 1.5 for codes 1, 2, 3 -- the encoding is additive in the planes, so no table is
+// needed).  Products are multiples of 1/4 and every partial sum is far below 2^24 of those, so the
+// float accumulators hold P/4 exactly; the result is converted back to int32.  HBM, L2 and the load
+// path only ever carry bits.  The k-slot a bit lands in is the same function of (lane half, dword,
+// nibble) for both operands, which is all the contraction needs:
+//   lane l = 32*g + i (i: row of A / column of B, g: lane half) owns word 2*s+g of K step s;
+//   nibble t of operand dword d  <->  bit d + 4*t of that word.
+//
+// The K loop is software-pipelined by hand: words are fetched four steps ahead into a ring of
+// register sets, and the expansion of step s+1 is interleaved with the MFMAs of step s so that the
+// vector ALU works in the shadow of the matrix pipe.
+#include <cstdlib>
+#include "apb_internal.h"
+
+namespace apb {
+
+namespace {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr uint32_t kNib = 0x11111111u;
+constexpr int kScaleOne = 0x7f7f7f7f;                          // E8M0 exponent 127 = 1.0 in every byte
+
+struct MfmaParams {
+    const uint32_t* __restrict__ signT;   // [Kw][Np]  word j of row n, rows in the layer's own order
+    const uint32_t* __restrict__ planes;  // [bits][Kw][Mp]
+    int32_t* __restrict__ P;              // [N][M]
+    int Np, Kw, Mp, M;
+    int tiles_m;                          // workgroup tiles along m
+    int waves_m;                          // waves of a workgroup laid along m (2 or 4); the rest along n
+};
+
+template <int RN, int RM>
+struct Frag {
+    v8i a[RN];
+    v8i b[RM];
+};
+
+template <int BITS, int RN, int RM>
+__device__ __forceinline__ void expand(const uint32_t (&aw)[RN], const uint32_t (&bw)[BITS][RM], Frag<RN, RM>& f) {
+#pragma unroll
+    for (int t = 0; t < RN; ++t) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) f.a[t][d] = (int)((aw[t] >> d) & kNib);
+    }
+#pragma unroll
+    for (int u = 0; u < RM; ++u) {
+        if (BITS == 1) {
+#pragma unroll
+            for (int d = 0; d < 4; ++d) f.b[u][d] = (int)((bw[0][u] >> d) & kNib);
+        } else {
+            const uint32_t z1 = bw[BITS - 1][u];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                // the plane-1 bit goes one position up inside the nibble: bit d+4t -> bit 4t+1
+                const uint32_t hi = d == 0 ? (z1 << 1) : (z1 >> (d - 1));
+                f.b[u][d] = (int)((hi & (kNib << 1)) | ((bw[0][u] >> d) & kNib));
+            }
+        }
+    }
+}
+
+// Workgroup = 4 waves; each wave owns RN x RM MFMA tiles of 32 x 32 and walks K in steps of 64.
+template <int BITS, int RN, int RM>
+__global__ __launch_bounds__(256) void k_binary_mfma(const MfmaParams p) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int i = lane & 31, g = lane >> 5;
+    const int tile_m = blockIdx.x % p.tiles_m;
+    const int tile_n = blockIdx.x / p.tiles_m;
+    const int waves_n = 4 / p.waves_m;
+    const int slot_base = (tile_n * waves_n + wave / p.waves_m) * (32 * RN);
+    const int m_base = (tile_m * p.waves_m + wave % p.waves_m) * (32 * RM);
+    if (slot_base >= p.Np || m_base >= p.Mp) return;          // wave-uniform: a tile fully outside
+
+    // Row/column this lane feeds in each tile, clamped so that loads stay inside the arrays (tiles
+    // may hang over Np / Mp; results of the overhang are never stored).  The lane half g selects the
+    // odd word of a step, which is a constant per-lane offset on top of a wave-uniform row pointer.
+    unsigned aoff[RN], boff[RM];
+#pragma unroll
+    for (int t = 0; t < RN; ++t) aoff[t] = (unsigned)(g * p.Np + min(slot_base + 32 * t + i, p.Np - 1));
+#pragma unroll
+    for (int u = 0; u < RM; ++u) boff[u] = (unsigned)(g * p.Mp + min(m_base + 32 * u + i, p.Mp - 1));
+    const size_t plane_stride = (size_t)p.Kw * p.Mp;
+    const int steps = (p.Kw + 1) / 2;
+
+    v16f acc[RN][RM];
+#pragma unroll
+    for (int t = 0; t < RN; ++t)
+#pragma unroll
+        for (int u = 0; u < RM; ++u)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][u][r] = 0.0f;
+
+    auto load_words = [&](int s, uint32_t (&a)[RN], uint32_t (&b)[BITS][RM]) {
+        // Branch-free on purpose (a branch here would make every step wait for its own loads).
+        // Odd word count: the weight array carries one extra all-zero word row, so the upper lane
+        // half of the last step multiplies by zero; its activation load then reads one row past
+        // the plane, which is still inside the packed buffer (the next plane, or the Mp column
+        // sums that follow the last plane) and, being FP4, cannot be a NaN or an infinity.
+        const int ss = min(s, steps - 1);                     // past the end: harmless re-read, never used
+        const uint32_t* arow = p.signT + (size_t)(2 * ss) * p.Np;
+#pragma unroll
+        for (int t = 0; t < RN; ++t) a[t] = arow[aoff[t]];
+#pragma unroll
+        for (int pl = 0; pl < BITS; ++pl) {
+            const uint32_t* brow = p.planes + pl * plane_stride + (size_t)(2 * ss) * p.Mp;
+#pragma unroll
+            for (int u = 0; u < RM; ++u) b[pl][u] = brow[boff[u]];
+        }
+    };
+
+    // A ring of kRing word sets (set s % kRing holds the words of step s) and two operand sets used
+    // alternately: the loads of step s+kRing are issued during step s and first touched in step
+    // s+kRing-1, so kRing-1 whole steps of work cover their latency.  No register copies.
+    constexpr int kRing = (RN + BITS * RM) <= 4 ? 16 : 8;    // ~1.5 us of HBM latency to cover
+    uint32_t aw[kRing][RN], bw[kRing][BITS][RM];
+    Frag<RN, RM> f[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+        for (int t = 0; t < RN; ++t)
+#pragma unroll
+            for (int d = 4; d < 8; ++d) f[h].a[t][d] = 0;     // FP4 uses the low four operand dwords
+#pragma unroll
+        for (int u = 0; u < RM; ++u)
+#pragma unroll
+            for (int d = 4; d < 8; ++d) f[h].b[u][d] = 0;
+    }
+#pragma unroll
+    for (int q = 0; q < kRing; ++q) load_words(q, aw[q], bw[q]);
+    expand<BITS, RN, RM>(aw[0], bw[0], f[0]);
+
+    constexpr int kValuPerMfma = (7 * RN + (BITS == 2 ? 15 : 7) * RM + RN * RM - 1) / (RN * RM);
+    // The main loop runs whole groups of kRing steps as straight-line code (no branch between a
+    // load and its use); the remainder (at most kRing-1 steps) is finished below.
+    auto one_step = [&](int s, int q) {
+        const Frag<RN, RM>& cur = f[q & 1];
+        load_words(s + kRing, aw[q], bw[q]);                                      // words of step s+kRing
+        expand<BITS, RN, RM>(aw[(q + 1) % kRing], bw[(q + 1) % kRing], f[(q + 1) & 1]);   // operands of step s+1
+#pragma unroll
+        for (int t = 0; t < RN; ++t)
+#pragma unroll
+            for (int u = 0; u < RM; ++u)
+                acc[t][u] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(cur.a[t], cur.b[u], acc[t][u], 4, 4, 0,
+                                                                            kScaleOne, 0, kScaleOne);
+        // Ask the scheduler to alternate: one MFMA, then a slice of the expansion ALU work.
+#pragma unroll
+        for (int e = 0; e < RN * RM; ++e) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                     // 1 MFMA
+            __builtin_amdgcn_sched_group_barrier(0x002, kValuPerMfma, 0);          // VALU
+        }
+    };
+    int s0 = 0;
+    for (; s0 + kRing <= steps; s0 += kRing) {
+#pragma unroll
+        for (int q = 0; q < kRing; ++q) one_step(s0 + q, q);
+    }
+#pragma unroll
+    for (int q = 0; q < kRing - 1; ++q)
+        if (s0 + q < steps) one_step(s0 + q, q);
+
+    // C layout of the 32x32 tile: lane (i, g), register r  ->  row 8*(r/4) + 4*g + (r%4), column i.
+    // Rows are in the layer's own order here (the dense part needs no load balancing), so the
+    // epilogue is straight-line: no index loads between the stores.
+    int32_t* out = p.P + (size_t)(slot_base + 4 * g) * p.M + m_base + i;
+#pragma unroll
+    for (int t = 0; t < RN; ++t) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = 32 * t + 8 * (r / 4) + (r % 4);          // + slot_base + 4*g
+            if (slot_base + 4 * g + row >= p.Np) continue;
+#pragma unroll
+            for (int u = 0; u < RM; ++u) {
+                if (m_base + 32 * u + i < p.M) out[(size_t)row * p.M + 32 * u] = (int)(acc[t][u][r] * 4.0f);
+            }
+        }
+    }
+}
+
+// P -> D in place (see the header of this file).
+template <int BITS>
+__global__ __launch_bounds__(256) void k_finalize_int(int32_t* __restrict__ PD, const int32_t* __restrict__ colsum,
+                                                      const int32_t* __restrict__ rowsum, int N, int M) {
+    const int m = blockIdx.x * 256 + threadIdx.x, n = blockIdx.y;
+    if (m >= M) return;
+    const size_t t = (size_t)n * M + m;
+    const int P = PD[t];
+    PD[t] = BITS == 2 ? 2 * P - colsum[m] : 4 * P - rowsum[n] - 2 * colsum[m];
+}
+
+template <int BITS, int RN, int RM>
+void launch_shape(MfmaParams p, int waves_m, hipStream_t s) {
+    const int waves_n = 4 / waves_m;
+    p.waves_m = waves_m;
+    p.tiles_m = (p.Mp + 32 * RM * waves_m - 1) / (32 * RM * waves_m);
+    const int tiles_n = (p.Np + 32 * RN * waves_n - 1) / (32 * RN * waves_n);
+    hipLaunchKernelGGL((k_binary_mfma<BITS, RN, RM>), dim3((unsigned)(p.tiles_m * tiles_n)), dim3(256), 0, s, p);
+}
+
+struct TileChoice {
+    int rn, rm;
+    int cycles;      // issue cycles per K step of 64 for one wave (expansion + loads + MFMA issue), 2-bit
+};
+
+}  // namespace
+
+// Raw product P (see above) into `P` (N*M int32).  Picks the wave tile that minimises
+// (rounds of waves over 1024 SIMDs) x (cycles per K step of that tile).
+int launch_binary_mfma(const LayerDev& L, const uint32_t* planes, int M, int bits, int32_t* P, hipStream_t s) {
+    const int Mp = kWave * ((M + kWave - 1) / kWave);
+    if ((long long)2 * L.N >= (1LL << 30) || (long long)2 * Mp >= (1LL << 30)) return APB_ERR_SHAPE;
+    MfmaParams p;
+    p.signT = L.signC;                                        // rows in the layer's own order
+    p.planes = planes;
+    p.P = P;
+    p.Np = L.N;
+    p.Kw = L.Kw;
+    p.Mp = Mp;
+    p.M = M;
+    p.tiles_m = p.waves_m = 0;
+
+    static const TileChoice menu[] = {{4, 2, 336}, {2, 4, 408}, {2, 2, 256}, {2, 1, 180}, {1, 1, 144}};
+    int best = 0;
+    double best_cost = 1e300;
+    for (int c = 0; c < 5; ++c) {
+        const long long waves = (long long)((L.N + 32 * menu[c].rn - 1) / (32 * menu[c].rn)) *
+                                ((Mp + 32 * menu[c].rm - 1) / (32 * menu[c].rm));
+        const double rounds = (double)((waves + 1023) / 1024);
+        const double cost = rounds * menu[c].cycles;
+        if (cost < best_cost) {
+            best_cost = cost;
+            best = c;
+        }
+    }
+    int rn = menu[best].rn, rm = menu[best].rm;
+    if (const char* e = getenv("APB_DEBUG_TILE")) { rn = e[0] - '0'; rm = e[1] - '0'; }   // TEMP experiment hook
+    // Waves of a workgroup: two along n when the layer has the rows for them, the rest along m.
+    const int waves_n = 32 * rn * 2 <= L.N ? 2 : 1;
+    const int waves_m = 4 / waves_n;
+#define APB_SHAPE(RN, RM)                                                                  \
+    if (rn == RN && rm == RM) {                                                            \
+        if (bits == 1) launch_shape<1, RN, RM>(p, waves_m, s); else launch_shape<2, RN, RM>(p, waves_m, s); \
+    }
+    APB_SHAPE(4, 2)
+    APB_SHAPE(2, 4)
+    APB_SHAPE(2, 2)
+    APB_SHAPE(2, 1)
+    APB_SHAPE(1, 1)
+#undef APB_SHAPE
+    APB_HIP(hipGetLastError());
+    return APB_OK;
+}
+
+int launch_finalize_int(const LayerDev& L, const int32_t* colsum, int M, int bits, int32_t* PD, hipStream_t s) {
+    if (L.N > 65535) return APB_ERR_SHAPE;
+    const dim3 grid((unsigned)((M + 255) / 256), (unsigned)L.N);
+    if (bits == 1) hipLaunchKernelGGL(k_finalize_int<1>, grid, dim3(256), 0, s, PD, colsum, L.rowsum, L.N, M);
+    else hipLaunchKernelGGL(k_finalize_int<2>, grid, dim3(256), 0, s, PD, colsum, L.rowsum, L.N, M);
+    APB_HIP(hipGetLastError());
+    return APB_OK;
+}
+
+}  // namespace apb

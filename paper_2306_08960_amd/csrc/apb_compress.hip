@@ -122,12 +122,12 @@ __global__ __launch_bounds__(kBlock) void k_scatter_csr(const float* __restrict_
 // signT[j][i] = word j of the row served by launch slot i (0 for padding slots).
 __global__ __launch_bounds__(kBlock) void k_slot_major_signs(const uint32_t* __restrict__ sign,
                                                              const int32_t* __restrict__ perm, int Np, int Kw,
-                                                             uint32_t* __restrict__ signT) {
+                                                             int rows_out, uint32_t* __restrict__ signT) {
     const long long t = (long long)blockIdx.x * kBlock + threadIdx.x;
-    if (t >= (long long)Np * Kw) return;
+    if (t >= (long long)Np * rows_out) return;
     const int j = (int)(t / Np), i = (int)(t % Np);
-    const int n = perm[i];
-    signT[t] = n >= 0 ? sign[(size_t)n * Kw + j] : 0u;
+    const int n = perm ? perm[i] : i;                          // no permutation: plain transpose
+    signT[t] = (n >= 0 && j < Kw) ? sign[(size_t)n * Kw + j] : 0u;   // word rows past Kw are zero padding
 }
 
 // chunk_ptr[c][i]: index of the first residual of the row in slot i whose column is >= 256*c
@@ -195,11 +195,11 @@ int launch_scatter_csr(const float* W, int N, int K, float delta, float alpha, c
     return APB_OK;
 }
 
-int launch_slot_major_signs(const uint32_t* sign, const int32_t* perm, int Np, int Kw, uint32_t* signT,
-                            hipStream_t s) {
-    const long long total = (long long)Np * Kw;
+int launch_slot_major_signs(const uint32_t* sign, const int32_t* perm, int Np, int Kw, int rows_out,
+                            uint32_t* signT, hipStream_t s) {
+    const long long total = (long long)Np * rows_out;
     hipLaunchKernelGGL(k_slot_major_signs, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
-                       sign, perm, Np, Kw, signT);
+                       sign, perm, Np, Kw, rows_out, signT);
     APB_HIP(hipGetLastError());
     return APB_OK;
 }

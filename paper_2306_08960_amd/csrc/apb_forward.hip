@@ -1,22 +1,31 @@
-// apb_forward: Y = s * (alpha*D + sum_j val_j * c[col_j, :])   (Sec. III Eq. 13, one fused kernel)
+// Vector-ALU kernels of apb_forward:  Y = s * (alpha*D + sum_j val_j * c[col_j, :])   (Sec. III Eq. 13)
 //
-// Integer part D (Sec. IV Eq. 16 for 1-bit activations; for 2-bit ones the two stored bit-planes
-// P0, P1 of the level index p stand in for the paper's (t, h, m) vectors of Eqs. 18-19:
-//   D[n,m] = sum_k sigma[n,k]*p[k,m] = 2 * sum_b 2^b * popcount(w & P_b) - colsum[m]).
+// One kernel template, three uses:
+//   kSparseEpilogue  the product path: the matrix-core kernel has left the raw binary product P in
+//                    the output buffer; this kernel adds the residual (sparse) part and the scalars
+//                    and overwrites P with Y in place (each lane reads and writes only its own
+//                    elements).
+//   kFusedPopcount   the paper's own formulation end to end on the vector ALU: xor/and + popcount
+//                    for D (Sec. IV Eq. 16; for 2-bit activations the two stored bit-planes P0, P1
+//                    of the level index stand in for the (t, h, m) vectors of Eqs. 18-19:
+//                    D = 2 * sum_b 2^b * popcount(w & P_b) - colsum), fused with the sparse part.
+//   kIntPopcount     D alone by popcount (test / measurement hook).
 //
 // Mapping: lanes run along m (one output column per lane), so a wave's activation word load is one
-// contiguous 256-byte segment of a plane row, and the weight words of the kRowTile rows a wave owns
-// are wave-uniform: they travel through the scalar path and feed v_and/v_xor as SGPR operands.  Per
-// 32 binary multiply-adds the inner loop issues one logic op and one v_bcnt_u32_b32 (popcount with
-// accumulate), the CDNA counterpart of the paper's xor/popcount/add port analysis.
+// contiguous 256-byte segment of a plane row, and everything that depends only on the weight row --
+// sign words, residual columns and values -- is wave-uniform and travels through the scalar path.
+// In the popcount loop the sign words feed v_and/v_xor as SGPR operands: per 32 binary
+// multiply-adds one logic op and one v_bcnt_u32_b32 (popcount with accumulate), the CDNA counterpart
+// of the paper's xor/popcount/add port analysis.
 //
-// Sparse part: a workgroup (up to 8 waves = 128 weight rows, one 64-column strip) walks K in chunks
-// of 256.  While a wave has the chunk's plane words in registers for the popcounts, it also expands
-// them into a byte-per-activation code table in LDS (row = output column, 256 codes + pad; the
-// 260-byte row pitch keeps the 64 lanes of a wave on distinct banks).  After a barrier every wave
-// adds the residuals of its rows whose column falls in the chunk: one ds_read_u8, one convert and
-// one float64 fused multiply-add per residual and lane; residual column/value pairs are wave-uniform
-// scalar loads, found through per-(row, chunk) offsets prepared at compress time.
+// Sparse part: a workgroup (up to 8 waves = 128 weight rows in launch-slot order, one 64-column
+// strip) walks K in chunks of 256.  The waves expand the chunk's plane words into a byte-per-
+// activation code table in LDS (row = output column, 256 codes + pad; the 260-byte row pitch keeps
+// the 64 lanes of a wave on distinct banks).  After a barrier every wave adds the residuals of its
+// rows whose column falls in the chunk: one ds_read_u8, one convert and one float64 fused
+// multiply-add per residual and lane, found through per-(row, chunk) offsets prepared at compress
+// time.  Rows are dealt to waves by residual count (see balanced_slots), which is what keeps the
+// skewed rows of pruned layers from serialising one wave.
 #include "apb_internal.h"
 
 namespace apb {
@@ -27,16 +36,19 @@ constexpr int TN = kRowTile;
 constexpr int kTablePitch = kChunkK + 4;                       // bytes per column row of the code table
 constexpr int kTableBytes = kWave * kTablePitch;               // one buffer; two are used alternately
 
+enum FwdMode { kFusedPopcount = 0, kIntPopcount = 1, kSparseEpilogue = 2 };
+
 struct FwdParams {
     const uint32_t* __restrict__ signT;
     const uint32_t* __restrict__ planes;
     const int32_t* __restrict__ colsum;
+    const int32_t* __restrict__ rowsum;
     const int32_t* __restrict__ perm;
     const int32_t* __restrict__ chunk_ptr;
     const int32_t* __restrict__ col_idx;
     const double* __restrict__ vald;
     const double* __restrict__ slot_valsum;
-    float* __restrict__ Y;
+    float* Y;                    // kSparseEpilogue: holds P (int32 bits) on entry
     int32_t* __restrict__ D;
     double alpha, step;
     int Np, Kw, K, Mp, M, nchunks;
@@ -47,9 +59,22 @@ struct FwdParams {
 // Spread the 4 low bits of `nib` to the least significant bits of the 4 bytes of a word.
 __device__ __forceinline__ uint32_t spread4(uint32_t nib) { return (nib * 0x00204081u) & 0x01010101u; }
 
-template <int BITS, bool INT_ONLY>
-__global__ __launch_bounds__(kWave* kMaxWavesPerBlock) void k_forward_fused(const FwdParams p) {
+template <int BITS>
+__device__ __forceinline__ void expand_word(uint32_t x0, uint32_t x1, uint8_t* dst_bytes) {
+    uint32_t* dst = reinterpret_cast<uint32_t*>(dst_bytes);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        uint32_t t = spread4((x0 >> (4 * i)) & 0xFu);
+        if (BITS == 2) t |= spread4((x1 >> (4 * i)) & 0xFu) << 1;
+        dst[i] = t;                                             // bytes: codes of k = 32*j + 4*i + 0..3
+    }
+}
+
+template <int BITS, int MODE>
+__global__ __launch_bounds__(kWave* kMaxWavesPerBlock) void k_forward_valu(const FwdParams p) {
     extern __shared__ __align__(16) uint8_t lds[];
+    constexpr bool kPop = MODE != kSparseEpilogue;              // popcount loop present
+    constexpr bool kSparse = MODE != kIntPopcount;              // sparse part present
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int waves = blockDim.x / kWave;
@@ -77,63 +102,69 @@ __global__ __launch_bounds__(kWave* kMaxWavesPerBlock) void k_forward_fused(cons
     const size_t plane_stride = (size_t)p.Kw * p.Mp;
     uint8_t* my_row = lds + lane * kTablePitch;
 
-    // Activation words of one whole chunk live in registers and are fetched one chunk ahead; the
-    // weight words (scalar loads) are fetched one word ahead.
+    // Popcount modes: the activation words of one whole chunk live in registers and are fetched one
+    // chunk ahead; the weight words (scalar loads) one word ahead.
     uint32_t xcur[BITS][kChunkWords], xnext[BITS][kChunkWords];
-#pragma unroll
-    for (int jj = 0; jj < kChunkWords; ++jj)
-#pragma unroll
-        for (int b = 0; b < BITS; ++b)
-            xnext[b][jj] = jj < p.Kw ? xp[b * plane_stride + (size_t)jj * p.Mp] : 0u;
     uint32_t wnext[TN];
+    if (kPop) {
 #pragma unroll
-    for (int r = 0; r < TN; ++r) wnext[r] = wp[r];
+        for (int jj = 0; jj < kChunkWords; ++jj)
+#pragma unroll
+            for (int b = 0; b < BITS; ++b)
+                xnext[b][jj] = jj < p.Kw ? xp[b * plane_stride + (size_t)jj * p.Mp] : 0u;
+#pragma unroll
+        for (int r = 0; r < TN; ++r) wnext[r] = wp[r];
+    }
 
     for (int c = 0; c < p.nchunks; ++c) {
         const int j0 = c * kChunkWords;
         uint8_t* table_row = my_row + (c & 1) * kTableBytes;
+        if (kPop) {
 #pragma unroll
-        for (int jj = 0; jj < kChunkWords; ++jj)
+            for (int jj = 0; jj < kChunkWords; ++jj)
 #pragma unroll
-            for (int b = 0; b < BITS; ++b) {
-                xcur[b][jj] = xnext[b][jj];
-                const int jn = j0 + kChunkWords + jj;               // words past the end read as zero
-                xnext[b][jj] = jn < p.Kw ? xp[b * plane_stride + (size_t)jn * p.Mp] : 0u;
-            }
-#pragma unroll
-        for (int jj = 0; jj < kChunkWords; ++jj) {
-            const int j = j0 + jj;
-            if (j >= p.Kw) break;
-            uint32_t wcur[TN];
-#pragma unroll
-            for (int r = 0; r < TN; ++r) wcur[r] = wnext[r];
-            if (j + 1 < p.Kw) {
-                const uint32_t* w = wp + (size_t)(j + 1) * p.Np;
-#pragma unroll
-                for (int r = 0; r < TN; ++r) wnext[r] = w[r];
-            }
-            const uint32_t x0 = xcur[0][jj];
-            const uint32_t x1 = xcur[BITS - 1][jj];
-#pragma unroll
-            for (int r = 0; r < TN; ++r) {
-                if (BITS == 1) {
-                    acc[0][r] += __builtin_popcount(wcur[r] ^ x0);
-                } else {
-                    acc[0][r] += __builtin_popcount(wcur[r] & x0);
-                    acc[1][r] += __builtin_popcount(wcur[r] & x1);
+                for (int b = 0; b < BITS; ++b) {
+                    xcur[b][jj] = xnext[b][jj];
+                    const int jn = j0 + kChunkWords + jj;           // words past the end read as zero
+                    xnext[b][jj] = jn < p.Kw ? xp[b * plane_stride + (size_t)jn * p.Mp] : 0u;
                 }
-            }
-            if (!INT_ONLY && (jj % waves) == wave) {           // this wave expands word jj of the chunk
-                uint32_t* dst = reinterpret_cast<uint32_t*>(table_row + 32 * jj);
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    uint32_t t = spread4((x0 >> (4 * i)) & 0xFu);
-                    if (BITS == 2) t |= spread4((x1 >> (4 * i)) & 0xFu) << 1;
-                    dst[i] = t;                                 // bytes: codes of k = 32*j + 4*i + 0..3
+            for (int jj = 0; jj < kChunkWords; ++jj) {
+                const int j = j0 + jj;
+                if (j >= p.Kw) break;
+                uint32_t wcur[TN];
+#pragma unroll
+                for (int r = 0; r < TN; ++r) wcur[r] = wnext[r];
+                if (j + 1 < p.Kw) {
+                    const uint32_t* w = wp + (size_t)(j + 1) * p.Np;
+#pragma unroll
+                    for (int r = 0; r < TN; ++r) wnext[r] = w[r];
                 }
+                const uint32_t x0 = xcur[0][jj];
+                const uint32_t x1 = xcur[BITS - 1][jj];
+#pragma unroll
+                for (int r = 0; r < TN; ++r) {
+                    if (BITS == 1) {
+                        acc[0][r] += __builtin_popcount(wcur[r] ^ x0);
+                    } else {
+                        acc[0][r] += __builtin_popcount(wcur[r] & x0);
+                        acc[1][r] += __builtin_popcount(wcur[r] & x1);
+                    }
+                }
+                if (kSparse && (jj % waves) == wave) expand_word<BITS>(x0, x1, table_row + 32 * jj);
+            }
+        } else {
+            // Sparse-only: each wave fetches just the words it expands (word jj of the chunk goes
+            // to wave jj % waves).
+            for (int jj = wave; jj < kChunkWords; jj += waves) {
+                const int j = j0 + jj;
+                if (j >= p.Kw) break;
+                const uint32_t x0 = xp[(size_t)j * p.Mp];
+                const uint32_t x1 = BITS == 2 ? xp[plane_stride + (size_t)j * p.Mp] : 0u;
+                expand_word<BITS>(x0, x1, table_row + 32 * jj);
             }
         }
-        if (INT_ONLY) continue;
+        if (!kSparse) continue;
         __syncthreads();                                        // the chunk's code table is complete
         const int kbase = c * kChunkK;
         const int32_t* cur_ptr = p.chunk_ptr + (size_t)c * p.Np + slot0;
@@ -163,14 +194,21 @@ __global__ __launch_bounds__(kWave* kMaxWavesPerBlock) void k_forward_fused(cons
         // every wave has passed the next barrier, i.e. has finished reading it.
     }
 
-    const int cs = BITS == 2 ? p.colsum[m] : 0;
+    const int cs = p.colsum[m];
     const bool col_ok = m < p.M;
 #pragma unroll
     for (int r = 0; r < TN; ++r) {
         const int n = p.perm[slot0 + r];
         if (n < 0) continue;
-        const int d = BITS == 1 ? p.K - 2 * acc[0][r] : 2 * (acc[0][r] + 2 * acc[BITS - 1][r]) - cs;
-        if (INT_ONLY) {
+        int d;
+        if (kPop) {
+            d = BITS == 1 ? p.K - 2 * acc[0][r] : 2 * (acc[0][r] + 2 * acc[BITS - 1][r]) - cs;
+        } else {
+            // raw matrix-core product P = sum_k b*code  ->  D (b = sign bit, code = stored code)
+            const int P = col_ok ? reinterpret_cast<const int32_t*>(p.Y)[(size_t)n * p.M + m] : 0;
+            d = BITS == 1 ? 4 * P - p.rowsum[n] - 2 * cs : 2 * P - cs;
+        }
+        if (MODE == kIntPopcount) {
             if (col_ok) p.D[(size_t)n * p.M + m] = d;
             continue;
         }
@@ -181,15 +219,14 @@ __global__ __launch_bounds__(kWave* kMaxWavesPerBlock) void k_forward_fused(cons
     }
 }
 
-}  // namespace
-
-int launch_forward(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
-                   float* Y, int32_t* D, hipStream_t s) {
+int launch_mode(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
+                float* Y, int32_t* D, int mode, hipStream_t s) {
     const int Mp = kWave * ((M + kWave - 1) / kWave);
     FwdParams p;
     p.signT = L.signT;
     p.planes = planes;
     p.colsum = colsum;
+    p.rowsum = L.rowsum;
     p.perm = L.perm;
     p.chunk_ptr = L.chunk_ptr;
     p.col_idx = L.col_idx;
@@ -210,16 +247,30 @@ int launch_forward(const LayerDev& L, const uint32_t* planes, const int32_t* col
     if (blocks > 0x7fffffffLL) return APB_ERR_SHAPE;
     p.blocks = (int)blocks;
     const dim3 grid((unsigned)blocks), block(kWave * L.waves);
-    const size_t lds_bytes = D ? 0 : 2 * kTableBytes;
-#define APB_FWD(B, I) hipLaunchKernelGGL((k_forward_fused<B, I>), grid, block, lds_bytes, s, p)
-    if (D != nullptr) {
-        if (bits == 1) APB_FWD(1, true); else APB_FWD(2, true);
+    const size_t lds_bytes = mode == kIntPopcount ? 0 : 2 * kTableBytes;
+#define APB_FWD(B, MD) hipLaunchKernelGGL((k_forward_valu<B, MD>), grid, block, lds_bytes, s, p)
+    if (mode == kFusedPopcount) {
+        if (bits == 1) APB_FWD(1, kFusedPopcount); else APB_FWD(2, kFusedPopcount);
+    } else if (mode == kIntPopcount) {
+        if (bits == 1) APB_FWD(1, kIntPopcount); else APB_FWD(2, kIntPopcount);
     } else {
-        if (bits == 1) APB_FWD(1, false); else APB_FWD(2, false);
+        if (bits == 1) APB_FWD(1, kSparseEpilogue); else APB_FWD(2, kSparseEpilogue);
     }
 #undef APB_FWD
     APB_HIP(hipGetLastError());
     return APB_OK;
+}
+
+}  // namespace
+
+int launch_forward_popcount(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
+                            float step, float* Y, int32_t* D, hipStream_t s) {
+    return launch_mode(L, planes, colsum, M, bits, step, Y, D, D ? kIntPopcount : kFusedPopcount, s);
+}
+
+int launch_sparse_epilogue(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
+                           float step, float* Y, hipStream_t s) {
+    return launch_mode(L, planes, colsum, M, bits, step, Y, nullptr, kSparseEpilogue, s);
 }
 
 }  // namespace apb

@@ -23,6 +23,8 @@ struct LayerDev {
     float alpha = 0.f;
     uint32_t* sign = nullptr;    // [N][Kw]   canonical sign words
     uint32_t* signT = nullptr;   // [Kw][Np]  sign words, slot-major: word j of launch slot i
+    uint32_t* signC = nullptr;   // [Kw2][N]  sign words, word-major in the layer's own row order;
+                                 //           Kw2 = Kw rounded up to even, the extra word row is zero
     int32_t* perm = nullptr;     // [Np]      row index served by launch slot i, -1 for padding
     int32_t* row_ptr = nullptr;  // [N+1]
     int32_t* col_idx = nullptr;  // [nnz]
@@ -53,8 +55,8 @@ int launch_sign_pack_count(const float* W, int N, int K, int Kw, float delta, ui
                            int32_t* rowsum, hipStream_t s);
 int launch_scatter_csr(const float* W, int N, int K, float delta, float alpha, const int32_t* row_ptr,
                        int32_t* col_idx, float* val, double* vald, hipStream_t s);
-int launch_slot_major_signs(const uint32_t* sign, const int32_t* perm, int Np, int Kw, uint32_t* signT,
-                            hipStream_t s);
+int launch_slot_major_signs(const uint32_t* sign, const int32_t* perm, int Np, int Kw, int rows_out,
+                            uint32_t* signT, hipStream_t s);
 int launch_slot_tables(const int32_t* perm, const int32_t* row_ptr, const int32_t* col_idx, const float* val, int Np,
                        int nchunks, int32_t* chunk_ptr, double* slot_valsum, hipStream_t s);
 
@@ -63,8 +65,16 @@ int launch_quantize(const float* X, int K, int M, int bits, float inv_step, uint
                     hipStream_t s);
 
 // forward
-int launch_forward(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
-                   float* Y, int32_t* D, hipStream_t s);
+// vector-ALU kernels: popcount formulation (Y, or D alone when D != nullptr), and the sparse part +
+// epilogue that turns the raw matrix-core product left in Y into the final output, in place
+int launch_forward_popcount(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
+                            float step, float* Y, int32_t* D, hipStream_t s);
+int launch_sparse_epilogue(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
+                           float step, float* Y, hipStream_t s);
+
+// binary part on the matrix cores: raw product P, and P -> D in place
+int launch_binary_mfma(const LayerDev& L, const uint32_t* planes, int M, int bits, int32_t* P, hipStream_t s);
+int launch_finalize_int(const LayerDev& L, const int32_t* colsum, int M, int bits, int32_t* PD, hipStream_t s);
 
 }  // namespace apb
 

@@ -69,17 +69,20 @@ def check_layer(b, W, delta, X, bits, step, alpha=None, tag=""):
 
     # a3: integer part, exact
     D = _bits_view(b.apb_forward_int(layer, packed, M, bits))
-    assert np.array_equal(D, F["D"])
+    assert np.array_equal(D, F["D"]), "matrix-core integer part"
+    D2 = _bits_view(b.apb_forward_int_popcount(layer, packed, M, bits))
+    assert np.array_equal(D2, F["D"]), "popcount integer part"
 
-    # a4 + a5: float output
-    Y = _bits_view(b.apb_forward(layer, packed, M, bits, float(step)))
+    # a4 + a5: float output, product path (matrix cores + sparse/epilogue) and popcount path
     ref = F["Y"]
-    err = np.abs(Y.astype(np.float64) - ref.astype(np.float64))
-    bound = REL_TOL * np.abs(ref.astype(np.float64))
-    bad = err > bound
-    assert not bad.any(), (f"{int(bad.sum())} of {bad.size} outputs off by more than {REL_TOL} relative; "
-                           f"worst {float((err / np.maximum(np.abs(ref), 1e-300)).max()):.3g}")
-    ulps = err / np.spacing(np.maximum(np.abs(ref), np.float32(1e-30)))
+    for name, fn in (("apb_forward", b.apb_forward), ("apb_forward_popcount", b.apb_forward_popcount)):
+        Y = _bits_view(fn(layer, packed, M, bits, float(step)))
+        err = np.abs(Y.astype(np.float64) - ref.astype(np.float64))
+        bound = REL_TOL * np.abs(ref.astype(np.float64))
+        bad = err > bound
+        assert not bad.any(), (f"{name}: {int(bad.sum())} of {bad.size} outputs off by more than {REL_TOL} "
+                               f"relative; worst {float((err / np.maximum(np.abs(ref), 1e-300)).max()):.3g}")
+        ulps = err / np.spacing(np.maximum(np.abs(ref), np.float32(1e-30)))
     print(f"        nnz={nnz} max |D|={int(np.abs(D).max())} max ulp diff of Y={float(ulps.max()):.2f}", flush=True)
     layer.free()
     return Y
