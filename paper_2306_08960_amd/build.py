@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libapb.so")
-SOURCES = ["apb_api.hip", "apb_compress.hip", "apb_quantize.hip", "apb_forward.hip", "apb_binary_mfma.hip"]
+SOURCES = ["apb_api.hip", "apb_compress.hip", "apb_quantize.hip", "apb_forward.hip", "apb_binary_mfma.hip", "apb_sparse.hip"]
 
 # Packed-FP32 VALU forms are disabled on purpose; contraction is off so that every fused
 # multiply-add in the kernels is one written explicitly.

@@ -18,7 +18,8 @@ namespace {
 hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 void free_layer_buffers(LayerDev& d) {
-    void* ptrs[] = {d.sign, d.signT, d.perm, d.row_ptr, d.col_idx, d.val, d.rowsum, d.chunk_ptr, d.slot_valsum, d.vald, d.signC};
+    void* ptrs[] = {d.sign, d.signT, d.perm, d.row_ptr, d.col_idx, d.val, d.rowsum, d.chunk_ptr, d.slot_valsum, d.vald, d.signC,
+                    d.seg_ptr, d.ent_key, d.ent_val};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     d = LayerDev{};
@@ -54,6 +55,44 @@ std::vector<int32_t> balanced_slots(const std::vector<int32_t>& counts, int Np) 
         perm[t * kRowTile + fill[t]++] = order[i];
     }
     return perm;
+}
+
+// Regroup the CSR for the sparse kernel: for every tile of kRowTile launch slots and every chunk of
+// kChunkK columns one flat run of entries, sorted by (row in tile, column).  The last entry of each
+// row's part of a run carries a flag so the kernel knows when to retire its partial sum.
+void build_tile_runs(const std::vector<int32_t>& perm, const std::vector<int32_t>& row_ptr,
+                     const std::vector<int32_t>& col, const std::vector<float>& val, int nchunks,
+                     std::vector<int32_t>& seg_ptr, std::vector<uint32_t>& key, std::vector<double>& dval) {
+    const int tiles = (int)perm.size() / kRowTile;
+    seg_ptr.assign((size_t)tiles * (nchunks + 1), 0);
+    key.clear();
+    dval.clear();
+    key.reserve(col.size());
+    dval.reserve(col.size());
+    std::vector<int32_t> cursor(kRowTile);
+    for (int t = 0; t < tiles; ++t) {
+        for (int r = 0; r < kRowTile; ++r) {
+            const int n = perm[(size_t)t * kRowTile + r];
+            cursor[r] = n >= 0 ? row_ptr[n] : 0;
+        }
+        for (int c = 0; c < nchunks; ++c) {
+            seg_ptr[(size_t)t * (nchunks + 1) + c] = (int32_t)key.size();
+            const int hi = (c + 1) * kChunkK;
+            for (int r = 0; r < kRowTile; ++r) {
+                const int n = perm[(size_t)t * kRowTile + r];
+                if (n < 0) continue;
+                const int end = row_ptr[n + 1];
+                const size_t first = key.size();
+                while (cursor[r] < end && col[cursor[r]] < hi) {
+                    key.push_back((uint32_t)(col[cursor[r]] - c * kChunkK) | ((uint32_t)r << 8));
+                    dval.push_back((double)val[cursor[r]]);
+                    ++cursor[r];
+                }
+                if (key.size() > first) key.back() |= 0x1000u;
+            }
+        }
+        seg_ptr[(size_t)t * (nchunks + 1) + nchunks] = (int32_t)key.size();
+    }
 }
 
 int compress_impl(const float* W, int N, int K, float delta, float alpha, hipStream_t s, LayerDev& d) {
@@ -138,6 +177,26 @@ int compress_impl(const float* W, int N, int K, float delta, float alpha, hipStr
     if ((rc = launch_slot_tables(d.perm, d.row_ptr, d.col_idx, d.val, d.Np, d.nchunks, d.chunk_ptr, d.slot_valsum,
                                  s)) != APB_OK)
         return rc;
+    // Tile runs for the sparse kernel: built on the host from the CSR just written (offline work).
+    std::vector<int32_t> hcol((size_t)nnz);
+    std::vector<float> hval((size_t)nnz);
+    if (nnz > 0) {
+        APB_HIP(hipMemcpyAsync(hcol.data(), d.col_idx, (size_t)nnz * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+        APB_HIP(hipMemcpyAsync(hval.data(), d.val, (size_t)nnz * sizeof(float), hipMemcpyDeviceToHost, s));
+    }
+    APB_HIP(hipStreamSynchronize(s));
+    std::vector<int32_t> hseg;
+    std::vector<uint32_t> hkey;
+    std::vector<double> hdval;
+    build_tile_runs(hperm, hrow_ptr, hcol, hval, d.nchunks, hseg, hkey, hdval);
+    if ((rc = dev_alloc(&d.seg_ptr, hseg.size())) != APB_OK) return rc;
+    if ((rc = dev_alloc(&d.ent_key, hkey.size())) != APB_OK) return rc;
+    if ((rc = dev_alloc(&d.ent_val, hdval.size())) != APB_OK) return rc;
+    APB_HIP(hipMemcpyAsync(d.seg_ptr, hseg.data(), hseg.size() * sizeof(int32_t), hipMemcpyHostToDevice, s));
+    if (nnz > 0) {
+        APB_HIP(hipMemcpyAsync(d.ent_key, hkey.data(), hkey.size() * sizeof(uint32_t), hipMemcpyHostToDevice, s));
+        APB_HIP(hipMemcpyAsync(d.ent_val, hdval.data(), hdval.size() * sizeof(double), hipMemcpyHostToDevice, s));
+    }
     APB_HIP(hipStreamSynchronize(s));                 // host staging vectors go out of scope after this
     return APB_OK;
 }

@@ -251,10 +251,8 @@ int launch_mode(const LayerDev& L, const uint32_t* planes, const int32_t* colsum
 #define APB_FWD(B, MD) hipLaunchKernelGGL((k_forward_valu<B, MD>), grid, block, lds_bytes, s, p)
     if (mode == kFusedPopcount) {
         if (bits == 1) APB_FWD(1, kFusedPopcount); else APB_FWD(2, kFusedPopcount);
-    } else if (mode == kIntPopcount) {
-        if (bits == 1) APB_FWD(1, kIntPopcount); else APB_FWD(2, kIntPopcount);
     } else {
-        if (bits == 1) APB_FWD(1, kSparseEpilogue); else APB_FWD(2, kSparseEpilogue);
+        if (bits == 1) APB_FWD(1, kIntPopcount); else APB_FWD(2, kIntPopcount);
     }
 #undef APB_FWD
     APB_HIP(hipGetLastError());
@@ -266,11 +264,6 @@ int launch_mode(const LayerDev& L, const uint32_t* planes, const int32_t* colsum
 int launch_forward_popcount(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
                             float step, float* Y, int32_t* D, hipStream_t s) {
     return launch_mode(L, planes, colsum, M, bits, step, Y, D, D ? kIntPopcount : kFusedPopcount, s);
-}
-
-int launch_sparse_epilogue(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
-                           float step, float* Y, hipStream_t s) {
-    return launch_mode(L, planes, colsum, M, bits, step, Y, nullptr, kSparseEpilogue, s);
 }
 
 }  // namespace apb

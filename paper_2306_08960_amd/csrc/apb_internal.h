@@ -33,6 +33,11 @@ struct LayerDev {
     int32_t* rowsum = nullptr;   // [N]
     int32_t* chunk_ptr = nullptr;  // [nchunks+1][Np]  first residual of slot i with column >= 256*c
     double* slot_valsum = nullptr; // [Np]             sum of the residuals of slot i (float64)
+    // Residuals regrouped for the sparse kernel: one flat run per (tile of kRowTile slots, chunk of
+    // 256 columns), sorted by row inside the run.
+    int32_t* seg_ptr = nullptr;    // [Np/kRowTile][nchunks+1]  first entry of (tile, chunk)
+    uint32_t* ent_key = nullptr;   // [nnz]  col - 256*chunk | row_in_tile << 8 | last_of_row_run << 12
+    double* ent_val = nullptr;     // [nnz]  residual widened to float64 (exact)
 };
 
 void set_last_hip_error(hipError_t e);
