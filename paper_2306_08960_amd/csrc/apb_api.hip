@@ -90,6 +90,10 @@ void build_tile_runs(const std::vector<int32_t>& perm, const std::vector<int32_t
                 }
                 if (key.size() > first) key.back() |= 0x1000u;
             }
+            while ((key.size() - (size_t)seg_ptr[(size_t)t * (nchunks + 1) + c]) % 8 != 0) {
+                key.push_back(0u);                              // padding: column 0, value 0, no flag
+                dval.push_back(0.0);
+            }
         }
         seg_ptr[(size_t)t * (nchunks + 1) + nchunks] = (int32_t)key.size();
     }
@@ -193,7 +197,7 @@ int compress_impl(const float* W, int N, int K, float delta, float alpha, hipStr
     if ((rc = dev_alloc(&d.ent_key, hkey.size())) != APB_OK) return rc;
     if ((rc = dev_alloc(&d.ent_val, hdval.size())) != APB_OK) return rc;
     APB_HIP(hipMemcpyAsync(d.seg_ptr, hseg.data(), hseg.size() * sizeof(int32_t), hipMemcpyHostToDevice, s));
-    if (nnz > 0) {
+    if (!hkey.empty()) {
         APB_HIP(hipMemcpyAsync(d.ent_key, hkey.data(), hkey.size() * sizeof(uint32_t), hipMemcpyHostToDevice, s));
         APB_HIP(hipMemcpyAsync(d.ent_val, hdval.data(), hdval.size() * sizeof(double), hipMemcpyHostToDevice, s));
     }

@@ -12,7 +12,7 @@
 //      banks when they read the same k);
 //   2. after a barrier each wave streams the residuals of its 16 rows that fall in the chunk.  They
 //      were laid out at compress time as ONE flat run per (tile, chunk), sorted by row, so the loop
-//      has no per-row prologue: per residual and lane one address add, one ds_read_u8, one convert
+//      has no per-row prologue (runs are padded to whole batches of 8): per residual and lane one address add, one ds_read_u8, one convert
 //      and one float64 fused multiply-add, plus a register flush when the run moves to the next row.
 // Tiles are filled by dealing rows in order of residual count (see balanced_slots), so the skewed
 // rows of pruned layers are spread over the waves instead of serialising one of them.
@@ -125,25 +125,42 @@ __global__ __launch_bounds__(kWave* kMaxWavesPerBlock) void k_sparse_epilogue(
         __syncthreads();                                        // the chunk's code table is complete
 
         double a = 0.0;                                         // partial sum of the current row run
-        for (; e + 4 <= e1; e += 4) {
-            const uint32_t k0 = ent_key[e], k1 = ent_key[e + 1], k2 = ent_key[e + 2], k3 = ent_key[e + 3];
-            const double v0 = ent_val[e], v1 = ent_val[e + 1], v2 = ent_val[e + 2], v3 = ent_val[e + 3];
-            const uint32_t c0 = table_row[k0 & 255u], c1 = table_row[k1 & 255u];
-            const uint32_t c2 = table_row[k2 & 255u], c3 = table_row[k3 & 255u];
-            a = fma(v0, (double)c0, a);
-            APB_FLUSH(k0)
-            a = fma(v1, (double)c1, a);
-            APB_FLUSH(k1)
-            a = fma(v2, (double)c2, a);
-            APB_FLUSH(k2)
-            a = fma(v3, (double)c3, a);
-            APB_FLUSH(k3)
+        // Runs are padded to a multiple of 8 entries (key 0, value 0.0) at compress time, so the loop
+        // works in whole batches: 16 entries per scalar-load round trip while they last, then at most
+        // one batch of 8.  A large batch is what amortises the scalar-cache latency.
+        for (; e + 16 <= e1; e += 16) {
+            uint32_t k[16];
+            double v[16];
+            uint32_t cc[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                k[i] = ent_key[e + i];
+                v[i] = ent_val[e + i];
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) cc[i] = table_row[k[i] & 255u];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                a = fma(v[i], (double)cc[i], a);
+                APB_FLUSH(k[i])
+            }
         }
-        for (; e < e1; ++e) {
-            const uint32_t k0 = ent_key[e];
-            const uint32_t c0 = table_row[k0 & 255u];
-            a = fma(ent_val[e], (double)c0, a);
-            APB_FLUSH(k0)
+        if (e < e1) {
+            uint32_t k[8];
+            double v[8];
+            uint32_t cc[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                k[i] = ent_key[e + i];
+                v[i] = ent_val[e + i];
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) cc[i] = table_row[k[i] & 255u];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                a = fma(v[i], (double)cc[i], a);
+                APB_FLUSH(k[i])
+            }
         }
         // Every run ends with a flagged entry, so `a` is zero here.  The next chunk writes the other
         // table buffer; this one is rewritten two chunks from now, after every wave has passed the
