@@ -82,16 +82,14 @@ void build_tile_runs(const std::vector<int32_t>& perm, const std::vector<int32_t
                 const int n = perm[(size_t)t * kRowTile + r];
                 if (n < 0) continue;
                 const int end = row_ptr[n + 1];
-                const size_t first = key.size();
                 while (cursor[r] < end && col[cursor[r]] < hi) {
-                    key.push_back((uint32_t)(col[cursor[r]] - c * kChunkK) | ((uint32_t)r << 8));
+                    key.push_back((uint32_t)(2 * r) | ((uint32_t)(col[cursor[r]] - c * kChunkK) << 8));
                     dval.push_back((double)val[cursor[r]]);
                     ++cursor[r];
                 }
-                if (key.size() > first) key.back() |= 0x1000u;
             }
             while ((key.size() - (size_t)seg_ptr[(size_t)t * (nchunks + 1) + c]) % 8 != 0) {
-                key.push_back(0u);                              // padding: column 0, value 0, no flag
+                key.push_back(0u);                              // padding: row 0, column 0, value 0
                 dval.push_back(0.0);
             }
         }

@@ -19,7 +19,6 @@
 // The K loop is software-pipelined by hand: words are fetched four steps ahead into a ring of
 // register sets, and the expansion of step s+1 is interleaved with the MFMAs of step s so that the
 // vector ALU works in the shadow of the matrix pipe.
-#include <cstdlib>
 #include "apb_internal.h"
 
 namespace apb {
@@ -244,8 +243,7 @@ int launch_binary_mfma(const LayerDev& L, const uint32_t* planes, int M, int bit
             best = c;
         }
     }
-    int rn = menu[best].rn, rm = menu[best].rm;
-    if (const char* e = getenv("APB_DEBUG_TILE")) { rn = e[0] - '0'; rm = e[1] - '0'; }   // TEMP experiment hook
+    const int rn = menu[best].rn, rm = menu[best].rm;
     // Waves of a workgroup: two along n when the layer has the rows for them, the rest along m.
     const int waves_n = 32 * rn * 2 <= L.N ? 2 : 1;
     const int waves_m = 4 / waves_n;

@@ -36,8 +36,8 @@ struct LayerDev {
     // Residuals regrouped for the sparse kernel: one flat run per (tile of kRowTile slots, chunk of
     // 256 columns), sorted by row inside the run.
     int32_t* seg_ptr = nullptr;    // [Np/kRowTile][nchunks+1]  first entry of (tile, chunk)
-    uint32_t* ent_key = nullptr;   // [nnz]  col - 256*chunk | row_in_tile << 8 | last_of_row_run << 12
-    double* ent_val = nullptr;     // [nnz]  residual widened to float64 (exact)
+    uint32_t* ent_key = nullptr;   // [entries]  2 * row_in_tile | (col - 256*chunk) << 8
+    double* ent_val = nullptr;     // [entries]  residual widened to float64 (exact); 0 for padding
 };
 
 void set_last_hip_error(hipError_t e);

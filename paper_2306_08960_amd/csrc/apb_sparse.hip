@@ -4,16 +4,20 @@
 // it into D, adds the residual part in float64 and overwrites the same elements with Y (every lane
 // reads and writes only its own outputs, so the pass is in place).
 //
-// Mapping: lanes run along m (64 output columns per wave), so residual columns and values are
-// wave-uniform and arrive through the scalar path.  A workgroup (up to 8 waves, each owning a tile
-// of 16 weight rows in launch-slot order) shares one 64-column strip and walks K in chunks of 256:
+// Mapping: lanes run along m, so residual columns and values are wave-uniform and arrive through
+// the scalar path.  A workgroup (up to 8 waves, each owning a tile of 16 weight rows in launch-slot
+// order) shares one strip of 64 output columns and walks K in chunks of 256:
 //   1. the waves expand the chunk's activation bit-planes into a byte-per-activation code table in
 //      LDS (row = output column, 256 codes + 4 pad bytes, so the 64 lanes of a wave hit distinct
 //      banks when they read the same k);
 //   2. after a barrier each wave streams the residuals of its 16 rows that fall in the chunk.  They
-//      were laid out at compress time as ONE flat run per (tile, chunk), sorted by row, so the loop
-//      has no per-row prologue (runs are padded to whole batches of 8): per residual and lane one address add, one ds_read_u8, one convert
-//      and one float64 fused multiply-add, plus a register flush when the run moves to the next row.
+//      were laid out at compress time as ONE flat run per (tile, chunk), padded to whole batches of
+//      8, so the loop has no per-row work at all.  The 16 float64 row sums of a lane live in 32
+//      consecutive vector registers, and the multiply-add of a residual addresses its row's pair
+//      through the register-index mode: one scalar instruction (index <- low byte of the entry
+//      key = 2*row) and one v_fma_f64.  With the address add (column taken straight from byte 1 of
+//      the key), the ds_read_u8 and the convert that is five instructions per residual and wave,
+//      and no branch.
 // Tiles are filled by dealing rows in order of residual count (see balanced_slots), so the skewed
 // rows of pruned layers are spread over the waves instead of serialising one of them.
 #include "apb_internal.h"
@@ -25,7 +29,8 @@ namespace {
 constexpr int TN = kRowTile;
 constexpr int kTablePitch = kChunkK + 4;                       // bytes per column row of the code table
 constexpr int kTableBytes = kWave * kTablePitch;               // one buffer; two are used alternately
-constexpr int kMaxWordsPerWave = kChunkWords;                  // a lone wave expands all 8 words of a chunk
+
+typedef __attribute__((address_space(3))) uint8_t lds_u8;
 
 struct SparseParams {
     double alpha, step;
@@ -50,31 +55,77 @@ __device__ __forceinline__ void expand_word(uint32_t x0, uint32_t x1, uint8_t* d
 
 typedef double v16d __attribute__((ext_vector_type(TN)));
 
-// acc[row] += a for a wave-uniform row; `a` restarts at zero.  The accumulators are one register
-// vector indexed through the scalar GPR-index mode (two moves in, one add, two moves out).  The
-// empty asm keeps this a real (uniform) branch: folded into selects it would touch all 16 rows.
-#define APB_FLUSH(KEY)                                   \
-    if ((KEY) & 0x1000u) {                               \
-        asm volatile("" ::: "memory");                   \
-        acc[((KEY) >> 8) & 15] += a;                     \
-        a = 0.0;                                         \
-    }
+// acc[key_i.byte0 / 2] += v_i * c_i for 8 entries.  `acc` is pinned to v[0:31]; while the
+// register-index mode is on (destination and third source relative), v[0:1] + M0[7:0] names the
+// pair of the entry's row.  s_set_gpr_idx_on / _idx copy the low byte of a key to M0[7:0]; only the
+// multiply-adds sit inside the indexed region, and the mode is off again when the statement ends.
+__device__ __forceinline__ void accumulate8(v16d& acc, const uint32_t* k, const double* v, const double* c) {
+    asm volatile(
+        "s_set_gpr_idx_on %1, gpr_idx(SRC2,DST)\n\t"
+        "v_fma_f64 v[0:1], %9, %17, v[0:1]\n\t"
+        "s_set_gpr_idx_idx %2\n\t"
+        "v_fma_f64 v[0:1], %10, %18, v[0:1]\n\t"
+        "s_set_gpr_idx_idx %3\n\t"
+        "v_fma_f64 v[0:1], %11, %19, v[0:1]\n\t"
+        "s_set_gpr_idx_idx %4\n\t"
+        "v_fma_f64 v[0:1], %12, %20, v[0:1]\n\t"
+        "s_set_gpr_idx_idx %5\n\t"
+        "v_fma_f64 v[0:1], %13, %21, v[0:1]\n\t"
+        "s_set_gpr_idx_idx %6\n\t"
+        "v_fma_f64 v[0:1], %14, %22, v[0:1]\n\t"
+        "s_set_gpr_idx_idx %7\n\t"
+        "v_fma_f64 v[0:1], %15, %23, v[0:1]\n\t"
+        "s_set_gpr_idx_idx %8\n\t"
+        "v_fma_f64 v[0:1], %16, %24, v[0:1]\n\t"
+        "s_set_gpr_idx_off"
+        : "+{v[0:31]}"(acc)
+        : "s"(k[0]), "s"(k[1]), "s"(k[2]), "s"(k[3]), "s"(k[4]), "s"(k[5]), "s"(k[6]), "s"(k[7]),
+          "s"(v[0]), "s"(v[1]), "s"(v[2]), "s"(v[3]), "s"(v[4]), "s"(v[5]), "s"(v[6]), "s"(v[7]),
+          "v"(c[0]), "v"(c[1]), "v"(c[2]), "v"(c[3]), "v"(c[4]), "v"(c[5]), "v"(c[6]), "v"(c[7]));
+}
 
-template <int BITS>
-__global__ __launch_bounds__(kWave* kMaxWavesPerBlock) void k_sparse_epilogue(
+// One batch of NB (8 or 16) entries starting at e: scalar loads of keys and values, then per entry
+// address add, table read and convert, then the indexed multiply-adds.
+template <int NB>
+__device__ __forceinline__ void batch(v16d& acc, const uint32_t* __restrict__ ent_key,
+                                      const double* __restrict__ ent_val, int e, uint32_t table_off) {
+    uint32_t k[NB];
+    double v[NB], c[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        k[i] = ent_key[e + i];
+        v[i] = ent_val[e + i];
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        uint32_t off;                                           // table row of this lane + column (key byte 1)
+        asm("v_add_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1 src1_sel:DWORD"
+            : "=v"(off)
+            : "s"(k[i]), "v"(table_off));
+        uint32_t code = *reinterpret_cast<const lds_u8*>(off);
+        asm("" : "+v"(code));                                   // keep it a plain zero-extending byte read
+        c[i] = (double)code;
+    }
+#pragma unroll
+    for (int i = 0; i < NB; i += 8) accumulate8(acc, k + i, v + i, c + i);
+}
+
+// WPW = words of a chunk each wave expands = 8 / waves per workgroup.
+template <int BITS, int WPW>
+__global__ __launch_bounds__(kWave* kChunkWords / WPW) void k_sparse_epilogue(
     // Separate restrict-qualified arguments (not struct members) so that the compiler knows the
     // read-only arrays cannot alias Y and keeps the wave-uniform loads on the scalar path.
     const uint32_t* __restrict__ planes, const int32_t* __restrict__ colsum, const int32_t* __restrict__ rowsum,
     const int32_t* __restrict__ perm,
     const int32_t* __restrict__ seg_ptr,     // [tiles][nchunks+1] first entry of (tile, chunk)
-    const uint32_t* __restrict__ ent_key,    // col_local | row_in_tile << 8 | last_of_row_run << 12
+    const uint32_t* __restrict__ ent_key,    // 2 * row_in_tile | col_local << 8
     const double* __restrict__ ent_val, const double* __restrict__ slot_valsum,
     float* Y,                                // holds P (int32 bits) on entry, Y on exit
     const SparseParams p) {
     extern __shared__ __align__(16) uint8_t lds[];
+    constexpr int waves = kChunkWords / WPW;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const int waves = blockDim.x / kWave;
 
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of tasks so
     // that the row groups sharing one activation strip also share one L2.
@@ -84,91 +135,54 @@ __global__ __launch_bounds__(kWave* kMaxWavesPerBlock) void k_sparse_epilogue(
     const int strip = task / p.row_groups;
     const int tile = rg * waves + wave;
     const int slot0 = tile * TN;
-    const int m = strip * kWave + lane;
+    const int m = strip * kWave + lane;                         // < Mp: the strips tile Mp exactly
+    const uint32_t* xp = planes + m;
 
-    static_assert(TN == 16, "row field of an entry key is 4 bits");
+    static_assert(TN == 16, "row field of an entry key addresses 16 register pairs");
     v16d acc;
 #pragma unroll
     for (int r = 0; r < TN; ++r) acc[r] = 0.0;
 
-    const uint32_t* xp = planes + m;
     const size_t plane_stride = (size_t)p.Kw * p.Mp;
     uint8_t* my_row = lds + lane * kTablePitch;
+    const uint32_t my_row_off = (uint32_t)(uintptr_t)(lds_u8*)my_row;   // the same row as an LDS byte address
     const int32_t* seg = seg_ptr + (size_t)tile * (p.nchunks + 1);
 
     // Words this wave expands in a chunk: jj = wave, wave + waves, ...  They are fetched one chunk
     // ahead so that their latency hides behind the residual loop of the chunk before.
-    uint32_t xw[BITS][kMaxWordsPerWave];
+    uint32_t xw[BITS][WPW];
     auto fetch = [&](int c) {
 #pragma unroll
-        for (int i = 0; i < kMaxWordsPerWave; ++i) {
-            const int jj = wave + i * waves;
-            const int j = c * kChunkWords + jj;
-            const bool ok = jj < kChunkWords && j < p.Kw;
+        for (int i = 0; i < WPW; ++i) {
+            const int j = c * kChunkWords + wave + i * waves;
 #pragma unroll
-            for (int b = 0; b < BITS; ++b) xw[b][i] = ok ? xp[b * plane_stride + (size_t)j * p.Mp] : 0u;
+            for (int b = 0; b < BITS; ++b) xw[b][i] = j < p.Kw ? xp[b * plane_stride + (size_t)j * p.Mp] : 0u;
         }
     };
     fetch(0);
     int e1 = seg[0];
 
     for (int c = 0; c < p.nchunks; ++c) {
-        uint8_t* table_row = my_row + (c & 1) * kTableBytes;
+        const int buf = (c & 1) * kTableBytes;
 #pragma unroll
-        for (int i = 0; i < kMaxWordsPerWave; ++i) {
-            const int jj = wave + i * waves;
-            if (jj < kChunkWords) expand_word<BITS>(xw[0][i], xw[BITS - 1][i], table_row + 32 * jj);
-        }
+        for (int i = 0; i < WPW; ++i)
+            expand_word<BITS>(xw[0][i], xw[BITS - 1][i], my_row + buf + 32 * (wave + i * waves));
         if (c + 1 < p.nchunks) fetch(c + 1);
         int e = e1;
         e1 = seg[c + 1];
         __syncthreads();                                        // the chunk's code table is complete
 
-        double a = 0.0;                                         // partial sum of the current row run
-        // Runs are padded to a multiple of 8 entries (key 0, value 0.0) at compress time, so the loop
-        // works in whole batches: 16 entries per scalar-load round trip while they last, then at most
-        // one batch of 8.  A large batch is what amortises the scalar-cache latency.
-        for (; e + 16 <= e1; e += 16) {
-            uint32_t k[16];
-            double v[16];
-            uint32_t cc[16];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                k[i] = ent_key[e + i];
-                v[i] = ent_val[e + i];
-            }
-#pragma unroll
-            for (int i = 0; i < 16; ++i) cc[i] = table_row[k[i] & 255u];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                a = fma(v[i], (double)cc[i], a);
-                APB_FLUSH(k[i])
-            }
-        }
-        if (e < e1) {
-            uint32_t k[8];
-            double v[8];
-            uint32_t cc[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                k[i] = ent_key[e + i];
-                v[i] = ent_val[e + i];
-            }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) cc[i] = table_row[k[i] & 255u];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                a = fma(v[i], (double)cc[i], a);
-                APB_FLUSH(k[i])
-            }
-        }
-        // Every run ends with a flagged entry, so `a` is zero here.  The next chunk writes the other
-        // table buffer; this one is rewritten two chunks from now, after every wave has passed the
-        // next barrier, i.e. has finished reading it.
+        // Whole batches only: 16 entries per scalar-load round trip while they last, then at most one
+        // batch of 8.  A large batch is what amortises the scalar-cache latency.
+        const uint32_t table_off = my_row_off + buf;
+        for (; e + 16 <= e1; e += 16) batch<16>(acc, ent_key, ent_val, e, table_off);
+        if (e < e1) batch<8>(acc, ent_key, ent_val, e, table_off);
+        // The next chunk writes the other table buffer; this one is rewritten two chunks from now,
+        // after every wave has passed the next barrier, i.e. has finished reading it.
     }
 
-    const int cs = colsum[m];
     const bool col_ok = m < p.M;
+    const int cs = colsum[m];
 #pragma unroll
     for (int r = 0; r < TN; ++r) {
         const int n = perm[slot0 + r];
@@ -176,11 +190,32 @@ __global__ __launch_bounds__(kWave* kMaxWavesPerBlock) void k_sparse_epilogue(
         // raw matrix-core product P = sum_k b*code  ->  D (b = sign bit, code = stored code)
         const int P = col_ok ? reinterpret_cast<const int32_t*>(Y)[(size_t)n * p.M + m] : 0;
         const int d = BITS == 1 ? 4 * P - rowsum[n] - 2 * cs : 2 * P - cs;
-        // 1-bit activations: the table holds (c+1)/2 in {0,1}, so sum val*c = 2*sum val*code - sum val.
+        // 1-bit activations: the table holds (c+1)/2 in {0,1}: sum val*c = 2*sum val*code - sum val.
         const double sparse = BITS == 1 ? 2.0 * acc[r] - slot_valsum[slot0 + r] : acc[r];
         const double y = fma(p.alpha, (double)d, sparse) * p.step;
         if (col_ok) Y[(size_t)n * p.M + m] = (float)y;
     }
+}
+
+template <int BITS, int WPW>
+void launch_one(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, float* Y, const SparseParams& p,
+                hipStream_t s) {
+    hipLaunchKernelGGL((k_sparse_epilogue<BITS, WPW>), dim3((unsigned)p.blocks), dim3(kWave * kChunkWords / WPW),
+                       2 * kTableBytes, s, planes, colsum, L.rowsum, L.perm, L.seg_ptr, L.ent_key, L.ent_val,
+                       L.slot_valsum, Y, p);
+}
+
+template <int BITS>
+int launch_bits(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, float* Y, const SparseParams& p,
+                hipStream_t s) {
+    switch (L.waves) {
+        case 8: launch_one<BITS, 1>(L, planes, colsum, Y, p, s); break;
+        case 4: launch_one<BITS, 2>(L, planes, colsum, Y, p, s); break;
+        case 2: launch_one<BITS, 4>(L, planes, colsum, Y, p, s); break;
+        case 1: launch_one<BITS, 8>(L, planes, colsum, Y, p, s); break;
+        default: return APB_ERR_SHAPE;
+    }
+    return APB_OK;
 }
 
 }  // namespace
@@ -200,12 +235,8 @@ int launch_sparse_epilogue(const LayerDev& L, const uint32_t* planes, const int3
     const long long blocks = (long long)p.row_groups * (Mp / kWave);
     if (blocks > 0x7fffffffLL) return APB_ERR_SHAPE;
     p.blocks = (int)blocks;
-    const dim3 grid((unsigned)blocks), block(kWave * L.waves);
-#define APB_SPARSE(B)                                                                                       \
-    hipLaunchKernelGGL(k_sparse_epilogue<B>, grid, block, 2 * kTableBytes, s, planes, colsum, L.rowsum, L.perm, \
-                       L.seg_ptr, L.ent_key, L.ent_val, L.slot_valsum, Y, p)
-    if (bits == 1) APB_SPARSE(1); else APB_SPARSE(2);
-#undef APB_SPARSE
+    const int rc = bits == 1 ? launch_bits<1>(L, planes, colsum, Y, p, s) : launch_bits<2>(L, planes, colsum, Y, p, s);
+    if (rc != APB_OK) return rc;
     APB_HIP(hipGetLastError());
     return APB_OK;
 }
