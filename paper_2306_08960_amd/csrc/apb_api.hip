@@ -84,7 +84,7 @@ void build_tile_runs(const std::vector<int32_t>& perm, const std::vector<int32_t
                 const int end = row_ptr[n + 1];
                 while (cursor[r] < end && col[cursor[r]] < hi) {
                     key.push_back((uint32_t)(2 * r) | ((uint32_t)(col[cursor[r]] - c * kChunkK) << 8));
-                    dval.push_back((double)val[cursor[r]]);
+                    dval.push_back(std::ldexp((double)val[cursor[r]], kEntValScaleLog2));
                     ++cursor[r];
                 }
             }

@@ -13,6 +13,9 @@ constexpr int kRowTile = 16;     // weight rows one wave keeps in registers in t
 constexpr int kChunkWords = 8;   // K is walked in chunks of 8 words = 256 weights (one LDS code table each)
 constexpr int kChunkK = 32 * kChunkWords;
 constexpr int kMaxWavesPerBlock = 8;
+// ent_val holds residual * 2^895: finite for every float, and large enough that the sparse kernel's
+// table codes (code * 2^-1009, see apb_sparse.hip) give products far from underflow.
+constexpr int kEntValScaleLog2 = 895;
 
 struct LayerDev {
     int N = 0, K = 0, Kw = 0;    // Kw = ceil(K/32)
@@ -37,7 +40,7 @@ struct LayerDev {
     // 256 columns), sorted by row inside the run.
     int32_t* seg_ptr = nullptr;    // [Np/kRowTile][nchunks+1]  first entry of (tile, chunk)
     uint32_t* ent_key = nullptr;   // [entries]  2 * row_in_tile | (col - 256*chunk) << 8
-    double* ent_val = nullptr;     // [entries]  residual widened to float64 (exact); 0 for padding
+    double* ent_val = nullptr;     // [entries]  residual * 2^kEntValScaleLog2 in float64 (exact); 0 for padding
 };
 
 void set_last_hip_error(hipError_t e);

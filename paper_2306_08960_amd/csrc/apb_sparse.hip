@@ -42,6 +42,16 @@ struct SparseParams {
 // Spread the 4 low bits of `nib` to the least significant bits of the 4 bytes of a word.
 __device__ __forceinline__ uint32_t spread4(uint32_t nib) { return (nib * 0x00204081u) & 0x01010101u; }
 
+// A table byte is bits 55..48 of a float64 whose other bits are zero: exponent field in the high
+// nibble, top of the mantissa in the low one.  Codes 0,1,2,3 map to 0x00, 0xE0, 0xF0, 0xF8, i.e. to
+// the (normal) numbers code * 2^-1009, so a byte loaded into the upper half of the high register of
+// a zeroed pair IS the multiplicand -- no integer-to-float conversion per residual.  The residuals
+// are stored times 2^895 (finite for every float) and the row sums are multiplied by 2^114 at the
+// end; powers of two commute with rounding, so the sums are those of the unscaled arithmetic.
+constexpr uint32_t kCodeBytes = 0xF8F0E000u;
+static_assert(kEntValScaleLog2 == 895, "kSumUnscale undoes 2^895 * 2^-1009");
+constexpr double kSumUnscale = 0x1p114;
+
 template <int BITS>
 __device__ __forceinline__ void expand_word(uint32_t x0, uint32_t x1, uint8_t* dst_bytes) {
     uint32_t* dst = reinterpret_cast<uint32_t*>(dst_bytes);
@@ -49,77 +59,88 @@ __device__ __forceinline__ void expand_word(uint32_t x0, uint32_t x1, uint8_t* d
     for (int i = 0; i < 8; ++i) {
         uint32_t t = spread4((x0 >> (4 * i)) & 0xFu);
         if (BITS == 2) t |= spread4((x1 >> (4 * i)) & 0xFu) << 1;
-        dst[i] = t;                                             // bytes: codes of k = 32*j + 4*i + 0..3
+        // bytes of t: codes of k = 32*j + 4*i + 0..3; each selects its byte of kCodeBytes
+        dst[i] = __builtin_amdgcn_perm(0u, kCodeBytes, t);
     }
 }
 
 typedef double v16d __attribute__((ext_vector_type(TN)));
+typedef double v8d __attribute__((ext_vector_type(8)));
 
-// acc[key_i.byte0 / 2] += v_i * c_i for 8 entries.  `acc` is pinned to v[0:31]; while the
-// register-index mode is on (destination and third source relative), v[0:1] + M0[7:0] names the
-// pair of the entry's row.  s_set_gpr_idx_on / _idx copy the low byte of a key to M0[7:0]; only the
-// multiply-adds sit inside the indexed region, and the mode is off again when the statement ends.
-__device__ __forceinline__ void accumulate8(v16d& acc, const uint32_t* k, const double* v, const double* c) {
+// Eight residuals: acc[key_i.byte0 / 2] += v_i * table[key_i.byte1].
+// `acc` is pinned to v[0:31] and `pairs` (eight zeroed register pairs) to v[32:47].  Per entry: the
+// byte address (table row of this lane + byte 1 of the key), a byte read into bits 31..16 of the
+// pair's high register (the low halves stay zero), and, once the reads have landed, one v_fma_f64
+// whose destination and addend are v[0:1] displaced by M0[7:0] = low byte of the key = 2*row.  Only
+// the multiply-adds sit inside the indexed region; the mode is off again when the statement ends.
+// The wait is for everything (lgkmcnt(0)): scalar loads in flight share the counter and may return
+// out of order, so no smaller count would prove that the table reads are back.
+__device__ __forceinline__ void accumulate8(v16d& acc, v8d& pairs, const uint32_t* k, const double* v,
+                                            uint32_t table_off) {
+    uint32_t t0, t1;
+#define APB_SDWA " dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1 src1_sel:DWORD\n\t"
     asm volatile(
-        "s_set_gpr_idx_on %1, gpr_idx(SRC2,DST)\n\t"
-        "v_fma_f64 v[0:1], %9, %17, v[0:1]\n\t"
-        "s_set_gpr_idx_idx %2\n\t"
-        "v_fma_f64 v[0:1], %10, %18, v[0:1]\n\t"
-        "s_set_gpr_idx_idx %3\n\t"
-        "v_fma_f64 v[0:1], %11, %19, v[0:1]\n\t"
-        "s_set_gpr_idx_idx %4\n\t"
-        "v_fma_f64 v[0:1], %12, %20, v[0:1]\n\t"
+        "v_add_u32_sdwa %2, %4, %20" APB_SDWA "ds_read_u8_d16_hi v33, %2\n\t"
+        "v_add_u32_sdwa %3, %5, %20" APB_SDWA "ds_read_u8_d16_hi v35, %3\n\t"
+        "v_add_u32_sdwa %2, %6, %20" APB_SDWA "ds_read_u8_d16_hi v37, %2\n\t"
+        "v_add_u32_sdwa %3, %7, %20" APB_SDWA "ds_read_u8_d16_hi v39, %3\n\t"
+        "v_add_u32_sdwa %2, %8, %20" APB_SDWA "ds_read_u8_d16_hi v41, %2\n\t"
+        "v_add_u32_sdwa %3, %9, %20" APB_SDWA "ds_read_u8_d16_hi v43, %3\n\t"
+        "v_add_u32_sdwa %2, %10, %20" APB_SDWA "ds_read_u8_d16_hi v45, %2\n\t"
+        "v_add_u32_sdwa %3, %11, %20" APB_SDWA "ds_read_u8_d16_hi v47, %3\n\t"
+        "s_waitcnt lgkmcnt(0)\n\t"
+        "s_set_gpr_idx_on %4, gpr_idx(SRC2,DST)\n\t"
+        "v_fma_f64 v[0:1], %12, v[32:33], v[0:1]\n\t"
         "s_set_gpr_idx_idx %5\n\t"
-        "v_fma_f64 v[0:1], %13, %21, v[0:1]\n\t"
+        "v_fma_f64 v[0:1], %13, v[34:35], v[0:1]\n\t"
         "s_set_gpr_idx_idx %6\n\t"
-        "v_fma_f64 v[0:1], %14, %22, v[0:1]\n\t"
+        "v_fma_f64 v[0:1], %14, v[36:37], v[0:1]\n\t"
         "s_set_gpr_idx_idx %7\n\t"
-        "v_fma_f64 v[0:1], %15, %23, v[0:1]\n\t"
+        "v_fma_f64 v[0:1], %15, v[38:39], v[0:1]\n\t"
         "s_set_gpr_idx_idx %8\n\t"
-        "v_fma_f64 v[0:1], %16, %24, v[0:1]\n\t"
+        "v_fma_f64 v[0:1], %16, v[40:41], v[0:1]\n\t"
+        "s_set_gpr_idx_idx %9\n\t"
+        "v_fma_f64 v[0:1], %17, v[42:43], v[0:1]\n\t"
+        "s_set_gpr_idx_idx %10\n\t"
+        "v_fma_f64 v[0:1], %18, v[44:45], v[0:1]\n\t"
+        "s_set_gpr_idx_idx %11\n\t"
+        "v_fma_f64 v[0:1], %19, v[46:47], v[0:1]\n\t"
         "s_set_gpr_idx_off"
-        : "+{v[0:31]}"(acc)
+        : "+{v[0:31]}"(acc), "+{v[32:47]}"(pairs), "=&v"(t0), "=&v"(t1)
         : "s"(k[0]), "s"(k[1]), "s"(k[2]), "s"(k[3]), "s"(k[4]), "s"(k[5]), "s"(k[6]), "s"(k[7]),
           "s"(v[0]), "s"(v[1]), "s"(v[2]), "s"(v[3]), "s"(v[4]), "s"(v[5]), "s"(v[6]), "s"(v[7]),
-          "v"(c[0]), "v"(c[1]), "v"(c[2]), "v"(c[3]), "v"(c[4]), "v"(c[5]), "v"(c[6]), "v"(c[7]));
+          "v"(table_off)
+        : "memory");
+#undef APB_SDWA
 }
 
-// One batch of NB (8 or 16) entries starting at e: scalar loads of keys and values, then per entry
-// address add, table read and convert, then the indexed multiply-adds.
+// One batch of NB (8 or 16) entries starting at e: scalar loads of keys and values, then the
+// multiply-adds eight at a time.
 template <int NB>
-__device__ __forceinline__ void batch(v16d& acc, const uint32_t* __restrict__ ent_key,
+__device__ __forceinline__ void batch(v16d& acc, v8d& pairs, const uint32_t* __restrict__ ent_key,
                                       const double* __restrict__ ent_val, int e, uint32_t table_off) {
     uint32_t k[NB];
-    double v[NB], c[NB];
+    double v[NB];
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
         k[i] = ent_key[e + i];
         v[i] = ent_val[e + i];
     }
 #pragma unroll
-    for (int i = 0; i < NB; ++i) {
-        uint32_t off;                                           // table row of this lane + column (key byte 1)
-        asm("v_add_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1 src1_sel:DWORD"
-            : "=v"(off)
-            : "s"(k[i]), "v"(table_off));
-        uint32_t code = *reinterpret_cast<const lds_u8*>(off);
-        asm("" : "+v"(code));                                   // keep it a plain zero-extending byte read
-        c[i] = (double)code;
-    }
-#pragma unroll
-    for (int i = 0; i < NB; i += 8) accumulate8(acc, k + i, v + i, c + i);
+    for (int h = 0; h < NB; h += 8) accumulate8(acc, pairs, k + h, v + h, table_off);
 }
 
 // WPW = words of a chunk each wave expands = 8 / waves per workgroup.
 template <int BITS, int WPW>
-__global__ __launch_bounds__(kWave* kChunkWords / WPW) void k_sparse_epilogue(
+__global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_waves_per_eu(WPW <= 2 ? 8 : 4, 8))) void k_sparse_epilogue(
     // Separate restrict-qualified arguments (not struct members) so that the compiler knows the
     // read-only arrays cannot alias Y and keeps the wave-uniform loads on the scalar path.
     const uint32_t* __restrict__ planes, const int32_t* __restrict__ colsum, const int32_t* __restrict__ rowsum,
     const int32_t* __restrict__ perm,
     const int32_t* __restrict__ seg_ptr,     // [tiles][nchunks+1] first entry of (tile, chunk)
     const uint32_t* __restrict__ ent_key,    // 2 * row_in_tile | col_local << 8
-    const double* __restrict__ ent_val, const double* __restrict__ slot_valsum,
+    const double* __restrict__ ent_val,      // residual * 2^895
+    const double* __restrict__ slot_valsum,
     float* Y,                                // holds P (int32 bits) on entry, Y on exit
     const SparseParams p) {
     extern __shared__ __align__(16) uint8_t lds[];
@@ -136,12 +157,14 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) void k_sparse_epilogue(
     const int tile = rg * waves + wave;
     const int slot0 = tile * TN;
     const int m = strip * kWave + lane;                         // < Mp: the strips tile Mp exactly
-    const uint32_t* xp = planes + m;
 
     static_assert(TN == 16, "row field of an entry key addresses 16 register pairs");
     v16d acc;
 #pragma unroll
     for (int r = 0; r < TN; ++r) acc[r] = 0.0;
+    v8d pairs;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) pairs[r] = 0.0;
 
     const size_t plane_stride = (size_t)p.Kw * p.Mp;
     uint8_t* my_row = lds + lane * kTablePitch;
@@ -156,7 +179,12 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) void k_sparse_epilogue(
         for (int i = 0; i < WPW; ++i) {
             const int j = c * kChunkWords + wave + i * waves;
 #pragma unroll
-            for (int b = 0; b < BITS; ++b) xw[b][i] = j < p.Kw ? xp[b * plane_stride + (size_t)j * p.Mp] : 0u;
+            for (int b = 0; b < BITS; ++b) {
+                // wave-uniform row pointer (scalar registers) + the lane's column
+                const uint32_t* row = planes + (b * plane_stride + (size_t)min(j, p.Kw - 1) * p.Mp);
+                const uint32_t w = row[m];
+                xw[b][i] = j < p.Kw ? w : 0u;
+            }
         }
     };
     fetch(0);
@@ -175,8 +203,8 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) void k_sparse_epilogue(
         // Whole batches only: 16 entries per scalar-load round trip while they last, then at most one
         // batch of 8.  A large batch is what amortises the scalar-cache latency.
         const uint32_t table_off = my_row_off + buf;
-        for (; e + 16 <= e1; e += 16) batch<16>(acc, ent_key, ent_val, e, table_off);
-        if (e < e1) batch<8>(acc, ent_key, ent_val, e, table_off);
+        for (; e + 16 <= e1; e += 16) batch<16>(acc, pairs, ent_key, ent_val, e, table_off);
+        if (e < e1) batch<8>(acc, pairs, ent_key, ent_val, e, table_off);
         // The next chunk writes the other table buffer; this one is rewritten two chunks from now,
         // after every wave has passed the next barrier, i.e. has finished reading it.
     }
@@ -191,7 +219,8 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) void k_sparse_epilogue(
         const int P = col_ok ? reinterpret_cast<const int32_t*>(Y)[(size_t)n * p.M + m] : 0;
         const int d = BITS == 1 ? 4 * P - rowsum[n] - 2 * cs : 2 * P - cs;
         // 1-bit activations: the table holds (c+1)/2 in {0,1}: sum val*c = 2*sum val*code - sum val.
-        const double sparse = BITS == 1 ? 2.0 * acc[r] - slot_valsum[slot0 + r] : acc[r];
+        const double sum = acc[r] * kSumUnscale;
+        const double sparse = BITS == 1 ? 2.0 * sum - slot_valsum[slot0 + r] : sum;
         const double y = fma(p.alpha, (double)d, sparse) * p.step;
         if (col_ok) Y[(size_t)n * p.M + m] = (float)y;
     }
