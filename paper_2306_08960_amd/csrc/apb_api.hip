@@ -19,7 +19,7 @@ hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 void free_layer_buffers(LayerDev& d) {
     void* ptrs[] = {d.sign, d.signT, d.perm, d.row_ptr, d.col_idx, d.val, d.rowsum, d.chunk_ptr, d.slot_valsum, d.vald, d.signC,
-                    d.seg_ptr, d.ent_key, d.ent_val};
+                    d.seg_ptr, d.ent};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     d = LayerDev{};
@@ -58,26 +58,29 @@ std::vector<int32_t> balanced_slots(const std::vector<int32_t>& counts, int Np) 
 }
 
 // Regroup the CSR for the sparse kernel: for every tile of kRowTile launch slots and every chunk of
-// kChunkK columns one flat run of entries, sorted by (row in tile, column).  The last entry of each
-// row's part of a run carries a flag so the kernel knows when to retire its partial sum.
+// kChunkK columns one flat run of entries, sorted by (row in tile, column) and padded to whole
+// blocks of 8.  A block is 24 words: 8 keys (2*row | column_in_chunk << 8), then the 8 residuals as
+// float64 times 2^kEntValScaleLog2; padding entries have key 0 and value 0.  seg_ptr counts blocks.
 void build_tile_runs(const std::vector<int32_t>& perm, const std::vector<int32_t>& row_ptr,
                      const std::vector<int32_t>& col, const std::vector<float>& val, int nchunks,
-                     std::vector<int32_t>& seg_ptr, std::vector<uint32_t>& key, std::vector<double>& dval) {
+                     std::vector<int32_t>& seg_ptr, std::vector<uint32_t>& ent) {
     const int tiles = (int)perm.size() / kRowTile;
     seg_ptr.assign((size_t)tiles * (nchunks + 1), 0);
-    key.clear();
-    dval.clear();
-    key.reserve(col.size());
-    dval.reserve(col.size());
+    ent.clear();
+    ent.reserve(col.size() * 3 + 24);
     std::vector<int32_t> cursor(kRowTile);
+    std::vector<uint32_t> key;
+    std::vector<double> dval;
     for (int t = 0; t < tiles; ++t) {
         for (int r = 0; r < kRowTile; ++r) {
             const int n = perm[(size_t)t * kRowTile + r];
             cursor[r] = n >= 0 ? row_ptr[n] : 0;
         }
         for (int c = 0; c < nchunks; ++c) {
-            seg_ptr[(size_t)t * (nchunks + 1) + c] = (int32_t)key.size();
+            seg_ptr[(size_t)t * (nchunks + 1) + c] = (int32_t)(ent.size() / kEntBlockWords);
             const int hi = (c + 1) * kChunkK;
+            key.clear();
+            dval.clear();
             for (int r = 0; r < kRowTile; ++r) {
                 const int n = perm[(size_t)t * kRowTile + r];
                 if (n < 0) continue;
@@ -88,12 +91,18 @@ void build_tile_runs(const std::vector<int32_t>& perm, const std::vector<int32_t
                     ++cursor[r];
                 }
             }
-            while ((key.size() - (size_t)seg_ptr[(size_t)t * (nchunks + 1) + c]) % 8 != 0) {
-                key.push_back(0u);                              // padding: row 0, column 0, value 0
+            while (key.size() % 8 != 0) {
+                key.push_back(0u);
                 dval.push_back(0.0);
             }
+            for (size_t b = 0; b < key.size(); b += 8) {
+                const size_t at = ent.size();
+                ent.resize(at + kEntBlockWords);
+                std::memcpy(&ent[at], &key[b], 8 * sizeof(uint32_t));
+                std::memcpy(&ent[at + 8], &dval[b], 8 * sizeof(double));
+            }
         }
-        seg_ptr[(size_t)t * (nchunks + 1) + nchunks] = (int32_t)key.size();
+        seg_ptr[(size_t)t * (nchunks + 1) + nchunks] = (int32_t)(ent.size() / kEntBlockWords);
     }
 }
 
@@ -188,17 +197,13 @@ int compress_impl(const float* W, int N, int K, float delta, float alpha, hipStr
     }
     APB_HIP(hipStreamSynchronize(s));
     std::vector<int32_t> hseg;
-    std::vector<uint32_t> hkey;
-    std::vector<double> hdval;
-    build_tile_runs(hperm, hrow_ptr, hcol, hval, d.nchunks, hseg, hkey, hdval);
+    std::vector<uint32_t> hent;
+    build_tile_runs(hperm, hrow_ptr, hcol, hval, d.nchunks, hseg, hent);
     if ((rc = dev_alloc(&d.seg_ptr, hseg.size())) != APB_OK) return rc;
-    if ((rc = dev_alloc(&d.ent_key, hkey.size())) != APB_OK) return rc;
-    if ((rc = dev_alloc(&d.ent_val, hdval.size())) != APB_OK) return rc;
+    if ((rc = dev_alloc(&d.ent, hent.size())) != APB_OK) return rc;
     APB_HIP(hipMemcpyAsync(d.seg_ptr, hseg.data(), hseg.size() * sizeof(int32_t), hipMemcpyHostToDevice, s));
-    if (!hkey.empty()) {
-        APB_HIP(hipMemcpyAsync(d.ent_key, hkey.data(), hkey.size() * sizeof(uint32_t), hipMemcpyHostToDevice, s));
-        APB_HIP(hipMemcpyAsync(d.ent_val, hdval.data(), hdval.size() * sizeof(double), hipMemcpyHostToDevice, s));
-    }
+    if (!hent.empty())
+        APB_HIP(hipMemcpyAsync(d.ent, hent.data(), hent.size() * sizeof(uint32_t), hipMemcpyHostToDevice, s));
     APB_HIP(hipStreamSynchronize(s));                 // host staging vectors go out of scope after this
     return APB_OK;
 }

@@ -16,6 +16,7 @@ constexpr int kMaxWavesPerBlock = 8;
 // ent_val holds residual * 2^895: finite for every float, and large enough that the sparse kernel's
 // table codes (code * 2^-1009, see apb_sparse.hip) give products far from underflow.
 constexpr int kEntValScaleLog2 = 895;
+constexpr int kEntBlockWords = 24;   // one block of 8 residual entries: 8 key words + 8 float64
 
 struct LayerDev {
     int N = 0, K = 0, Kw = 0;    // Kw = ceil(K/32)
@@ -37,10 +38,10 @@ struct LayerDev {
     int32_t* chunk_ptr = nullptr;  // [nchunks+1][Np]  first residual of slot i with column >= 256*c
     double* slot_valsum = nullptr; // [Np]             sum of the residuals of slot i (float64)
     // Residuals regrouped for the sparse kernel: one flat run per (tile of kRowTile slots, chunk of
-    // 256 columns), sorted by row inside the run.
-    int32_t* seg_ptr = nullptr;    // [Np/kRowTile][nchunks+1]  first entry of (tile, chunk)
-    uint32_t* ent_key = nullptr;   // [entries]  2 * row_in_tile | (col - 256*chunk) << 8
-    double* ent_val = nullptr;     // [entries]  residual * 2^kEntValScaleLog2 in float64 (exact); 0 for padding
+    // 256 columns), sorted by row inside the run, in blocks of 8 entries.
+    int32_t* seg_ptr = nullptr;    // [Np/kRowTile][nchunks+1]  first block of (tile, chunk)
+    uint32_t* ent = nullptr;       // [blocks][24]  8 keys: 2 * row_in_tile | (col - 256*chunk) << 8, then
+                                   //               8 float64: residual * 2^kEntValScaleLog2 (0 for padding)
 };
 
 void set_last_hip_error(hipError_t e);

@@ -11,7 +11,7 @@
 //      LDS (row = output column, 256 codes + 4 pad bytes, so the 64 lanes of a wave hit distinct
 //      banks when they read the same k);
 //   2. after a barrier each wave streams the residuals of its 16 rows that fall in the chunk.  They
-//      were laid out at compress time as ONE flat run per (tile, chunk), padded to whole batches of
+//      were laid out at compress time as ONE flat run per (tile, chunk), padded to whole blocks of
 //      8, so the loop has no per-row work at all.  The 16 float64 row sums of a lane live in 32
 //      consecutive vector registers, and the multiply-add of a residual addresses its row's pair
 //      through the register-index mode: one scalar instruction (index <- low byte of the entry
@@ -31,6 +31,8 @@ constexpr int kTablePitch = kChunkK + 4;                       // bytes per colu
 constexpr int kTableBytes = kWave * kTablePitch;               // one buffer; two are used alternately
 
 typedef __attribute__((address_space(3))) uint8_t lds_u8;
+
+__host__ __device__ constexpr int table_buffers(int wpw) { return wpw == 1 ? 2 : 1; }
 
 struct SparseParams {
     double alpha, step;
@@ -114,20 +116,23 @@ __device__ __forceinline__ void accumulate8(v16d& acc, v8d& pairs, const uint32_
 #undef APB_SDWA
 }
 
-// One batch of NB (8 or 16) entries starting at e: scalar loads of keys and values, then the
-// multiply-adds eight at a time.
+// NB (1 or 2) blocks of 8 entries starting at block b.  Keys and values of a block sit side by side,
+// so all the scalar loads of a batch leave together and cost one round trip.
 template <int NB>
-__device__ __forceinline__ void batch(v16d& acc, v8d& pairs, const uint32_t* __restrict__ ent_key,
-                                      const double* __restrict__ ent_val, int e, uint32_t table_off) {
-    uint32_t k[NB];
-    double v[NB];
+__device__ __forceinline__ void batch(v16d& acc, v8d& pairs, const uint32_t* __restrict__ ent, int b,
+                                      uint32_t table_off) {
+    uint32_t k[NB][8];
+    double v[NB][8];
+    const uint32_t* blk = ent + (size_t)b * kEntBlockWords;
 #pragma unroll
-    for (int i = 0; i < NB; ++i) {
-        k[i] = ent_key[e + i];
-        v[i] = ent_val[e + i];
+    for (int h = 0; h < NB; ++h) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) k[h][i] = blk[h * kEntBlockWords + i];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[h][i] = reinterpret_cast<const double*>(blk + h * kEntBlockWords + 8)[i];
     }
 #pragma unroll
-    for (int h = 0; h < NB; h += 8) accumulate8(acc, pairs, k + h, v + h, table_off);
+    for (int h = 0; h < NB; ++h) accumulate8(acc, pairs, k[h], v[h], table_off);
 }
 
 // WPW = words of a chunk each wave expands = 8 / waves per workgroup.
@@ -137,14 +142,14 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
     // read-only arrays cannot alias Y and keeps the wave-uniform loads on the scalar path.
     const uint32_t* __restrict__ planes, const int32_t* __restrict__ colsum, const int32_t* __restrict__ rowsum,
     const int32_t* __restrict__ perm,
-    const int32_t* __restrict__ seg_ptr,     // [tiles][nchunks+1] first entry of (tile, chunk)
-    const uint32_t* __restrict__ ent_key,    // 2 * row_in_tile | col_local << 8
-    const double* __restrict__ ent_val,      // residual * 2^895
+    const int32_t* __restrict__ seg_ptr,     // [tiles][nchunks+1] first entry block of (tile, chunk)
+    const uint32_t* __restrict__ ent,        // blocks of 8 keys + 8 scaled residuals
     const double* __restrict__ slot_valsum,
     float* Y,                                // holds P (int32 bits) on entry, Y on exit
     const SparseParams p) {
     extern __shared__ __align__(16) uint8_t lds[];
     constexpr int waves = kChunkWords / WPW;
+    constexpr int kBufs = table_buffers(WPW);
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
 
@@ -191,7 +196,10 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
     int e1 = seg[0];
 
     for (int c = 0; c < p.nchunks; ++c) {
-        const int buf = (c & 1) * kTableBytes;
+        // Large workgroups alternate between two table buffers (one barrier per chunk); small ones keep
+        // one buffer, so that twice as many of them fit a CU, and pay a second barrier.
+        const int buf = kBufs == 2 ? (c & 1) * kTableBytes : 0;
+        if (kBufs == 1 && c > 0) __syncthreads();               // every wave has finished reading the table
 #pragma unroll
         for (int i = 0; i < WPW; ++i)
             expand_word<BITS>(xw[0][i], xw[BITS - 1][i], my_row + buf + 32 * (wave + i * waves));
@@ -200,29 +208,36 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
         e1 = seg[c + 1];
         __syncthreads();                                        // the chunk's code table is complete
 
-        // Whole batches only: 16 entries per scalar-load round trip while they last, then at most one
-        // batch of 8.  A large batch is what amortises the scalar-cache latency.
+        // Two blocks (16 entries) per scalar-load round trip while they last, then at most one block.
+        // A large batch is what amortises the scalar-cache latency.
         const uint32_t table_off = my_row_off + buf;
-        for (; e + 16 <= e1; e += 16) batch<16>(acc, pairs, ent_key, ent_val, e, table_off);
-        if (e < e1) batch<8>(acc, pairs, ent_key, ent_val, e, table_off);
-        // The next chunk writes the other table buffer; this one is rewritten two chunks from now,
-        // after every wave has passed the next barrier, i.e. has finished reading it.
+        for (; e + 2 <= e1; e += 2) batch<2>(acc, pairs, ent, e, table_off);
+        if (e < e1) batch<1>(acc, pairs, ent, e, table_off);
+        // With two buffers the next chunk writes the other one; this one is rewritten two chunks from
+        // now, after every wave has passed the next barrier, i.e. has finished reading it.
     }
 
+    // Epilogue.  Everything is read before anything is written: row numbers, then the 16 raw products
+    // of this lane in one volley (rows of padding slots and columns past M re-read a valid element
+    // instead of branching), then the arithmetic and the stores.
     const bool col_ok = m < p.M;
+    const int mc = min(m, p.M - 1);
     const int cs = colsum[m];
+    int n[TN], P[TN];
+#pragma unroll
+    for (int r = 0; r < TN; ++r) n[r] = perm[slot0 + r];
+#pragma unroll
+    for (int r = 0; r < TN; ++r)
+        P[r] = reinterpret_cast<const int32_t*>(Y)[(size_t)max(n[r], 0) * p.M + mc];
 #pragma unroll
     for (int r = 0; r < TN; ++r) {
-        const int n = perm[slot0 + r];
-        if (n < 0) continue;
         // raw matrix-core product P = sum_k b*code  ->  D (b = sign bit, code = stored code)
-        const int P = col_ok ? reinterpret_cast<const int32_t*>(Y)[(size_t)n * p.M + m] : 0;
-        const int d = BITS == 1 ? 4 * P - rowsum[n] - 2 * cs : 2 * P - cs;
+        const int d = BITS == 1 ? 4 * P[r] - rowsum[max(n[r], 0)] - 2 * cs : 2 * P[r] - cs;
         // 1-bit activations: the table holds (c+1)/2 in {0,1}: sum val*c = 2*sum val*code - sum val.
         const double sum = acc[r] * kSumUnscale;
         const double sparse = BITS == 1 ? 2.0 * sum - slot_valsum[slot0 + r] : sum;
         const double y = fma(p.alpha, (double)d, sparse) * p.step;
-        if (col_ok) Y[(size_t)n * p.M + m] = (float)y;
+        if (col_ok && n[r] >= 0) Y[(size_t)n[r] * p.M + m] = (float)y;
     }
 }
 
@@ -230,7 +245,7 @@ template <int BITS, int WPW>
 void launch_one(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, float* Y, const SparseParams& p,
                 hipStream_t s) {
     hipLaunchKernelGGL((k_sparse_epilogue<BITS, WPW>), dim3((unsigned)p.blocks), dim3(kWave * kChunkWords / WPW),
-                       2 * kTableBytes, s, planes, colsum, L.rowsum, L.perm, L.seg_ptr, L.ent_key, L.ent_val,
+                       table_buffers(WPW) * kTableBytes, s, planes, colsum, L.rowsum, L.perm, L.seg_ptr, L.ent,
                        L.slot_valsum, Y, p);
 }
 
