@@ -32,6 +32,9 @@ constexpr int kTableBytes = kWave * kTablePitch;               // one buffer; tw
 
 typedef __attribute__((address_space(3))) uint8_t lds_u8;
 
+// Fourth word of a raw buffer descriptor on gfx9-family parts: 32-bit data format, no swizzle.
+constexpr int kBufferFlags = 0x00020000;
+
 __host__ __device__ constexpr int table_buffers(int wpw) { return wpw == 1 ? 2 : 1; }
 
 struct SparseParams {
@@ -162,6 +165,7 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
     const int tile = rg * waves + wave;
     const int slot0 = tile * TN;
     const int m = strip * kWave + lane;                         // < Mp: the strips tile Mp exactly
+    const int m_off = m * 4;                                    // the launcher keeps 4 * Mp below 2^31
 
     static_assert(TN == 16, "row field of an entry key addresses 16 register pairs");
     v16d acc;
@@ -185,10 +189,14 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
             const int j = c * kChunkWords + wave + i * waves;
 #pragma unroll
             for (int b = 0; b < BITS; ++b) {
-                // wave-uniform row pointer (scalar registers) + the lane's column
+                // Buffer load: the descriptor carries the wave-uniform row (scalar registers, range =
+                // one row of Mp words), the lane adds its 32-bit byte offset.  Words past Kw re-read
+                // the last row: their codes land in table columns >= K, which no residual refers to,
+                // and leaving them unmasked keeps the wait for the load at the next chunk.
                 const uint32_t* row = planes + (b * plane_stride + (size_t)min(j, p.Kw - 1) * p.Mp);
-                const uint32_t w = row[m];
-                xw[b][i] = j < p.Kw ? w : 0u;
+                const __amdgpu_buffer_rsrc_t rsrc =
+                    __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(row), 0, p.Mp * 4, kBufferFlags);
+                xw[b][i] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, m_off, 0, 0);
             }
         }
     };
@@ -220,9 +228,12 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
     // Epilogue.  Everything is read before anything is written: row numbers, then the 16 raw products
     // of this lane in one volley (rows of padding slots and columns past M re-read a valid element
     // instead of branching), then the arithmetic and the stores.
-    const bool col_ok = m < p.M;
-    const int mc = min(m, p.M - 1);
-    const int cs = colsum[m];
+    // (The column is recomputed from the lane number here rather than kept in a register -- or
+    // spilled -- through the loops above.)
+    const int m_e = strip * kWave + (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    const bool col_ok = m_e < p.M;
+    const int mc = min(m_e, p.M - 1);
+    const int cs = colsum[m_e];
     int n[TN], P[TN];
 #pragma unroll
     for (int r = 0; r < TN; ++r) n[r] = perm[slot0 + r];
@@ -237,7 +248,7 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
         const double sum = acc[r] * kSumUnscale;
         const double sparse = BITS == 1 ? 2.0 * sum - slot_valsum[slot0 + r] : sum;
         const double y = fma(p.alpha, (double)d, sparse) * p.step;
-        if (col_ok && n[r] >= 0) Y[(size_t)n[r] * p.M + m] = (float)y;
+        if (col_ok && n[r] >= 0) Y[(size_t)n[r] * p.M + m_e] = (float)y;
     }
 }
 
@@ -277,7 +288,7 @@ int launch_sparse_epilogue(const LayerDev& L, const uint32_t* planes, const int3
     p.nchunks = L.nchunks;
     p.row_groups = L.Np / (TN * L.waves);
     const long long blocks = (long long)p.row_groups * (Mp / kWave);
-    if (blocks > 0x7fffffffLL) return APB_ERR_SHAPE;
+    if (blocks > 0x7fffffffLL || (long long)Mp * 4 >= (1LL << 31)) return APB_ERR_SHAPE;
     p.blocks = (int)blocks;
     const int rc = bits == 1 ? launch_bits<1>(L, planes, colsum, Y, p, s) : launch_bits<2>(L, planes, colsum, Y, p, s);
     if (rc != APB_OK) return rc;
