@@ -2,12 +2,12 @@
 """Benchmark of the APB layer forward pass on one MI355X.
 
 One "step" = the whole per-batch hot path on inputs already resident in HBM:
-apb_quantize_acts (quantize + bit-plane packing) followed by apb_forward (popcount GEMM +
-CSR part + epilogue).  apb_compress is per-layer offline work and is not timed.
+apb_quantize_acts (quantize + bit-plane packing) followed by apb_forward (binary product on the
+matrix cores, then CSR part + epilogue).  apb_compress is per-layer offline work and is not timed.
 
 Prints ONE JSON line.  `value` is (2*N*K*M + 2*nnz*M) / step time, in GOPS, for the workload
 named in config.workload; `roofline` describes the kernel that dominates the step and
-`roofline_forward` the forward kernel; `cpu_baseline` is the CPU oracle timed on a bounded
+`roofline_forward` the two forward kernels together; `cpu_baseline` is the CPU oracle timed on a bounded
 column sample of the same workload on this machine's host cores.
 """
 from __future__ import annotations
@@ -24,8 +24,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0                  # MI355X HBM3E, published
-CUS, CLOCK_GHZ, LANES_PER_CU_CLK = 256, 2.4, 64
-VALU_LANE_OPS_PER_S = CUS * LANES_PER_CU_CLK * CLOCK_GHZ * 1e9     # 39.3e12 32-bit lane-ops/s
+MFMA_FP4_PEAK_TFLOPS = 10100.0         # dense FP4 MFMA, published
+FP64_VECTOR_PEAK_TFLOPS = 78.6         # 256 CUs x 64 lanes x 2.4 GHz x 2 (fused multiply-add)
+
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# calibrated against a plain copy of known size (profiles/traffic_C2_pmc.txt says how).
+MEASURED_TRAFFIC_BYTES = {("C2", "k_quantize_pack"): 321.5e6}
 
 
 def parse_args():
@@ -50,13 +54,6 @@ def time_events(fn, iters):
     stop.record()
     stop.synchronize()
     return start.elapsed_time(stop) / iters          # ms per launch, on the stream the kernels run on
-
-
-def forward_lane_ops(N, K, M, bits, nnz):
-    """Algorithmic 32-bit VALU lane-ops of the forward kernel: per weight word, plane and column one
-    logic op + one popcount-accumulate; per residual and column one fused multiply-add."""
-    Kw = (K + 31) // 32
-    return 2.0 * bits * N * Kw * M + float(nnz) * M
 
 
 def run_workload(name, steps, warmup):
@@ -99,17 +96,31 @@ def run_workload(name, steps, warmup):
 
     ops = 2.0 * N * K * M + 2.0 * nnz * M
     Kw, Mp = (K + 31) // 32, 64 * ((M + 63) // 64)
+    # quantize: reads X once, writes the bit-planes and the column sums
     quant_bytes = 4.0 * K * M + 4.0 * bits * Kw * Mp + 4.0 * Mp
-    fwd_bytes = 4.0 * N * Kw + 4.0 * bits * Kw * Mp + 4.0 * Mp + 8.0 * nnz + 4.0 * (N + 1) + 4.0 * N * M
-    lane_ops = forward_lane_ops(N, K, M, bits, nnz)
-    fwd_peak_tops = ops / (lane_ops / VALU_LANE_OPS_PER_S) / 1e12
     roof_quant = {"kernel": "k_quantize_pack", "bound": "hbm", "achieved": quant_bytes / (ms_quant * 1e-3) / 1e9,
-                  "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": None, "ms": ms_quant}
+                  "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": MEASURED_TRAFFIC_BYTES.get((name, "k_quantize_pack")),
+                  "algorithmic_bytes": quant_bytes, "ms": ms_quant}
     roof_quant["frac"] = roof_quant["achieved"] / roof_quant["peak"]
-    roof_fwd = {"kernel": "k_forward_valu", "bound": "alu", "achieved": ops / (ms_fwd * 1e-3) / 1e12,
-                "peak": fwd_peak_tops, "unit": "TOP/s", "traffic": None, "ms": ms_fwd,
-                "hbm_frac": fwd_bytes / (ms_fwd * 1e-3) / 1e9 / HBM_PEAK_GBS}
-    roof_fwd["frac"] = roof_fwd["achieved"] / roof_fwd["peak"]
+    # forward = k_binary_mfma + k_sparse_epilogue.  Its floor is the largest of: the bytes it has to move
+    # (sign words, bit-planes, residual entries, Y), the FP4 matrix-core time of the binary product and
+    # the float64 vector time of the residual multiply-adds.
+    fwd_bytes = 4.0 * N * Kw + 4.0 * bits * Kw * Mp + 4.0 * Mp + 12.0 * nnz + 4.0 * N * M
+    t_hbm = fwd_bytes / (HBM_PEAK_GBS * 1e9)
+    t_mfma = 2.0 * N * K * M / (MFMA_FP4_PEAK_TFLOPS * 1e12)
+    t_f64 = 2.0 * nnz * M / (FP64_VECTOR_PEAK_TFLOPS * 1e12)
+    t_fwd = ms_fwd * 1e-3
+    if t_hbm >= max(t_mfma, t_f64):
+        roof_fwd = {"bound": "hbm", "achieved": fwd_bytes / t_fwd / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    elif t_mfma >= t_f64:
+        roof_fwd = {"bound": "mfma", "achieved": 2.0 * N * K * M / t_fwd / 1e12, "peak": MFMA_FP4_PEAK_TFLOPS,
+                    "unit": "TFLOP/s"}
+    else:
+        roof_fwd = {"bound": "alu", "achieved": 2.0 * nnz * M / t_fwd / 1e12, "peak": FP64_VECTOR_PEAK_TFLOPS,
+                    "unit": "TFLOP/s"}
+    roof_fwd = {"kernel": "k_binary_mfma + k_sparse_epilogue"} | roof_fwd
+    roof_fwd |= {"frac": roof_fwd["achieved"] / roof_fwd["peak"], "traffic": None, "ms": ms_fwd,
+                 "floor_us": {"hbm": t_hbm * 1e6, "mfma_fp4": t_mfma * 1e6, "fp64_vector": t_f64 * 1e6}}
     res = {
         "workload": name, "N": N, "K": K, "M": M, "act_bits": bits, "nnz": int(nnz),
         "ms_per_step": ms_step, "gops_step": ops / (ms_step * 1e-3) / 1e9,
@@ -167,7 +178,7 @@ def main():
         "metric": "APB layer forward GOPS (binary+sparse) and % of MI355X roofline",
         "value": res["gops_step"], "unit": "GOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u32 popcount + f64 accumulate (f32 in/out)", "data": "synthetic",
+        "dtype": "fp4 (exact 0/1 and 2-bit codes) on MFMA + f64 accumulate (f32 in/out)", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.note}", "N": cfg.N, "K": cfg.K, "M": cfg.M,
                    "act_bits": cfg.bits, "outlier_rate": cfg.rho, "nnz": res["nnz"],
                    "step": "apb_quantize_acts + apb_forward, inputs resident in HBM"},
@@ -187,7 +198,8 @@ def main():
             r, _ = run_workload(name, max(20, args.steps // 4), max(5, args.warmup // 4))
             others.append({k: r[k] for k in ("workload", "N", "K", "M", "act_bits", "nnz", "ms_per_step", "gops_step",
                                              "ms_quantize", "ms_forward", "gops_forward")}
-                          | {"forward_frac_of_valu_roof": r["roofline_forward"]["frac"],
+                          | {"forward_bound": r["roofline_forward"]["bound"],
+                             "forward_frac_of_roof": r["roofline_forward"]["frac"],
                              "quantize_frac_of_hbm_roof": r["roofline_quantize"]["frac"]})
         out["others"] = others
     print(json.dumps(out))
