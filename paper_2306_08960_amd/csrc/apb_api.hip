@@ -153,7 +153,7 @@ int compress_impl(const float* W, int N, int K, float delta, float alpha, hipStr
     if ((rc = dev_alloc(&d.rowsum, (size_t)N)) != APB_OK) return rc;
     if ((rc = dev_alloc(&d.row_ptr, (size_t)N + 1)) != APB_OK) return rc;
     if ((rc = dev_alloc(&d.perm, (size_t)d.Np)) != APB_OK) return rc;
-    if ((rc = dev_alloc(&d.signT, (size_t)d.Np * d.Kw)) != APB_OK) return rc;
+    if ((rc = dev_alloc(&d.signT, (size_t)d.Np * (2 * ((d.Kw + 1) / 2)))) != APB_OK) return rc;
     if ((rc = dev_alloc(&d.signC, (size_t)N * (2 * ((d.Kw + 1) / 2)))) != APB_OK) return rc;
     if ((rc = dev_alloc(&d.chunk_ptr, (size_t)d.Np * (d.nchunks + 1))) != APB_OK) return rc;
     if ((rc = dev_alloc(&d.slot_valsum, (size_t)d.Np)) != APB_OK) return rc;
@@ -183,7 +183,7 @@ int compress_impl(const float* W, int N, int K, float delta, float alpha, hipStr
     APB_HIP(hipMemcpyAsync(d.row_ptr, hrow_ptr.data(), ((size_t)N + 1) * sizeof(int32_t), hipMemcpyHostToDevice, s));
     APB_HIP(hipMemcpyAsync(d.perm, hperm.data(), (size_t)d.Np * sizeof(int32_t), hipMemcpyHostToDevice, s));
     if (nnz > 0 && (rc = launch_scatter_csr(W, N, K, delta, alpha, d.row_ptr, d.col_idx, d.val, d.vald, s)) != APB_OK) return rc;
-    if ((rc = launch_slot_major_signs(d.sign, d.perm, d.Np, d.Kw, d.Kw, d.signT, s)) != APB_OK) return rc;
+    if ((rc = launch_slot_major_signs(d.sign, d.perm, d.Np, d.Kw, 2 * ((d.Kw + 1) / 2), d.signT, s)) != APB_OK) return rc;
     if ((rc = launch_slot_major_signs(d.sign, nullptr, N, d.Kw, 2 * ((d.Kw + 1) / 2), d.signC, s)) != APB_OK) return rc;
     if ((rc = launch_slot_tables(d.perm, d.row_ptr, d.col_idx, d.val, d.Np, d.nchunks, d.chunk_ptr, d.slot_valsum,
                                  s)) != APB_OK)
@@ -326,10 +326,13 @@ static int forward_common(const apb_layer* layer, const void* packed, int M, int
         return rc != APB_OK ? rc : launch_finalize_int(d, colsum, M, bits, D, s);
     }
     if (kind == kFwdFull) {
-        // The raw binary product is left in the output buffer itself (same size, int32 bits) and
-        // turned into Y in place by the sparse/epilogue kernel: no workspace, no allocation.
+        // Layers of at most 32 rows (fewer than four 16-row tiles): the raw binary product is left in the output buffer itself
+        // (same size, int32 bits) and turned into Y in place by the sparse/epilogue kernel: no
+        // workspace, no allocation.
+        // Workgroups of 4 or 8 waves compute the product themselves (one kernel, nothing but Y written).
+        if (sparse_epilogue_can_fuse(d)) return launch_sparse_epilogue(d, planes, colsum, M, bits, step, Y, true, s);
         const int rc = launch_binary_mfma(d, planes, M, bits, reinterpret_cast<int32_t*>(Y), s);
-        return rc != APB_OK ? rc : launch_sparse_epilogue(d, planes, colsum, M, bits, step, Y, s);
+        return rc != APB_OK ? rc : launch_sparse_epilogue(d, planes, colsum, M, bits, step, Y, false, s);
     }
     return launch_forward_popcount(d, planes, colsum, M, bits, step, Y, D, s);
 }

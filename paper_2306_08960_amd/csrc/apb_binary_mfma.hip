@@ -19,17 +19,12 @@
 // The K loop is software-pipelined by hand: words are fetched four steps ahead into a ring of
 // register sets, and the expansion of step s+1 is interleaved with the MFMAs of step s so that the
 // vector ALU works in the shadow of the matrix pipe.
+#include "apb_fp4_expand.h"
 #include "apb_internal.h"
 
 namespace apb {
 
 namespace {
-
-typedef int v8i __attribute__((ext_vector_type(8)));
-typedef float v16f __attribute__((ext_vector_type(16)));
-
-constexpr uint32_t kNib = 0x11111111u;
-constexpr int kScaleOne = 0x7f7f7f7f;                          // E8M0 exponent 127 = 1.0 in every byte
 
 struct MfmaParams {
     const uint32_t* __restrict__ signT;   // [Kw][Np]  word j of row n, rows in the layer's own order
@@ -39,36 +34,6 @@ struct MfmaParams {
     int tiles_m;                          // workgroup tiles along m
     int waves_m;                          // waves of a workgroup laid along m (2 or 4); the rest along n
 };
-
-template <int RN, int RM>
-struct Frag {
-    v8i a[RN];
-    v8i b[RM];
-};
-
-template <int BITS, int RN, int RM>
-__device__ __forceinline__ void expand(const uint32_t (&aw)[RN], const uint32_t (&bw)[BITS][RM], Frag<RN, RM>& f) {
-#pragma unroll
-    for (int t = 0; t < RN; ++t) {
-#pragma unroll
-        for (int d = 0; d < 4; ++d) f.a[t][d] = (int)((aw[t] >> d) & kNib);
-    }
-#pragma unroll
-    for (int u = 0; u < RM; ++u) {
-        if (BITS == 1) {
-#pragma unroll
-            for (int d = 0; d < 4; ++d) f.b[u][d] = (int)((bw[0][u] >> d) & kNib);
-        } else {
-            const uint32_t z1 = bw[BITS - 1][u];
-#pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                // the plane-1 bit goes one position up inside the nibble: bit d+4t -> bit 4t+1
-                const uint32_t hi = d == 0 ? (z1 << 1) : (z1 >> (d - 1));
-                f.b[u][d] = (int)((hi & (kNib << 1)) | ((bw[0][u] >> d) & kNib));
-            }
-        }
-    }
-}
 
 // Workgroup = 4 waves; each wave owns RN x RM MFMA tiles of 32 x 32 and walks K in steps of 64.
 template <int BITS, int RN, int RM>
@@ -126,17 +91,8 @@ __global__ __launch_bounds__(256) void k_binary_mfma(const MfmaParams p) {
     constexpr int kRing = (RN + BITS * RM) <= 4 ? 16 : 8;    // ~1.5 us of HBM latency to cover
     uint32_t aw[kRing][RN], bw[kRing][BITS][RM];
     Frag<RN, RM> f[2];
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-#pragma unroll
-        for (int t = 0; t < RN; ++t)
-#pragma unroll
-            for (int d = 4; d < 8; ++d) f[h].a[t][d] = 0;     // FP4 uses the low four operand dwords
-#pragma unroll
-        for (int u = 0; u < RM; ++u)
-#pragma unroll
-            for (int d = 4; d < 8; ++d) f[h].b[u][d] = 0;
-    }
+    clear_upper(f[0]);
+    clear_upper(f[1]);
 #pragma unroll
     for (int q = 0; q < kRing; ++q) load_words(q, aw[q], bw[q]);
     expand<BITS, RN, RM>(aw[0], bw[0], f[0]);
@@ -152,8 +108,7 @@ __global__ __launch_bounds__(256) void k_binary_mfma(const MfmaParams p) {
         for (int t = 0; t < RN; ++t)
 #pragma unroll
             for (int u = 0; u < RM; ++u)
-                acc[t][u] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(cur.a[t], cur.b[u], acc[t][u], 4, 4, 0,
-                                                                            kScaleOne, 0, kScaleOne);
+                acc[t][u] = mfma_fp4(cur.a[t], cur.b[u], acc[t][u]);
         // Ask the scheduler to alternate: one MFMA, then a slice of the expansion ALU work.
 #pragma unroll
         for (int e = 0; e < RN * RM; ++e) {

@@ -26,7 +26,8 @@ struct LayerDev {
     long long nnz = 0;
     float alpha = 0.f;
     uint32_t* sign = nullptr;    // [N][Kw]   canonical sign words
-    uint32_t* signT = nullptr;   // [Kw][Np]  sign words, slot-major: word j of launch slot i
+    uint32_t* signT = nullptr;   // [Kw2][Np] sign words, slot-major: word j of launch slot i (padding slots and
+                                 //           the extra word row of an odd Kw are zero; Kw2 as for signC)
     uint32_t* signC = nullptr;   // [Kw2][N]  sign words, word-major in the layer's own row order;
                                  //           Kw2 = Kw rounded up to even, the extra word row is zero
     int32_t* perm = nullptr;     // [Np]      row index served by launch slot i, -1 for padding
@@ -78,8 +79,11 @@ int launch_quantize(const float* X, int K, int M, int bits, float inv_step, uint
 // epilogue that turns the raw matrix-core product left in Y into the final output, in place
 int launch_forward_popcount(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
                             float step, float* Y, int32_t* D, hipStream_t s);
+// fused: the kernel computes the binary part itself (workgroups of 4 or 8 waves only) instead of
+// reading the raw product from Y
+bool sparse_epilogue_can_fuse(const LayerDev& L);
 int launch_sparse_epilogue(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
-                           float step, float* Y, hipStream_t s);
+                           float step, float* Y, bool fused, hipStream_t s);
 
 // binary part on the matrix cores: raw product P, and P -> D in place
 int launch_binary_mfma(const LayerDev& L, const uint32_t* planes, int M, int bits, int32_t* P, hipStream_t s);

@@ -20,6 +20,7 @@
 //      and no branch.
 // Tiles are filled by dealing rows in order of residual count (see balanced_slots), so the skewed
 // rows of pruned layers are spread over the waves instead of serialising one of them.
+#include "apb_fp4_expand.h"
 #include "apb_internal.h"
 
 namespace apb {
@@ -138,8 +139,65 @@ __device__ __forceinline__ void batch(v16d& acc, v8d& pairs, const uint32_t* __r
     for (int h = 0; h < NB; ++h) accumulate8(acc, pairs, k[h], v[h], table_off);
 }
 
+// Fused mode, first phase: the raw binary product P = sum_k bit * code of the workgroup's
+// (16 * WAVES rows) x 64 columns on the matrix cores, left in LDS as int32 [16 * WAVES][64].  Wave w
+// computes the 32 x 32 tile (w / 2, w % 2) with one FP4 MFMA per 64 values of k (see
+// apb_fp4_expand.h); rows are launch slots, read from the slot-major sign words (padding slots and
+// the pad word row past an odd Kw are zero).  The upper lane half of the last step of an odd Kw
+// reads one activation row past its plane -- still inside the packed buffer (the next plane, or the
+// column sums) and multiplied by zero weights.  Words are fetched four steps ahead.
+template <int BITS, int WAVES>
+__device__ __forceinline__ void binary_tile_to_lds(const uint32_t* __restrict__ signT,
+                                                   const uint32_t* __restrict__ planes, int Np, int Kw, int Mp,
+                                                   int slot_base, int m_base, int wave, int lane, int32_t* tile) {
+    static_assert(WAVES % 2 == 0, "two waves side by side cover the 64 columns");
+    const int i = lane & 31, g = lane >> 5;
+    const int tn = wave >> 1, tm = wave & 1;
+    const unsigned aoff = (unsigned)(g * Np + slot_base + 32 * tn + i);
+    const unsigned boff = (unsigned)(g * Mp + m_base + 32 * tm + i);
+    const size_t plane_stride = (size_t)Kw * Mp;
+    const int steps = (Kw + 1) / 2;
+    constexpr int kRing = 4;
+    uint32_t aw[kRing][1], bw[kRing][BITS][1];
+    Frag<1, 1> f[2];
+    clear_upper(f[0]);
+    clear_upper(f[1]);
+    auto load_words = [&](int st, uint32_t (&a)[1], uint32_t (&b)[BITS][1]) {
+        const int ss = min(st, steps - 1);                      // past the end: harmless re-read, never used
+        a[0] = (signT + (size_t)(2 * ss) * Np)[aoff];
+#pragma unroll
+        for (int pl = 0; pl < BITS; ++pl) b[pl][0] = (planes + pl * plane_stride + (size_t)(2 * ss) * Mp)[boff];
+    };
+    v16f c;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) c[r] = 0.0f;
+#pragma unroll
+    for (int q = 0; q < kRing; ++q) load_words(q, aw[q], bw[q]);
+    expand<BITS, 1, 1>(aw[0], bw[0], f[0]);
+    auto one_step = [&](int st, int q) {
+        const Frag<1, 1>& cur = f[q & 1];
+        load_words(st + kRing, aw[q], bw[q]);
+        expand<BITS, 1, 1>(aw[(q + 1) % kRing], bw[(q + 1) % kRing], f[(q + 1) & 1]);
+        c = mfma_fp4(cur.a[0], cur.b[0], c);
+    };
+    int s0 = 0;
+    for (; s0 + kRing <= steps; s0 += kRing) {
+#pragma unroll
+        for (int q = 0; q < kRing; ++q) one_step(s0 + q, q);
+    }
+#pragma unroll
+    for (int q = 0; q < kRing - 1; ++q)
+        if (s0 + q < steps) one_step(s0 + q, q);
+    // C layout of the 32x32 tile: lane (i, g), register r  ->  row 8*(r/4) + 4*g + (r%4), column i.
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+        tile[(32 * tn + 8 * (r / 4) + 4 * g + (r % 4)) * kWave + 32 * tm + i] = (int)(c[r] * 4.0f);
+}
+
 // WPW = words of a chunk each wave expands = 8 / waves per workgroup.
-template <int BITS, int WPW>
+// FUSED: the binary part is computed here as well (first phase, see binary_tile_to_lds) and never
+// leaves the chip; otherwise the raw product is read from Y, where the matrix-core kernel left it.
+template <int BITS, int WPW, bool FUSED>
 __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_waves_per_eu(WPW <= 2 ? 8 : 4, 8))) void k_sparse_epilogue(
     // Separate restrict-qualified arguments (not struct members) so that the compiler knows the
     // read-only arrays cannot alias Y and keeps the wave-uniform loads on the scalar path.
@@ -148,7 +206,8 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
     const int32_t* __restrict__ seg_ptr,     // [tiles][nchunks+1] first entry block of (tile, chunk)
     const uint32_t* __restrict__ ent,        // blocks of 8 keys + 8 scaled residuals
     const double* __restrict__ slot_valsum,
-    float* Y,                                // holds P (int32 bits) on entry, Y on exit
+    const uint32_t* __restrict__ signT,      // [Kw rounded up to even][Np] slot-major sign words (FUSED)
+    float* Y,                                // not FUSED: holds P (int32 bits) on entry; Y on exit
     const SparseParams p) {
     extern __shared__ __align__(16) uint8_t lds[];
     constexpr int waves = kChunkWords / WPW;
@@ -169,8 +228,31 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
 
     static_assert(TN == 16, "row field of an entry key addresses 16 register pairs");
     v16d acc;
+    if (FUSED) {
+        // Binary part first; every lane then picks up the 16 products of its column and starts its
+        // float64 sums at alpha * D (in the scaled domain of the residual products, and halved for
+        // 1-bit activations, whose sum is doubled at the end).  The tile shares LDS with the code
+        // tables, hence the second barrier.
+        int32_t* tile_lds = reinterpret_cast<int32_t*>(lds);
+        binary_tile_to_lds<BITS, (waves >= 2 ? waves : 2)>(signT, planes, p.Np, p.Kw, p.Mp, rg * waves * TN, strip * kWave,
+                                                          wave, lane, tile_lds);
+        __syncthreads();
+        int P[TN];
 #pragma unroll
-    for (int r = 0; r < TN; ++r) acc[r] = 0.0;
+        for (int r = 0; r < TN; ++r) P[r] = tile_lds[(wave * TN + r) * kWave + lane];
+        __syncthreads();
+        const int cs = colsum[m];
+        const double a0 = p.alpha * (BITS == 1 ? 0.5 : 1.0) * (1.0 / kSumUnscale);
+#pragma unroll
+        for (int r = 0; r < TN; ++r) {
+            const int nr = perm[slot0 + r];
+            const int d = BITS == 1 ? 4 * P[r] - rowsum[max(nr, 0)] - 2 * cs : 2 * P[r] - cs;
+            acc[r] = a0 * (double)d;
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < TN; ++r) acc[r] = 0.0;
+    }
     v8d pairs;
 #pragma unroll
     for (int r = 0; r < 8; ++r) pairs[r] = 0.0;
@@ -237,37 +319,50 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
     int n[TN], P[TN];
 #pragma unroll
     for (int r = 0; r < TN; ++r) n[r] = perm[slot0 + r];
+    if (!FUSED) {
 #pragma unroll
-    for (int r = 0; r < TN; ++r)
-        P[r] = reinterpret_cast<const int32_t*>(Y)[(size_t)max(n[r], 0) * p.M + mc];
+        for (int r = 0; r < TN; ++r)
+            P[r] = reinterpret_cast<const int32_t*>(Y)[(size_t)max(n[r], 0) * p.M + mc];
+    }
 #pragma unroll
     for (int r = 0; r < TN; ++r) {
-        // raw matrix-core product P = sum_k b*code  ->  D (b = sign bit, code = stored code)
-        const int d = BITS == 1 ? 4 * P[r] - rowsum[max(n[r], 0)] - 2 * cs : 2 * P[r] - cs;
         // 1-bit activations: the table holds (c+1)/2 in {0,1}: sum val*c = 2*sum val*code - sum val.
         const double sum = acc[r] * kSumUnscale;
         const double sparse = BITS == 1 ? 2.0 * sum - slot_valsum[slot0 + r] : sum;
-        const double y = fma(p.alpha, (double)d, sparse) * p.step;
+        double y;
+        if (FUSED) {
+            y = sparse * p.step;                                // alpha * D is already in the sum
+        } else {
+            // raw matrix-core product P = sum_k b*code  ->  D (b = sign bit, code = stored code)
+            const int d = BITS == 1 ? 4 * P[r] - rowsum[max(n[r], 0)] - 2 * cs : 2 * P[r] - cs;
+            y = fma(p.alpha, (double)d, sparse) * p.step;
+        }
         if (col_ok && n[r] >= 0) Y[(size_t)n[r] * p.M + m_e] = (float)y;
     }
 }
 
-template <int BITS, int WPW>
+template <int BITS, int WPW, bool FUSED>
 void launch_one(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, float* Y, const SparseParams& p,
                 hipStream_t s) {
-    hipLaunchKernelGGL((k_sparse_epilogue<BITS, WPW>), dim3((unsigned)p.blocks), dim3(kWave * kChunkWords / WPW),
+    hipLaunchKernelGGL((k_sparse_epilogue<BITS, WPW, FUSED>), dim3((unsigned)p.blocks), dim3(kWave * kChunkWords / WPW),
                        table_buffers(WPW) * kTableBytes, s, planes, colsum, L.rowsum, L.perm, L.seg_ptr, L.ent,
-                       L.slot_valsum, Y, p);
+                       L.slot_valsum, L.signT, Y, p);
 }
 
 template <int BITS>
 int launch_bits(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, float* Y, const SparseParams& p,
-                hipStream_t s) {
+                bool fused, hipStream_t s) {
     switch (L.waves) {
-        case 8: launch_one<BITS, 1>(L, planes, colsum, Y, p, s); break;
-        case 4: launch_one<BITS, 2>(L, planes, colsum, Y, p, s); break;
-        case 2: launch_one<BITS, 4>(L, planes, colsum, Y, p, s); break;
-        case 1: launch_one<BITS, 8>(L, planes, colsum, Y, p, s); break;
+        case 8:
+            if (fused) launch_one<BITS, 1, true>(L, planes, colsum, Y, p, s);
+            else launch_one<BITS, 1, false>(L, planes, colsum, Y, p, s);
+            break;
+        case 4:
+            if (fused) launch_one<BITS, 2, true>(L, planes, colsum, Y, p, s);
+            else launch_one<BITS, 2, false>(L, planes, colsum, Y, p, s);
+            break;
+        case 2: launch_one<BITS, 4, false>(L, planes, colsum, Y, p, s); break;
+        case 1: launch_one<BITS, 8, false>(L, planes, colsum, Y, p, s); break;
         default: return APB_ERR_SHAPE;
     }
     return APB_OK;
@@ -275,8 +370,11 @@ int launch_bits(const LayerDev& L, const uint32_t* planes, const int32_t* colsum
 
 }  // namespace
 
+bool sparse_epilogue_can_fuse(const LayerDev& L) { return L.waves >= 4; }
+
 int launch_sparse_epilogue(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
-                           float step, float* Y, hipStream_t s) {
+                           float step, float* Y, bool fused, hipStream_t s) {
+    if (fused && !sparse_epilogue_can_fuse(L)) return APB_ERR_SHAPE;
     const int Mp = kWave * ((M + kWave - 1) / kWave);
     SparseParams p;
     p.alpha = (double)L.alpha;
@@ -290,7 +388,8 @@ int launch_sparse_epilogue(const LayerDev& L, const uint32_t* planes, const int3
     const long long blocks = (long long)p.row_groups * (Mp / kWave);
     if (blocks > 0x7fffffffLL || (long long)Mp * 4 >= (1LL << 31)) return APB_ERR_SHAPE;
     p.blocks = (int)blocks;
-    const int rc = bits == 1 ? launch_bits<1>(L, planes, colsum, Y, p, s) : launch_bits<2>(L, planes, colsum, Y, p, s);
+    const int rc = bits == 1 ? launch_bits<1>(L, planes, colsum, Y, p, fused, s)
+                             : launch_bits<2>(L, planes, colsum, Y, p, fused, s);
     if (rc != APB_OK) return rc;
     APB_HIP(hipGetLastError());
     return APB_OK;

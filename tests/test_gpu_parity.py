@@ -90,7 +90,7 @@ def check_layer(b, W, delta, X, bits, step, alpha=None, tag=""):
 
 # ----------------------------------------------------------------------------- small shapes and edges
 EDGE_SHAPES = [(1, 1, 1), (1, 31, 1), (2, 32, 64), (3, 33, 65), (33, 64, 63), (31, 95, 127), (32, 96, 128),
-               (65, 257, 193), (100, 1000, 300), (7, 4100, 5)]
+               (65, 257, 193), (100, 1000, 300), (7, 4100, 5), (130, 200, 70)]
 
 
 @pytest.mark.parametrize("bits", [1, 2])
