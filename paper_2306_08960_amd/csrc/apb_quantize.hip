@@ -34,12 +34,12 @@ template <int CPL>
 struct Vec;
 template <>
 struct Vec<4> {
-    typedef float4 F;
+    typedef float F __attribute__((ext_vector_type(4)));
     typedef uint4 U;
 };
 template <>
 struct Vec<2> {
-    typedef float2 F;
+    typedef float F __attribute__((ext_vector_type(2)));
     typedef uint2 U;
 };
 template <>
@@ -68,7 +68,9 @@ __global__ __launch_bounds__(kWave* kMaxWaves) void k_quantize_pack(const float*
     for (int q = 0; q < CPL; ++q) sum[q] = 0;
 
     // Loads are unconditional (addresses clamped into the matrix, results masked afterwards): a
-    // branch around each load would make every load wait for the one before.
+    // branch around each load would make every load wait for the one before.  They carry the
+    // non-temporal hint: X is read exactly once, and streaming it through L2 as ordinary data would
+    // evict what the forward kernel is about to read (the planes written here, the layer).
     const float* src = X + min(m0, M - CPL);
     const int j_begin = blockIdx.y * words_per_slab;
     const int j_end = min(Kw, j_begin + words_per_slab);
@@ -82,7 +84,7 @@ __global__ __launch_bounds__(kWave* kMaxWaves) void k_quantize_pack(const float*
             FV xv[16];                                              // 16 independent loads in flight
 #pragma unroll
             for (int i = 0; i < 16; ++i)
-                xv[i] = *reinterpret_cast<const FV*>(src + (size_t)min(k0 + 16 * half + i, K - 1) * M);
+                xv[i] = __builtin_nontemporal_load(reinterpret_cast<const FV*>(src + (size_t)min(k0 + 16 * half + i, K - 1) * M));
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 float xs[CPL];
