@@ -152,13 +152,16 @@ def cpu_baseline(cfg, W, delta, X, step):
     target_ops = 60e9 * cores ** 0.5                 # sized for roughly 10-30 s of CPU work
     m = int(max(64, min(cfg.M, target_ops / per_col)))
     Xs = np.ascontiguousarray(X[:, :m])
-    t0 = time.perf_counter()
-    c = o.quantize(Xs, cfg.bits, step)
-    packed = o.pack_acts(c, cfg.bits)
-    capi.forward(L, packed, c, cfg.bits, step, threads=cores)
-    dt = time.perf_counter() - t0
-    return {"value": per_col * m / dt / 1e9, "unit": "GOPS", "cores": cores, "kind": "oracle",
-            "sample": f"first {m} of {cfg.M} columns of {cfg.name}, one pass (quantize+pack+forward), {dt:.2f} s"}
+    passes, dt = 0, 0.0
+    while passes == 0 or (dt < 1.0 and passes < 20):    # about 10-30 core-seconds in all
+        t0 = time.perf_counter()
+        c = o.quantize(Xs, cfg.bits, step)
+        packed = o.pack_acts(c, cfg.bits)
+        capi.forward(L, packed, c, cfg.bits, step, threads=cores)
+        dt += time.perf_counter() - t0
+        passes += 1
+    return {"value": per_col * m * passes / dt / 1e9, "unit": "GOPS", "cores": cores, "kind": "oracle",
+            "sample": f"first {m} of {cfg.M} columns of {cfg.name}, {passes} passes (quantize+pack+forward), {dt:.2f} s"}
 
 
 def main():
