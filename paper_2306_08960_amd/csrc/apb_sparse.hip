@@ -273,8 +273,8 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
             for (int b = 0; b < BITS; ++b) {
                 // Buffer load: the descriptor carries the wave-uniform row (scalar registers, range =
                 // one row of Mp words), the lane adds its 32-bit byte offset.  Words past Kw re-read
-                // the last row: their codes land in table columns >= K, which no residual refers to,
-                // and leaving them unmasked keeps the wait for the load at the next chunk.
+                // the last row and are never expanded; leaving the load unconditional and unmasked
+                // keeps the wait for it at the next chunk.
                 const uint32_t* row = planes + (b * plane_stride + (size_t)min(j, p.Kw - 1) * p.Mp);
                 const __amdgpu_buffer_rsrc_t rsrc =
                     __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(row), 0, p.Mp * 4, kBufferFlags);
@@ -291,8 +291,11 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
         const int buf = kBufs == 2 ? (c & 1) * kTableBytes : 0;
         if (kBufs == 1 && c > 0) __syncthreads();               // every wave has finished reading the table
 #pragma unroll
-        for (int i = 0; i < WPW; ++i)
-            expand_word<BITS>(xw[0][i], xw[BITS - 1][i], my_row + buf + 32 * (wave + i * waves));
+        for (int i = 0; i < WPW; ++i) {
+            const int jj = wave + i * waves;
+            if (c * kChunkWords + jj < p.Kw)                    // no residual refers to columns >= K
+                expand_word<BITS>(xw[0][i], xw[BITS - 1][i], my_row + buf + 32 * jj);
+        }
         if (c + 1 < p.nchunks) fetch(c + 1);
         int e = e1;
         e1 = seg[c + 1];
