@@ -1,10 +1,8 @@
-// Vector-ALU kernels of apb_forward:  Y = s * (alpha*D + sum_j val_j * c[col_j, :])   (Sec. III Eq. 13)
+// Vector-ALU comparison kernels of apb_forward:  Y = s * (alpha*D + sum_j val_j * c[col_j, :])
+// (Sec. III Eq. 13).  They serve apb_forward_popcount / apb_forward_int_popcount -- the measured
+// alternative to the matrix-core path and a second route to D in the tests -- not apb_forward.
 //
-// One kernel template, three uses:
-//   kSparseEpilogue  the product path: the matrix-core kernel has left the raw binary product P in
-//                    the output buffer; this kernel adds the residual (sparse) part and the scalars
-//                    and overwrites P with Y in place (each lane reads and writes only its own
-//                    elements).
+// One kernel template, two uses:
 //   kFusedPopcount   the paper's own formulation end to end on the vector ALU: xor/and + popcount
 //                    for D (Sec. IV Eq. 16; for 2-bit activations the two stored bit-planes P0, P1
 //                    of the level index stand in for the (t, h, m) vectors of Eqs. 18-19:
@@ -36,7 +34,7 @@ constexpr int TN = kRowTile;
 constexpr int kTablePitch = kChunkK + 4;                       // bytes per column row of the code table
 constexpr int kTableBytes = kWave * kTablePitch;               // one buffer; two are used alternately
 
-enum FwdMode { kFusedPopcount = 0, kIntPopcount = 1, kSparseEpilogue = 2 };
+enum FwdMode { kFusedPopcount = 0, kIntPopcount = 1 };
 
 struct FwdParams {
     const uint32_t* __restrict__ signT;
@@ -48,7 +46,7 @@ struct FwdParams {
     const int32_t* __restrict__ col_idx;
     const double* __restrict__ vald;
     const double* __restrict__ slot_valsum;
-    float* Y;                    // kSparseEpilogue: holds P (int32 bits) on entry
+    float* Y;
     int32_t* __restrict__ D;
     double alpha, step;
     int Np, Kw, K, Mp, M, nchunks;
@@ -73,7 +71,6 @@ __device__ __forceinline__ void expand_word(uint32_t x0, uint32_t x1, uint8_t* d
 template <int BITS, int MODE>
 __global__ __launch_bounds__(kWave* kMaxWavesPerBlock) void k_forward_valu(const FwdParams p) {
     extern __shared__ __align__(16) uint8_t lds[];
-    constexpr bool kPop = MODE != kSparseEpilogue;              // popcount loop present
     constexpr bool kSparse = MODE != kIntPopcount;              // sparse part present
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -102,67 +99,52 @@ __global__ __launch_bounds__(kWave* kMaxWavesPerBlock) void k_forward_valu(const
     const size_t plane_stride = (size_t)p.Kw * p.Mp;
     uint8_t* my_row = lds + lane * kTablePitch;
 
-    // Popcount modes: the activation words of one whole chunk live in registers and are fetched one
+    // The activation words of one whole chunk live in registers and are fetched one
     // chunk ahead; the weight words (scalar loads) one word ahead.
     uint32_t xcur[BITS][kChunkWords], xnext[BITS][kChunkWords];
     uint32_t wnext[TN];
-    if (kPop) {
 #pragma unroll
-        for (int jj = 0; jj < kChunkWords; ++jj)
+    for (int jj = 0; jj < kChunkWords; ++jj)
 #pragma unroll
-            for (int b = 0; b < BITS; ++b)
-                xnext[b][jj] = jj < p.Kw ? xp[b * plane_stride + (size_t)jj * p.Mp] : 0u;
+        for (int b = 0; b < BITS; ++b) xnext[b][jj] = jj < p.Kw ? xp[b * plane_stride + (size_t)jj * p.Mp] : 0u;
 #pragma unroll
-        for (int r = 0; r < TN; ++r) wnext[r] = wp[r];
-    }
+    for (int r = 0; r < TN; ++r) wnext[r] = wp[r];
 
     for (int c = 0; c < p.nchunks; ++c) {
         const int j0 = c * kChunkWords;
         uint8_t* table_row = my_row + (c & 1) * kTableBytes;
-        if (kPop) {
 #pragma unroll
-            for (int jj = 0; jj < kChunkWords; ++jj)
+        for (int jj = 0; jj < kChunkWords; ++jj)
 #pragma unroll
-                for (int b = 0; b < BITS; ++b) {
-                    xcur[b][jj] = xnext[b][jj];
-                    const int jn = j0 + kChunkWords + jj;           // words past the end read as zero
-                    xnext[b][jj] = jn < p.Kw ? xp[b * plane_stride + (size_t)jn * p.Mp] : 0u;
-                }
-#pragma unroll
-            for (int jj = 0; jj < kChunkWords; ++jj) {
-                const int j = j0 + jj;
-                if (j >= p.Kw) break;
-                uint32_t wcur[TN];
-#pragma unroll
-                for (int r = 0; r < TN; ++r) wcur[r] = wnext[r];
-                if (j + 1 < p.Kw) {
-                    const uint32_t* w = wp + (size_t)(j + 1) * p.Np;
-#pragma unroll
-                    for (int r = 0; r < TN; ++r) wnext[r] = w[r];
-                }
-                const uint32_t x0 = xcur[0][jj];
-                const uint32_t x1 = xcur[BITS - 1][jj];
-#pragma unroll
-                for (int r = 0; r < TN; ++r) {
-                    if (BITS == 1) {
-                        acc[0][r] += __builtin_popcount(wcur[r] ^ x0);
-                    } else {
-                        acc[0][r] += __builtin_popcount(wcur[r] & x0);
-                        acc[1][r] += __builtin_popcount(wcur[r] & x1);
-                    }
-                }
-                if (kSparse && (jj % waves) == wave) expand_word<BITS>(x0, x1, table_row + 32 * jj);
+            for (int b = 0; b < BITS; ++b) {
+                xcur[b][jj] = xnext[b][jj];
+                const int jn = j0 + kChunkWords + jj;           // words past the end read as zero
+                xnext[b][jj] = jn < p.Kw ? xp[b * plane_stride + (size_t)jn * p.Mp] : 0u;
             }
-        } else {
-            // Sparse-only: each wave fetches just the words it expands (word jj of the chunk goes
-            // to wave jj % waves).
-            for (int jj = wave; jj < kChunkWords; jj += waves) {
-                const int j = j0 + jj;
-                if (j >= p.Kw) break;
-                const uint32_t x0 = xp[(size_t)j * p.Mp];
-                const uint32_t x1 = BITS == 2 ? xp[plane_stride + (size_t)j * p.Mp] : 0u;
-                expand_word<BITS>(x0, x1, table_row + 32 * jj);
+#pragma unroll
+        for (int jj = 0; jj < kChunkWords; ++jj) {
+            const int j = j0 + jj;
+            if (j >= p.Kw) break;
+            uint32_t wcur[TN];
+#pragma unroll
+            for (int r = 0; r < TN; ++r) wcur[r] = wnext[r];
+            if (j + 1 < p.Kw) {
+                const uint32_t* w = wp + (size_t)(j + 1) * p.Np;
+#pragma unroll
+                for (int r = 0; r < TN; ++r) wnext[r] = w[r];
             }
+            const uint32_t x0 = xcur[0][jj];
+            const uint32_t x1 = xcur[BITS - 1][jj];
+#pragma unroll
+            for (int r = 0; r < TN; ++r) {
+                if (BITS == 1) {
+                    acc[0][r] += __builtin_popcount(wcur[r] ^ x0);
+                } else {
+                    acc[0][r] += __builtin_popcount(wcur[r] & x0);
+                    acc[1][r] += __builtin_popcount(wcur[r] & x1);
+                }
+            }
+            if (kSparse && (jj % waves) == wave) expand_word<BITS>(x0, x1, table_row + 32 * jj);
         }
         if (!kSparse) continue;
         __syncthreads();                                        // the chunk's code table is complete
@@ -200,14 +182,7 @@ __global__ __launch_bounds__(kWave* kMaxWavesPerBlock) void k_forward_valu(const
     for (int r = 0; r < TN; ++r) {
         const int n = p.perm[slot0 + r];
         if (n < 0) continue;
-        int d;
-        if (kPop) {
-            d = BITS == 1 ? p.K - 2 * acc[0][r] : 2 * (acc[0][r] + 2 * acc[BITS - 1][r]) - cs;
-        } else {
-            // raw matrix-core product P = sum_k b*code  ->  D (b = sign bit, code = stored code)
-            const int P = col_ok ? reinterpret_cast<const int32_t*>(p.Y)[(size_t)n * p.M + m] : 0;
-            d = BITS == 1 ? 4 * P - p.rowsum[n] - 2 * cs : 2 * P - cs;
-        }
+        const int d = BITS == 1 ? p.K - 2 * acc[0][r] : 2 * (acc[0][r] + 2 * acc[BITS - 1][r]) - cs;
         if (MODE == kIntPopcount) {
             if (col_ok) p.D[(size_t)n * p.M + m] = d;
             continue;
