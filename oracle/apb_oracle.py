@@ -24,6 +24,12 @@ What is computed, and where it is defined:
                   printed equation leaves out, plus the zero-centering term
                   mu * sum(w), mu = 3s/2
   forward         Sec. III Eq. 13:  C = A^bin * B + A^full * B
+  dot_2_2_mbm     Sec. IV "2/2": the 1/2 routine applied twice -- four mbm terms
+                  under the and of the two masks, with the level weights 9/4,
+                  3/4, 3/4, 1/4 that the printed equation leaves out (and the
+                  operands t_w, t_a in its first term)
+  gemm_2_2        Sec. IV "2/2": 2-bit weights (zero-centred levels) times
+                  2-bit activations a_p = p*s
   brute_force     the plain definition: APB(W) (Eq. 3) times the dequantized
                   activations, as one dense float64 product
 
@@ -35,7 +41,10 @@ float64 mean of |w| over the binarized set rounded to float32; the 2-bit
 quantizer is p = clamp(rint(x * (1/s)), 0, 3) with float32 arithmetic and
 round-half-to-even; dequantized activations are the exact reals c*s (float64);
 all floating-point accumulation is float64, the output is rounded once to
-float32.
+float32.  For the 2/2 routine the paper takes the quantized weights as given;
+here the 2-bit weight quantizer is the uniform mid-rise one with step s_w:
+level index q = clamp(floor(w * (1/s_w)) + 2, 0, 3), value (q - 3/2) * s_w
+(the zero-centred levels of Sec. IV "2/2"), float32 arithmetic, NaN -> 0.
 
 Packed activation buffer (the library's interface layout, re-stated here
 independently): Kw = ceil(K/32), Mp = 64*ceil(M/64); uint32 planes
@@ -286,3 +295,77 @@ def forward(layer: dict, c: np.ndarray, step) -> dict:
 def brute_force(W: np.ndarray, delta, alpha, X: np.ndarray, bits: int, step) -> np.ndarray:
     """The plain definition, float64: APB(W) @ dequantize(quantize(X))."""
     return apb_dense(W, delta, alpha) @ dequantize(quantize(X, bits, step), step)
+
+
+# --------------------------------------------------------------------------- the 2/2 routine
+
+
+def quantize_weights_2bit(W: np.ndarray, step_w) -> np.ndarray:
+    """Level index q in {0,1,2,3} of every weight; the weight it stands for is (q - 3/2) * s_w."""
+    W = np.asarray(W, dtype=np.float32)
+    inv = np.float32(1.0) / np.float32(step_w)
+    t = np.floor(W * inv) + np.float32(2.0)
+    with np.errstate(invalid="ignore"):
+        t = np.where(np.isnan(t), np.float32(0.0), t)
+    return np.clip(t, 0.0, 3.0).astype(np.uint8)
+
+
+def pack_weight_planes(q: np.ndarray) -> np.ndarray:
+    """uint32 [2][N][Kw]: bit i of word j of plane b = bit b of q[n, 32*j + i]; pad bits 0."""
+    q = np.asarray(q, dtype=np.uint8)
+    return np.stack([pack_bits_rows((q >> b) & 1) for b in range(2)])
+
+
+def dot_2_2_mbm_times4(q, p) -> int:
+    """FOUR times the dot product, in units of s_w*s_a, of zero-centred 2-bit vectors, the paper's way.
+
+    Both level-index vectors stand for values (q - 3/2) and (p - 3/2).  T splits each into a
+    three-halves part (under its mask m) and a one-half part (under not-m); each of the four
+    pairings is one mbm under the and of the two masks and carries the product of its levels:
+        4 * (w_bar . a_bar) = 9*mbm(t_w,t_a,m_w&m_a) + 3*mbm(t_w,h_a,m_w&~m_a)
+                            + 3*mbm(h_w,t_a,~m_w&m_a) + mbm(h_w,h_a,~m_w&~m_a).
+    """
+    tw, hw, mw = T_transform(q)
+    ta, ha, ma = T_transform(p)
+    return (9 * mbm(tw, ta, mw & ma) + 3 * mbm(tw, ha, mw & ~ma)
+            + 3 * mbm(hw, ta, ~mw & ma) + mbm(hw, ha, ~mw & ~ma))
+
+
+def int_2_2_unpacked(q: np.ndarray, c: np.ndarray) -> np.ndarray:
+    """D22[n,m] = sum_k (2*q[n,k] - 3) * p[k,m]  (= 2/(s_w*s_a) times the product of the zero-centred
+    weights with the activations p*s_a).  The matrix product runs in float64, which is exact here
+    (every partial sum is an integer far below 2^53)."""
+    wq = 2.0 * np.asarray(q).astype(np.float64) - 3.0
+    return np.rint(wq @ np.asarray(c).astype(np.float64)).astype(np.int32)
+
+
+def int_2_2_packed(wplanes: np.ndarray, packed: np.ndarray, K: int, M: int) -> np.ndarray:
+    """The same D22 from packed words: sum over the four plane pairs of 2^(a+b) * popcount(W_a & P_b)
+    gives sum_k q*p; the zero-centring of the weights takes 3/2 * colsum off.  Small cases only."""
+    _, N, Kw = wplanes.shape
+    Mp = 64 * ((M + 63) // 64)
+    planes = packed[: 2 * Kw * Mp].reshape(2, Kw, Mp)
+    colsum = packed[2 * Kw * Mp:].view(np.int32)
+    D = np.zeros((N, M), dtype=np.int32)
+    for n in range(N):
+        for m in range(M):
+            qp = sum((1 << (a + b)) * popcount(wplanes[a, n, j] & planes[b, j, m])
+                     for a in range(2) for b in range(2) for j in range(Kw))
+            D[n, m] = 2 * qp - 3 * int(colsum[m])
+    return D
+
+
+def gemm_2_2(q: np.ndarray, c: np.ndarray, step_w, step_a) -> dict:
+    """Y = W_q @ A_q with W_q = (q - 3/2)*s_w and A_q = p*s_a: (s_w*s_a/2) * D22 in float64, rounded
+    once to float32."""
+    D = int_2_2_unpacked(q, c)
+    sw = np.float64(np.float32(step_w))
+    sa = np.float64(np.float32(step_a))
+    return {"D": D, "Y": (0.5 * sw * sa * D.astype(np.float64)).astype(np.float32)}
+
+
+def brute_force_2_2(W: np.ndarray, step_w, X: np.ndarray, step_a) -> np.ndarray:
+    """The plain definition, float64: dequantized 2-bit weights times dequantized 2-bit activations."""
+    q = quantize_weights_2bit(W, step_w).astype(np.float64)
+    Wq = (q - 1.5) * np.float64(np.float32(step_w))
+    return Wq @ dequantize(quantize(X, 2, step_a), step_a)

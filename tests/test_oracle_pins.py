@@ -336,3 +336,89 @@ def test_empty_and_full_rows():
     F = o.forward(L, c, np.float32(0.75))
     Yb = o.brute_force(W, np.float32(1.0), L["alpha"], X, 2, np.float32(0.75))
     assert np.allclose(F["Y"], Yb, rtol=1e-6, atol=1e-7)
+
+
+# --------------------------------------------------------------------------- the 2/2 routine (Sec. IV "2/2")
+
+def test_2_2_mbm_form_equals_the_direct_sum_for_every_length():
+    r = np.random.default_rng(22)
+    for n in range(1, 131):
+        q = r.integers(0, 4, n)
+        p = r.integers(0, 4, n)
+        assert o.dot_2_2_mbm_times4(q, p) == int(np.sum((2 * q - 3) * (2 * p - 3)))
+
+
+def test_2_2_extremes_and_single_levels():
+    n = 37
+    for q0, p0 in [(3, 3), (0, 3), (3, 0), (2, 2), (1, 2), (2, 0), (1, 1)]:
+        q = np.full(n, q0)
+        p = np.full(n, p0)
+        assert o.dot_2_2_mbm_times4(q, p) == n * (2 * q0 - 3) * (2 * p0 - 3)
+
+
+def test_2_2_printed_formula_without_level_weights_is_not_the_product():
+    # one element, both vectors at +3/2: the product is 9/4, the four unweighted mbm terms add up to 1
+    q = np.array([3])
+    p = np.array([3])
+    tw, hw, mw = o.T_transform(q)
+    ta, ha, ma = o.T_transform(p)
+    unweighted = (o.mbm(tw, ta, mw & ma) + o.mbm(tw, ha, mw & ~ma) + o.mbm(hw, ta, ~mw & ma)
+                  + o.mbm(hw, ha, ~mw & ~ma))
+    assert unweighted == 1
+    assert o.dot_2_2_mbm_times4(q, p) == 9
+
+
+def test_2_2_zero_centring_term_and_integer_form():
+    # w . a = w_bar . a_bar + (3/2) * sum(w_bar)  (activations a = p*s are not zero-centred), hence
+    # D22 = sum (2q-3) p = ( 4*(w_bar . a_bar) + 3 * sum(2q-3) ) / 2
+    r = np.random.default_rng(23)
+    q = r.integers(0, 4, (6, 75)).astype(np.uint8)
+    p = r.integers(0, 4, (75, 5)).astype(np.int8)
+    D = o.int_2_2_unpacked(q, p)
+    for n in range(6):
+        for m in range(5):
+            t4 = o.dot_2_2_mbm_times4(q[n], p[:, m])
+            assert 2 * int(D[n, m]) == t4 + 3 * int(np.sum(2 * q[n].astype(int) - 3))
+
+
+def test_2_2_packed_equals_unpacked_with_ragged_k():
+    r = np.random.default_rng(24)
+    for N, K, M in [(3, 1, 2), (4, 33, 5), (5, 64, 3), (2, 97, 66)]:
+        W = (r.standard_normal((N, K)) * 0.1).astype(np.float32)
+        X = np.maximum(r.standard_normal((K, M)), 0).astype(np.float32)
+        q = o.quantize_weights_2bit(W, np.float32(0.07))
+        c = o.quantize(X, 2, np.float32(0.75))
+        D = o.int_2_2_packed(o.pack_weight_planes(q), o.pack_acts(c, 2), K, M)
+        assert np.array_equal(D, o.int_2_2_unpacked(q, c))
+
+
+def test_2_2_with_half_levels_only_is_the_1_2_integer_part():
+    # weights restricted to -1/2, +1/2 (q = 1, 2) are a +-1 vector scaled by 1/2: D22 must equal the
+    # integer part of the binary layer with the same signs
+    r = np.random.default_rng(25)
+    bit = r.integers(0, 2, (7, 90)).astype(bool)
+    p = r.integers(0, 4, (90, 11)).astype(np.int8)
+    assert np.array_equal(o.int_2_2_unpacked(1 + bit.astype(np.uint8), p), o.int_part_unpacked(bit, p))
+
+
+def test_2_2_weight_quantizer_levels_and_boundaries():
+    s = np.float32(0.5)
+    w = np.array([0.0, -0.0, 0.49, 0.5, 0.99, 1.0, 7.0, -1e-30, -0.5, -0.51, -1.0, -1.01, -9.0, np.nan, np.inf, -np.inf],
+                 dtype=np.float32)
+    assert o.quantize_weights_2bit(w, s).tolist() == [2, 2, 2, 3, 3, 3, 3, 1, 1, 0, 0, 0, 0, 0, 3, 0]
+    # the dequantized weight is the midpoint of the cell the weight falls in
+    r = np.random.default_rng(26)
+    w = (r.uniform(-0.999, 0.999, 1000)).astype(np.float32)
+    q = o.quantize_weights_2bit(w, s).astype(np.float64)
+    assert np.all(np.abs((q - 1.5) * 0.5 - w) <= 0.25 + 1e-7)
+
+
+def test_2_2_gemm_matches_the_plain_definition():
+    r = np.random.default_rng(27)
+    W = (r.standard_normal((9, 130)) * 0.1).astype(np.float32)
+    X = np.maximum(r.standard_normal((130, 17)), 0).astype(np.float32)
+    sw, sa = np.float32(0.08), np.float32(0.75)
+    G = o.gemm_2_2(o.quantize_weights_2bit(W, sw), o.quantize(X, 2, sa), sw, sa)
+    Yb = o.brute_force_2_2(W, sw, X, sa)
+    assert np.allclose(G["Y"], Yb, rtol=1e-6, atol=1e-9)
+    assert np.abs(G["D"]).max() <= 3 * 3 * 130
