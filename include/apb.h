@@ -114,8 +114,9 @@ int apb_quantize_acts(const float* X, int K, int M, int bits, float step, void* 
  * Asynchronous on `stream`. */
 int apb_forward(const apb_layer* layer, const void* packed, int M, int bits, float step, float* Y, void* stream);
 
-/* Test hook: the integer part D (N*M int32, row-major, DEVICE) alone, computed by the same
- * matrix-core kernel apb_forward uses. Asynchronous on `stream`. */
+/* Test hook: the integer part D (N*M int32, row-major, DEVICE) alone, computed by the stand-alone
+ * matrix-core kernel (the same bit expansion and matrix instruction as apb_forward's first
+ * phase). Asynchronous on `stream`. */
 int apb_forward_int(const apb_layer* layer, const void* packed, int M, int bits, int32_t* D, void* stream);
 
 /* The same D through the paper's own formulation: xor/and + popcount over packed words
@@ -129,6 +130,40 @@ int apb_forward_int_popcount(const apb_layer* layer, const void* packed, int M, 
  * that the two formulations can be timed against each other. */
 int apb_forward_popcount(const apb_layer* layer, const void* packed, int M, int bits, float step, float* Y,
                          void* stream);
+
+/* ---- Sec. IV "2/2": 2-bit weights times 2-bit activations ----------------------------------
+ *
+ * Both operands are 2-bit uniformly quantized; the weights take the zero-centred levels
+ * (q - 3/2) * step_w, q in 0..3, the activations the levels p * step_a, p in 0..3 (the packed
+ * buffer of apb_quantize_acts with bits = 2).  The paper decomposes both into three binary
+ * vectors and applies its 1/2 routine twice (four masked binary products, cost 8x the 1/1
+ * routine); here the two bit-planes of q and of p feed the same matrix-core kernel as the binary
+ * layer, which yields sum_k q*p exactly, and the zero-centring of the weights is applied with
+ * the per-column sums of p:
+ *      D22[n,m] = sum_k (2*q[n,k] - 3) * p[k,m] = 2 * sum_k q*p - 3 * colsum[m],
+ *      Y[n,m]   = (step_w * step_a / 2) * D22[n,m]        (float64 product, rounded once).
+ * The paper takes the quantized weights as given; apb_w2_pack uses the uniform mid-rise
+ * quantizer q = clamp(floor(w * (1/step_w)) + 2, 0, 3) in float arithmetic (NaN -> 0). */
+typedef struct apb_w2 apb_w2;   /* opaque; owns the packed weight planes in device memory */
+
+/*   W       DEVICE, N*K floats, row-major, read-only.     step_w  finite and > 0.
+ *   out     receives a new handle on APB_OK (free with apb_w2_free), NULL otherwise.
+ * Asynchronous on `stream` except for the allocations. */
+int apb_w2_pack(const float* W, int N, int K, float step_w, void* stream, apb_w2** out);
+
+/* Copy the canonical planes out: 2 * N * ceil(K/32) uint32 (device or host), plane b first;
+ * bit i of word j of row n of plane b = bit b of q[n, 32*j+i]; bits beyond K are 0.
+ * Synchronizes `stream`. */
+int apb_w2_export(const apb_w2* w2, uint32_t* planes, void* stream);
+
+/* NULL-safe.  The caller makes sure no enqueued work still uses the handle. */
+void apb_w2_free(apb_w2* w2);
+
+/*   packed  DEVICE buffer written by apb_quantize_acts with the same K, M and bits = 2.
+ *   D / Y   DEVICE, N*M int32 / floats, row-major, fully overwritten.
+ * Asynchronous on `stream`. */
+int apb_gemm_2_2_int(const apb_w2* w2, const void* packed, int M, int32_t* D, void* stream);
+int apb_gemm_2_2(const apb_w2* w2, const void* packed, int M, float step_a, float* Y, void* stream);
 
 const char* apb_strerror(int code);
 int apb_last_hip_error(void);

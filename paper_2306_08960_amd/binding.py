@@ -20,8 +20,9 @@ LIB_PATH = os.path.join(_HERE, "libapb.so")
 
 EXPORTS = (
     "apb_compress", "apb_layer_info", "apb_layer_export", "apb_layer_free", "apb_acts_bytes",
-    "apb_quantize_acts", "apb_forward", "apb_forward_int", "apb_forward_int_popcount", "apb_forward_popcount", "apb_strerror",
-    "apb_last_hip_error",
+    "apb_quantize_acts", "apb_forward", "apb_forward_int", "apb_forward_int_popcount", "apb_forward_popcount",
+    "apb_w2_pack", "apb_w2_export", "apb_w2_free", "apb_gemm_2_2_int", "apb_gemm_2_2",
+    "apb_strerror", "apb_last_hip_error",
 )
 
 APB_OK = 0
@@ -67,6 +68,16 @@ def load() -> ctypes.CDLL:
     lib.apb_forward_int_popcount.restype = ci
     lib.apb_forward_popcount.argtypes = [vp, vp, ci, ci, cf, vp, vp]
     lib.apb_forward_popcount.restype = ci
+    lib.apb_w2_pack.argtypes = [vp, ci, ci, cf, vp, ctypes.POINTER(vp)]
+    lib.apb_w2_pack.restype = ci
+    lib.apb_w2_export.argtypes = [vp, vp, vp]
+    lib.apb_w2_export.restype = ci
+    lib.apb_w2_free.argtypes = [vp]
+    lib.apb_w2_free.restype = None
+    lib.apb_gemm_2_2_int.argtypes = [vp, vp, ci, vp, vp]
+    lib.apb_gemm_2_2_int.restype = ci
+    lib.apb_gemm_2_2.argtypes = [vp, vp, ci, cf, vp, vp]
+    lib.apb_gemm_2_2.restype = ci
     lib.apb_strerror.argtypes = [ci]
     lib.apb_strerror.restype = ctypes.c_char_p
     lib.apb_last_hip_error.argtypes = []
@@ -246,4 +257,81 @@ def apb_forward_popcount(layer: ApbLayer, packed: torch.Tensor, M: int, bits: in
     _check(load().apb_forward_popcount(layer.handle, _dev_ptr(packed, torch.int32, "packed"), int(M), int(bits),
                                        float(step), _dev_ptr(Y, torch.float32, "Y"), _stream(stream)),
            "apb_forward_popcount")
+    return Y
+
+
+# ----------------------------------------------------------------------------- 2/2 routine
+
+class ApbW2:
+    """Owner of an apb_w2 handle (packed 2-bit weights)."""
+
+    def __init__(self, handle: int, N: int, K: int):
+        self._h = ctypes.c_void_p(handle)
+        self.N, self.K = N, K
+
+    @property
+    def handle(self) -> ctypes.c_void_p:
+        if not self._h:
+            raise RuntimeError("weights already freed")
+        return self._h
+
+    def free(self) -> None:
+        if self._h:
+            load().apb_w2_free(self._h)
+            self._h = ctypes.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def apb_w2_pack(W: torch.Tensor, step_w: float, stream: Optional[torch.cuda.Stream] = None) -> ApbW2:
+    if W.dim() != 2:
+        raise ValueError("W must be [N, K]")
+    ptr = _dev_ptr(W, torch.float32, "W")
+    N, K = int(W.shape[0]), int(W.shape[1])
+    out = ctypes.c_void_p(None)
+    _check(load().apb_w2_pack(ptr, N, K, float(step_w), _stream(stream), ctypes.byref(out)), "apb_w2_pack")
+    return ApbW2(out.value, N, K)
+
+
+def apb_w2_export(w2: ApbW2, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """int32 view of the canonical planes, shape [2, N, ceil(K/32)]."""
+    Kw = (w2.K + 31) // 32
+    planes = torch.empty((2, w2.N, Kw), dtype=torch.int32, device="cuda")
+    _check(load().apb_w2_export(w2.handle, planes.data_ptr(), _stream(stream)), "apb_w2_export")
+    return planes
+
+
+def _check_packed_w2(w2: ApbW2, packed: torch.Tensor, M: int) -> None:
+    need = apb_acts_bytes(w2.K, M, 2)
+    if need == 0:
+        raise ValueError("bad K, M")
+    if packed.numel() * packed.element_size() < need:
+        raise ValueError("packed buffer smaller than apb_acts_bytes(K, M, 2)")
+
+
+def apb_gemm_2_2_int(w2: ApbW2, packed: torch.Tensor, M: int, D: Optional[torch.Tensor] = None,
+                     stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    _check_packed_w2(w2, packed, M)
+    if D is None:
+        D = torch.empty((w2.N, M), dtype=torch.int32, device=packed.device)
+    elif tuple(D.shape) != (w2.N, M):
+        raise ValueError("D must be [N, M]")
+    _check(load().apb_gemm_2_2_int(w2.handle, _dev_ptr(packed, torch.int32, "packed"), int(M),
+                                   _dev_ptr(D, torch.int32, "D"), _stream(stream)), "apb_gemm_2_2_int")
+    return D
+
+
+def apb_gemm_2_2(w2: ApbW2, packed: torch.Tensor, M: int, step_a: float, Y: Optional[torch.Tensor] = None,
+                 stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    _check_packed_w2(w2, packed, M)
+    if Y is None:
+        Y = torch.empty((w2.N, M), dtype=torch.float32, device=packed.device)
+    elif tuple(Y.shape) != (w2.N, M):
+        raise ValueError("Y must be [N, M]")
+    _check(load().apb_gemm_2_2(w2.handle, _dev_ptr(packed, torch.int32, "packed"), int(M), float(step_a),
+                               _dev_ptr(Y, torch.float32, "Y"), _stream(stream)), "apb_gemm_2_2")
     return Y

@@ -358,6 +358,66 @@ int apb_forward_int_popcount(const apb_layer* layer, const void* packed, int M, 
     return forward_common(layer, packed, M, bits, 1.0f, nullptr, D, stream, kFwdIntPopcount);
 }
 
+int apb_w2_pack(const float* W, int N, int K, float step_w, void* stream, apb_w2** out) {
+    if (out) *out = nullptr;
+    if (!W || !out) return APB_ERR_NULL;
+    if (N <= 0 || K <= 0 || (long long)N * K >= (1LL << 31) || (long long)K * 3 >= (1LL << 31)) return APB_ERR_SHAPE;
+    if (!std::isfinite(step_w) || !(step_w > 0.0f)) return APB_ERR_VALUE;
+    apb_w2* w = new (std::nothrow) apb_w2();
+    if (!w) return APB_ERR_NOMEM;
+    w->N = N;
+    w->K = K;
+    w->Kw = (K + 31) / 32;
+    w->step_w = step_w;
+    const size_t Kw2 = 2 * (((size_t)w->Kw + 1) / 2);
+    int rc = dev_alloc(&w->planes, (size_t)2 * N * w->Kw);
+    if (rc == APB_OK) rc = dev_alloc(&w->planesC, (size_t)2 * Kw2 * N);
+    if (rc == APB_OK) rc = launch_w2_pack(W, N, K, 1.0f / step_w, w->planes, w->planesC, as_stream(stream));
+    if (rc != APB_OK) {
+        apb_w2_free(w);
+        return rc;
+    }
+    *out = w;
+    return APB_OK;
+}
+
+int apb_w2_export(const apb_w2* w2, uint32_t* planes, void* stream) {
+    if (!w2 || !planes) return APB_ERR_NULL;
+    hipStream_t s = as_stream(stream);
+    APB_HIP(hipMemcpyAsync(planes, w2->planes, (size_t)2 * w2->N * w2->Kw * sizeof(uint32_t), hipMemcpyDefault, s));
+    APB_HIP(hipStreamSynchronize(s));
+    return APB_OK;
+}
+
+void apb_w2_free(apb_w2* w2) {
+    if (!w2) return;
+    if (w2->planes) (void)hipFree(w2->planes);
+    if (w2->planesC) (void)hipFree(w2->planesC);
+    delete w2;
+}
+
+static int gemm_2_2_common(const apb_w2* w2, const void* packed, int M, float step_a, int32_t* D, float* Y,
+                           void* stream) {
+    if (!w2 || !packed || (!D && !Y)) return APB_ERR_NULL;
+    if (bad_shape_acts(w2->K, M) || (long long)w2->N * M >= (1LL << 40)) return APB_ERR_SHAPE;
+    if (Y && (!std::isfinite(step_a) || !(step_a > 0.0f))) return APB_ERR_VALUE;
+    const size_t Mp = (size_t)kWave * (((size_t)M + kWave - 1) / kWave);
+    const uint32_t* planes = static_cast<const uint32_t*>(packed);
+    const int32_t* colsum = reinterpret_cast<const int32_t*>(planes + (size_t)2 * w2->Kw * Mp);
+    const double scale = 0.5 * (double)w2->step_w * (double)step_a;
+    return launch_gemm_2_2(w2->planesC, w2->N, w2->Kw, planes, colsum, M, scale, D, Y, as_stream(stream));
+}
+
+int apb_gemm_2_2_int(const apb_w2* w2, const void* packed, int M, int32_t* D, void* stream) {
+    if (!D) return APB_ERR_NULL;
+    return gemm_2_2_common(w2, packed, M, 1.0f, D, nullptr, stream);
+}
+
+int apb_gemm_2_2(const apb_w2* w2, const void* packed, int M, float step_a, float* Y, void* stream) {
+    if (!Y) return APB_ERR_NULL;
+    return gemm_2_2_common(w2, packed, M, step_a, nullptr, Y, stream);
+}
+
 const char* apb_strerror(int code) {
     switch (code) {
         case APB_OK: return "ok";

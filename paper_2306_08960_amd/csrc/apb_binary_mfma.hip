@@ -16,6 +16,11 @@
 //   lane l = 32*g + i (i: row of A / column of B, g: lane half) owns word 2*s+g of K step s;
 //   nibble t of operand dword d  <->  bit d + 4*t of that word.
 //
+// The same kernel serves the 2/2 routine of Sec. IV (2-bit weights x 2-bit activations): the
+// weight operand is then expanded from two bit-planes exactly like the activations, P = sum_k q*p,
+// and the epilogue applies the zero-centring of the weights, D22 = sum_k (2q-3)*p = 2*P - 3*colsum[m]
+// (written as int32, or scaled to Y = (s_w*s_a/2) * D22).
+//
 // The K loop is software-pipelined by hand: words are fetched four steps ahead into a ring of
 // register sets, and the expansion of step s+1 is interleaved with the MFMAs of step s so that the
 // vector ALU works in the shadow of the matrix pipe.
@@ -26,17 +31,22 @@ namespace apb {
 
 namespace {
 
+enum Epilogue { kRawProduct = 0, kInt22 = 1, kFloat22 = 2 };
+
 struct MfmaParams {
-    const uint32_t* __restrict__ signT;   // [Kw][Np]  word j of row n, rows in the layer's own order
+    const uint32_t* __restrict__ signT;   // [wbits][Kw2][Np]  word j of row n, rows in the layer's own order
     const uint32_t* __restrict__ planes;  // [bits][Kw][Mp]
-    int32_t* __restrict__ P;              // [N][M]
+    const int32_t* __restrict__ colsum;   // [Mp]   (2/2 epilogues)
+    void* __restrict__ out;               // [N][M] int32 (kRawProduct, kInt22) or float (kFloat22)
+    double scale;                         // kFloat22: s_w * s_a / 2
+    size_t wplane_stride;                 // words between the weight planes
     int Np, Kw, Mp, M;
     int tiles_m;                          // workgroup tiles along m
     int waves_m;                          // waves of a workgroup laid along m (2 or 4); the rest along n
 };
 
 // Workgroup = 4 waves; each wave owns RN x RM MFMA tiles of 32 x 32 and walks K in steps of 64.
-template <int BITS, int RN, int RM>
+template <int WBITS, int BITS, int RN, int RM, int EPI>
 __global__ __launch_bounds__(256) void k_binary_mfma(const MfmaParams p) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -67,16 +77,19 @@ __global__ __launch_bounds__(256) void k_binary_mfma(const MfmaParams p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[t][u][r] = 0.0f;
 
-    auto load_words = [&](int s, uint32_t (&a)[RN], uint32_t (&b)[BITS][RM]) {
+    auto load_words = [&](int s, uint32_t (&a)[WBITS][RN], uint32_t (&b)[BITS][RM]) {
         // Branch-free on purpose (a branch here would make every step wait for its own loads).
         // Odd word count: the weight array carries one extra all-zero word row, so the upper lane
         // half of the last step multiplies by zero; its activation load then reads one row past
         // the plane, which is still inside the packed buffer (the next plane, or the Mp column
         // sums that follow the last plane) and, being FP4, cannot be a NaN or an infinity.
         const int ss = min(s, steps - 1);                     // past the end: harmless re-read, never used
-        const uint32_t* arow = p.signT + (size_t)(2 * ss) * p.Np;
 #pragma unroll
-        for (int t = 0; t < RN; ++t) a[t] = arow[aoff[t]];
+        for (int pl = 0; pl < WBITS; ++pl) {
+            const uint32_t* arow = p.signT + pl * p.wplane_stride + (size_t)(2 * ss) * p.Np;
+#pragma unroll
+            for (int t = 0; t < RN; ++t) a[pl][t] = arow[aoff[t]];
+        }
 #pragma unroll
         for (int pl = 0; pl < BITS; ++pl) {
             const uint32_t* brow = p.planes + pl * plane_stride + (size_t)(2 * ss) * p.Mp;
@@ -88,22 +101,22 @@ __global__ __launch_bounds__(256) void k_binary_mfma(const MfmaParams p) {
     // A ring of kRing word sets (set s % kRing holds the words of step s) and two operand sets used
     // alternately: the loads of step s+kRing are issued during step s and first touched in step
     // s+kRing-1, so kRing-1 whole steps of work cover their latency.  No register copies.
-    constexpr int kRing = (RN + BITS * RM) <= 4 ? 16 : 8;    // ~1.5 us of HBM latency to cover
-    uint32_t aw[kRing][RN], bw[kRing][BITS][RM];
+    constexpr int kRing = (WBITS * RN + BITS * RM) <= 4 ? 16 : 8;    // ~1.5 us of HBM latency to cover
+    uint32_t aw[kRing][WBITS][RN], bw[kRing][BITS][RM];
     Frag<RN, RM> f[2];
     clear_upper(f[0]);
     clear_upper(f[1]);
 #pragma unroll
     for (int q = 0; q < kRing; ++q) load_words(q, aw[q], bw[q]);
-    expand<BITS, RN, RM>(aw[0], bw[0], f[0]);
+    expand<WBITS, BITS, RN, RM>(aw[0], bw[0], f[0]);
 
-    constexpr int kValuPerMfma = (7 * RN + (BITS == 2 ? 15 : 7) * RM + RN * RM - 1) / (RN * RM);
+    constexpr int kValuPerMfma = ((WBITS == 2 ? 15 : 7) * RN + (BITS == 2 ? 15 : 7) * RM + RN * RM - 1) / (RN * RM);
     // The main loop runs whole groups of kRing steps as straight-line code (no branch between a
     // load and its use); the remainder (at most kRing-1 steps) is finished below.
     auto one_step = [&](int s, int q) {
         const Frag<RN, RM>& cur = f[q & 1];
         load_words(s + kRing, aw[q], bw[q]);                                      // words of step s+kRing
-        expand<BITS, RN, RM>(aw[(q + 1) % kRing], bw[(q + 1) % kRing], f[(q + 1) & 1]);   // operands of step s+1
+        expand<WBITS, BITS, RN, RM>(aw[(q + 1) % kRing], bw[(q + 1) % kRing], f[(q + 1) & 1]);   // operands of step s+1
 #pragma unroll
         for (int t = 0; t < RN; ++t)
 #pragma unroll
@@ -128,7 +141,10 @@ __global__ __launch_bounds__(256) void k_binary_mfma(const MfmaParams p) {
     // C layout of the 32x32 tile: lane (i, g), register r  ->  row 8*(r/4) + 4*g + (r%4), column i.
     // Rows are in the layer's own order here (the dense part needs no load balancing), so the
     // epilogue is straight-line: no index loads between the stores.
-    int32_t* out = p.P + (size_t)(slot_base + 4 * g) * p.M + m_base + i;
+    const size_t out0 = (size_t)(slot_base + 4 * g) * p.M + m_base + i;
+    int cs[RM];
+#pragma unroll
+    for (int u = 0; u < RM; ++u) cs[u] = EPI == kRawProduct ? 0 : p.colsum[min(m_base + 32 * u + i, p.Mp - 1)];
 #pragma unroll
     for (int t = 0; t < RN; ++t) {
 #pragma unroll
@@ -137,7 +153,12 @@ __global__ __launch_bounds__(256) void k_binary_mfma(const MfmaParams p) {
             if (slot_base + 4 * g + row >= p.Np) continue;
 #pragma unroll
             for (int u = 0; u < RM; ++u) {
-                if (m_base + 32 * u + i < p.M) out[(size_t)row * p.M + 32 * u] = (int)(acc[t][u][r] * 4.0f);
+                if (m_base + 32 * u + i >= p.M) continue;
+                const size_t at = out0 + (size_t)row * p.M + 32 * u;
+                const int P = (int)(acc[t][u][r] * 4.0f);
+                if (EPI == kRawProduct) static_cast<int32_t*>(p.out)[at] = P;
+                else if (EPI == kInt22) static_cast<int32_t*>(p.out)[at] = 2 * P - 3 * cs[u];
+                else static_cast<float*>(p.out)[at] = (float)(p.scale * (double)(2 * P - 3 * cs[u]));
             }
         }
     }
@@ -154,13 +175,14 @@ __global__ __launch_bounds__(256) void k_finalize_int(int32_t* __restrict__ PD, 
     PD[t] = BITS == 2 ? 2 * P - colsum[m] : 4 * P - rowsum[n] - 2 * colsum[m];
 }
 
-template <int BITS, int RN, int RM>
+template <int WBITS, int BITS, int RN, int RM, int EPI>
 void launch_shape(MfmaParams p, int waves_m, hipStream_t s) {
     const int waves_n = 4 / waves_m;
     p.waves_m = waves_m;
     p.tiles_m = (p.Mp + 32 * RM * waves_m - 1) / (32 * RM * waves_m);
     const int tiles_n = (p.Np + 32 * RN * waves_n - 1) / (32 * RN * waves_n);
-    hipLaunchKernelGGL((k_binary_mfma<BITS, RN, RM>), dim3((unsigned)(p.tiles_m * tiles_n)), dim3(256), 0, s, p);
+    hipLaunchKernelGGL((k_binary_mfma<WBITS, BITS, RN, RM, EPI>), dim3((unsigned)(p.tiles_m * tiles_n)), dim3(256), 0, s,
+                       p);
 }
 
 struct TileChoice {
@@ -168,29 +190,17 @@ struct TileChoice {
     int cycles;      // issue cycles per K step of 64 for one wave (expansion + loads + MFMA issue), 2-bit
 };
 
-}  // namespace
-
-// Raw product P (see above) into `P` (N*M int32).  Picks the wave tile that minimises
-// (rounds of waves over 1024 SIMDs) x (cycles per K step of that tile).
-int launch_binary_mfma(const LayerDev& L, const uint32_t* planes, int M, int bits, int32_t* P, hipStream_t s) {
-    const int Mp = kWave * ((M + kWave - 1) / kWave);
-    if ((long long)2 * L.N >= (1LL << 30) || (long long)2 * Mp >= (1LL << 30)) return APB_ERR_SHAPE;
-    MfmaParams p;
-    p.signT = L.signC;                                        // rows in the layer's own order
-    p.planes = planes;
-    p.P = P;
-    p.Np = L.N;
-    p.Kw = L.Kw;
-    p.Mp = Mp;
-    p.M = M;
-    p.tiles_m = p.waves_m = 0;
-
+// Picks the wave tile that minimises (rounds of waves over 1024 SIMDs) x (cycles per K step of that
+// tile) and launches kernel variant (WBITS, BITS, EPI).
+template <int WBITS, int BITS, int EPI>
+int launch_best_tile(MfmaParams p, int N, hipStream_t s) {
+    if ((long long)2 * N >= (1LL << 30) || (long long)2 * p.Mp >= (1LL << 30)) return APB_ERR_SHAPE;
     static const TileChoice menu[] = {{4, 2, 336}, {2, 4, 408}, {2, 2, 256}, {2, 1, 180}, {1, 1, 144}};
     int best = 0;
     double best_cost = 1e300;
     for (int c = 0; c < 5; ++c) {
-        const long long waves = (long long)((L.N + 32 * menu[c].rn - 1) / (32 * menu[c].rn)) *
-                                ((Mp + 32 * menu[c].rm - 1) / (32 * menu[c].rm));
+        const long long waves = (long long)((N + 32 * menu[c].rn - 1) / (32 * menu[c].rn)) *
+                                ((p.Mp + 32 * menu[c].rm - 1) / (32 * menu[c].rm));
         const double rounds = (double)((waves + 1023) / 1024);
         const double cost = rounds * menu[c].cycles;
         if (cost < best_cost) {
@@ -200,12 +210,10 @@ int launch_binary_mfma(const LayerDev& L, const uint32_t* planes, int M, int bit
     }
     const int rn = menu[best].rn, rm = menu[best].rm;
     // Waves of a workgroup: two along n when the layer has the rows for them, the rest along m.
-    const int waves_n = 32 * rn * 2 <= L.N ? 2 : 1;
+    const int waves_n = 32 * rn * 2 <= N ? 2 : 1;
     const int waves_m = 4 / waves_n;
-#define APB_SHAPE(RN, RM)                                                                  \
-    if (rn == RN && rm == RM) {                                                            \
-        if (bits == 1) launch_shape<1, RN, RM>(p, waves_m, s); else launch_shape<2, RN, RM>(p, waves_m, s); \
-    }
+#define APB_SHAPE(RN, RM) \
+    if (rn == RN && rm == RM) launch_shape<WBITS, BITS, RN, RM, EPI>(p, waves_m, s);
     APB_SHAPE(4, 2)
     APB_SHAPE(2, 4)
     APB_SHAPE(2, 2)
@@ -214,6 +222,38 @@ int launch_binary_mfma(const LayerDev& L, const uint32_t* planes, int M, int bit
 #undef APB_SHAPE
     APB_HIP(hipGetLastError());
     return APB_OK;
+}
+
+}  // namespace
+
+// Raw product P (see above) of a binary layer into `P` (N*M int32).
+int launch_binary_mfma(const LayerDev& L, const uint32_t* planes, int M, int bits, int32_t* P, hipStream_t s) {
+    MfmaParams p{};
+    p.signT = L.signC;                                        // rows in the layer's own order
+    p.planes = planes;
+    p.out = P;
+    p.Np = L.N;
+    p.Kw = L.Kw;
+    p.Mp = kWave * ((M + kWave - 1) / kWave);
+    p.M = M;
+    return bits == 1 ? launch_best_tile<1, 1, kRawProduct>(p, L.N, s) : launch_best_tile<1, 2, kRawProduct>(p, L.N, s);
+}
+
+// 2/2 routine: D22 (int32) when Y == nullptr, else Y = scale * D22 (float).
+int launch_gemm_2_2(const uint32_t* wplanesC, int N, int Kw, const uint32_t* planes, const int32_t* colsum, int M,
+                    double scale, int32_t* D, float* Y, hipStream_t s) {
+    MfmaParams p{};
+    p.signT = wplanesC;
+    p.wplane_stride = (size_t)(2 * ((Kw + 1) / 2)) * N;
+    p.planes = planes;
+    p.colsum = colsum;
+    p.out = Y ? static_cast<void*>(Y) : static_cast<void*>(D);
+    p.scale = scale;
+    p.Np = N;
+    p.Kw = Kw;
+    p.Mp = kWave * ((M + kWave - 1) / kWave);
+    p.M = M;
+    return Y ? launch_best_tile<2, 2, kFloat22>(p, N, s) : launch_best_tile<2, 2, kInt22>(p, N, s);
 }
 
 int launch_finalize_int(const LayerDev& L, const int32_t* colsum, int M, int bits, int32_t* PD, hipStream_t s) {

@@ -130,6 +130,32 @@ __global__ __launch_bounds__(kBlock) void k_slot_major_signs(const uint32_t* __r
     signT[t] = (n >= 0 && j < Kw) ? sign[(size_t)n * Kw + j] : 0u;   // word rows past Kw are zero padding
 }
 
+// Sec. IV "2/2": level index q = clamp(floor(w / s_w) + 2, 0, 3) of every weight (the weight it
+// stands for is (q - 3/2) * s_w), packed as two bit-planes.  One thread per (row, word): it reads
+// its 32 weights and writes the word of each plane twice, in the canonical [2][N][Kw] order and in
+// the word-major [2][Kw2][N] order the matrix-core kernel reads (pad word row = 0).  Offline work.
+__global__ __launch_bounds__(kBlock) void k_w2_pack(const float* __restrict__ W, int N, int K, int Kw, int Kw2,
+                                                    float inv_step, uint32_t* __restrict__ planes,
+                                                    uint32_t* __restrict__ planesC) {
+    const long long t = (long long)blockIdx.x * kBlock + threadIdx.x;
+    if (t >= (long long)N * Kw2) return;
+    const int j = (int)(t / N), n = (int)(t % N);
+    uint32_t w0 = 0, w1 = 0;
+    if (j < Kw) {
+        const float* src = W + (size_t)n * K + 32 * j;
+        const int valid = min(32, K - 32 * j);
+        for (int i = 0; i < valid; ++i) {
+            const uint32_t q = (uint32_t)(int)fminf(3.0f, fmaxf(0.0f, floorf(src[i] * inv_step) + 2.0f));
+            w0 |= (q & 1u) << i;
+            w1 |= (q >> 1) << i;
+        }
+        planes[(size_t)n * Kw + j] = w0;
+        planes[((size_t)N + n) * Kw + j] = w1;
+    }
+    planesC[(size_t)j * N + n] = w0;
+    planesC[((size_t)Kw2 + j) * N + n] = w1;
+}
+
 // chunk_ptr[c][i]: index of the first residual of the row in slot i whose column is >= 256*c
 // (lower bound in the ascending column list); slot_valsum[i]: float64 sum of that row's residuals.
 __global__ __launch_bounds__(kBlock) void k_slot_tables(const int32_t* __restrict__ perm,
@@ -175,6 +201,15 @@ int launch_slot_tables(const int32_t* perm, const int32_t* row_ptr, const int32_
 int launch_inlier_abs_sum(const float* W, long long count, float delta, double* part_sum, long long* part_cnt,
                           int parts, hipStream_t s) {
     hipLaunchKernelGGL(k_inlier_abs_sum, dim3(parts), dim3(kBlock), 0, s, W, count, delta, part_sum, part_cnt);
+    APB_HIP(hipGetLastError());
+    return APB_OK;
+}
+
+int launch_w2_pack(const float* W, int N, int K, float inv_step, uint32_t* planes, uint32_t* planesC, hipStream_t s) {
+    const int Kw = (K + 31) / 32, Kw2 = 2 * ((Kw + 1) / 2);
+    const long long total = (long long)N * Kw2;
+    hipLaunchKernelGGL(k_w2_pack, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, W, N, K, Kw,
+                       Kw2, inv_step, planes, planesC);
     APB_HIP(hipGetLastError());
     return APB_OK;
 }

@@ -1,7 +1,7 @@
 // Bit-packed operands -> FP4 (E2M1) operand registers of v_mfma_scale_f32_32x32x64_f8f6f4, shared by
 // the matrix-core kernels.  A weight bit becomes the nibble 0b0001 (= 0.5), the two plane bits of an
-// activation become the nibble p0 | p1<<1 (= 0.5, 1.0, 1.5 for codes 1, 2, 3 -- additive in the
-// planes, so no table).  Products are multiples of 1/4 and every partial sum is far below 2^24 of
+// activation (or of a 2-bit weight) become the nibble p0 | p1<<1 (= 0.5, 1.0, 1.5 for codes 1, 2,
+// 3 -- additive in the planes, so no table).  Products are multiples of 1/4 and every partial sum is far below 2^24 of
 // those, so a float accumulator holds P/4 exactly, P = sum_k bit * code.
 //   lane l = 32*g + i (i: row of A / column of B, g: lane half) owns word 2*s+g of K step s;
 //   nibble t of operand dword d  <->  bit d + 4*t of that word (the same for both operands, which is
@@ -38,28 +38,31 @@ __device__ __forceinline__ void clear_upper(Frag<RN, RM>& f) {
         for (int d = 4; d < 8; ++d) f.b[u][d] = 0;
 }
 
-template <int BITS, int RN, int RM>
-__device__ __forceinline__ void expand(const uint32_t (&aw)[RN], const uint32_t (&bw)[BITS][RM], Frag<RN, RM>& f) {
+// One operand register set from the words of NB bit-planes (NB = 1: a bit; NB = 2: a 2-bit code).
+template <int NB>
+__device__ __forceinline__ void expand_words(uint32_t w0, uint32_t w1, v8i& f) {
+    if (NB == 1) {
 #pragma unroll
-    for (int t = 0; t < RN; ++t) {
+        for (int d = 0; d < 4; ++d) f[d] = (int)((w0 >> d) & kNib);
+    } else {
 #pragma unroll
-        for (int d = 0; d < 4; ++d) f.a[t][d] = (int)((aw[t] >> d) & kNib);
-    }
-#pragma unroll
-    for (int u = 0; u < RM; ++u) {
-        if (BITS == 1) {
-#pragma unroll
-            for (int d = 0; d < 4; ++d) f.b[u][d] = (int)((bw[0][u] >> d) & kNib);
-        } else {
-            const uint32_t z1 = bw[BITS - 1][u];
-#pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                // the plane-1 bit goes one position up inside the nibble: bit d+4t -> bit 4t+1
-                const uint32_t hi = d == 0 ? (z1 << 1) : (z1 >> (d - 1));
-                f.b[u][d] = (int)((hi & (kNib << 1)) | ((bw[0][u] >> d) & kNib));
-            }
+        for (int d = 0; d < 4; ++d) {
+            // the plane-1 bit goes one position up inside the nibble: bit d+4t -> bit 4t+1
+            const uint32_t hi = d == 0 ? (w1 << 1) : (w1 >> (d - 1));
+            f[d] = (int)((hi & (kNib << 1)) | ((w0 >> d) & kNib));
         }
     }
+}
+
+// WBITS weight planes (1: sign bits of a binary layer; 2: level indices of 2-bit weights), BITS
+// activation planes.
+template <int WBITS, int BITS, int RN, int RM>
+__device__ __forceinline__ void expand(const uint32_t (&aw)[WBITS][RN], const uint32_t (&bw)[BITS][RM],
+                                       Frag<RN, RM>& f) {
+#pragma unroll
+    for (int t = 0; t < RN; ++t) expand_words<WBITS>(aw[0][t], aw[WBITS - 1][t], f.a[t]);
+#pragma unroll
+    for (int u = 0; u < RM; ++u) expand_words<BITS>(bw[0][u], bw[BITS - 1][u], f.b[u]);
 }
 
 __device__ __forceinline__ v16f mfma_fp4(const v8i& a, const v8i& b, const v16f& c) {

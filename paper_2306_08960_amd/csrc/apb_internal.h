@@ -89,8 +89,21 @@ int launch_sparse_epilogue(const LayerDev& L, const uint32_t* planes, const int3
 int launch_binary_mfma(const LayerDev& L, const uint32_t* planes, int M, int bits, int32_t* P, hipStream_t s);
 int launch_finalize_int(const LayerDev& L, const int32_t* colsum, int M, int bits, int32_t* PD, hipStream_t s);
 
+// 2/2 routine: quantize + pack 2-bit weights (canonical [2][N][Kw] and word-major [2][Kw2][N], Kw2 =
+// Kw rounded up to even with a zero pad row), and the product itself (D22 when Y == nullptr)
+int launch_w2_pack(const float* W, int N, int K, float inv_step, uint32_t* planes, uint32_t* planesC, hipStream_t s);
+int launch_gemm_2_2(const uint32_t* wplanesC, int N, int Kw, const uint32_t* planes, const int32_t* colsum, int M,
+                    double scale, int32_t* D, float* Y, hipStream_t s);
+
 }  // namespace apb
 
 struct apb_layer {
     apb::LayerDev d;
+};
+
+struct apb_w2 {
+    int N = 0, K = 0, Kw = 0;
+    float step_w = 0.f;
+    uint32_t* planes = nullptr;    // [2][N][Kw]   canonical bit-planes of the level indices
+    uint32_t* planesC = nullptr;   // [2][Kw2][N]  the same, word-major, for the matrix-core kernel
 };

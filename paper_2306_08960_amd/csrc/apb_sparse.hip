@@ -158,13 +158,13 @@ __device__ __forceinline__ void binary_tile_to_lds(const uint32_t* __restrict__ 
     const size_t plane_stride = (size_t)Kw * Mp;
     const int steps = (Kw + 1) / 2;
     constexpr int kRing = 4;
-    uint32_t aw[kRing][1], bw[kRing][BITS][1];
+    uint32_t aw[kRing][1][1], bw[kRing][BITS][1];
     Frag<1, 1> f[2];
     clear_upper(f[0]);
     clear_upper(f[1]);
-    auto load_words = [&](int st, uint32_t (&a)[1], uint32_t (&b)[BITS][1]) {
+    auto load_words = [&](int st, uint32_t (&a)[1][1], uint32_t (&b)[BITS][1]) {
         const int ss = min(st, steps - 1);                      // past the end: harmless re-read, never used
-        a[0] = (signT + (size_t)(2 * ss) * Np)[aoff];
+        a[0][0] = (signT + (size_t)(2 * ss) * Np)[aoff];
 #pragma unroll
         for (int pl = 0; pl < BITS; ++pl) b[pl][0] = (planes + pl * plane_stride + (size_t)(2 * ss) * Mp)[boff];
     };
@@ -173,11 +173,11 @@ __device__ __forceinline__ void binary_tile_to_lds(const uint32_t* __restrict__ 
     for (int r = 0; r < 16; ++r) c[r] = 0.0f;
 #pragma unroll
     for (int q = 0; q < kRing; ++q) load_words(q, aw[q], bw[q]);
-    expand<BITS, 1, 1>(aw[0], bw[0], f[0]);
+    expand<1, BITS, 1, 1>(aw[0], bw[0], f[0]);
     auto one_step = [&](int st, int q) {
         const Frag<1, 1>& cur = f[q & 1];
         load_words(st + kRing, aw[q], bw[q]);
-        expand<BITS, 1, 1>(aw[(q + 1) % kRing], bw[(q + 1) % kRing], f[(q + 1) & 1]);
+        expand<1, BITS, 1, 1>(aw[(q + 1) % kRing], bw[(q + 1) % kRing], f[(q + 1) & 1]);
         c = mfma_fp4(cur.a[0], cur.b[0], c);
     };
     int s0 = 0;

@@ -15,7 +15,7 @@ pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libapb.so not b
 def _declared():
     text = open(os.path.join(ROOT, "include", "apb.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(apb_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(apb_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported():
@@ -30,7 +30,7 @@ def test_binding_names_match_header():
     from paper_2306_08960_amd import binding
     assert sorted(binding.EXPORTS) == _declared()
     for n in binding.EXPORTS:
-        if n not in ("apb_layer_free", "apb_strerror", "apb_last_hip_error"):
+        if n not in ("apb_layer_free", "apb_w2_free", "apb_strerror", "apb_last_hip_error"):
             assert hasattr(binding, n), n
 
 
@@ -69,6 +69,17 @@ def test_argument_errors_without_touching_the_gpu():
     assert lib.apb_layer_info(None, None, None, None, None, None) == b.APB_ERR_NULL
     assert lib.apb_layer_export(None, None, None, None, None, None, None) == b.APB_ERR_NULL
     lib.apb_layer_free(None)
+    # 2/2 routine
+    assert lib.apb_w2_pack(None, 4, 4, 0.1, None, ctypes.byref(out)) == b.APB_ERR_NULL
+    assert lib.apb_w2_pack(fake, 4, 4, 0.1, None, None) == b.APB_ERR_NULL
+    assert lib.apb_w2_pack(fake, 0, 4, 0.1, None, ctypes.byref(out)) == b.APB_ERR_SHAPE
+    for bad in (0.0, -1.0, nan, float("inf")):
+        assert lib.apb_w2_pack(fake, 4, 4, bad, None, ctypes.byref(out)) == b.APB_ERR_VALUE
+    assert out.value is None
+    assert lib.apb_w2_export(None, fake, None) == b.APB_ERR_NULL
+    assert lib.apb_gemm_2_2_int(None, fake, 4, fake, None) == b.APB_ERR_NULL
+    assert lib.apb_gemm_2_2(None, fake, 4, 1.0, fake, None) == b.APB_ERR_NULL
+    lib.apb_w2_free(None)
     for code in range(-6, 1):
         assert b.strerror(code) and "unknown" not in b.strerror(code)
     assert "unknown" in b.strerror(-99)

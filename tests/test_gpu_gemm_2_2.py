@@ -1,0 +1,82 @@
+"""Parity of the 2/2 routine (Sec. IV "2/2": 2-bit weights x 2-bit activations) with the CPU oracle,
+through the C ABI, on the same seeded inputs.  Bars: bit-exact for the packed weight planes and the
+integer product D22; max relative error 1e-5 for Y, every element, no floor."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import apb_oracle as o
+from paper_2306_08960_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def b():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2306_08960_amd import binding
+    binding.load()
+    return binding
+
+
+def check_2_2(b, W, step_w, X, step_a, rows=None, tag=""):
+    """Pack, multiply and compare; `rows` restricts the oracle product to a sample of weight rows."""
+    N, K = W.shape
+    M = X.shape[1]
+    print(f"[case 2/2] {tag} N={N} K={K} M={M} step_w={float(step_w):.4g} step_a={float(step_a):.4g}", flush=True)
+    q = o.quantize_weights_2bit(W, step_w)
+    c = o.quantize(X, 2, step_a)
+    Wd = torch.from_numpy(W).cuda()
+    Xd = torch.from_numpy(X).cuda()
+    w2 = b.apb_w2_pack(Wd, float(step_w))
+    planes = b.apb_w2_export(w2).cpu().numpy().view(np.uint32)
+    assert np.array_equal(planes, o.pack_weight_planes(q))
+    packed = b.apb_quantize_acts(Xd, 2, float(step_a))
+    D = b.apb_gemm_2_2_int(w2, packed, M).cpu().numpy()
+    Y = b.apb_gemm_2_2(w2, packed, M, float(step_a)).cpu().numpy()
+    torch.cuda.synchronize()
+    sel = np.arange(N) if rows is None else np.asarray(rows)
+    ref = o.gemm_2_2(q[sel], c, step_w, step_a)
+    assert np.array_equal(D[sel], ref["D"])
+    err = np.abs(Y[sel].astype(np.float64) - ref["Y"].astype(np.float64))
+    assert np.all(err <= REL_TOL * np.abs(ref["Y"].astype(np.float64))), float(err.max())
+    w2.free()
+
+
+EDGE_SHAPES = [(1, 1, 1), (1, 31, 1), (2, 32, 64), (3, 33, 65), (33, 64, 63), (31, 95, 127), (65, 257, 193),
+               (100, 1000, 300), (7, 4100, 5), (130, 200, 70)]
+
+
+@pytest.mark.parametrize("N,K,M", EDGE_SHAPES)
+def test_edge_shapes(b, N, K, M):
+    W, _, X, step = synth.random_case(2200 + N * 7 + K + M, N, K, M, 2, rho=0.05)
+    check_2_2(b, W, np.float32(0.04), X, step, tag="edge")
+
+
+def test_special_values_and_degenerate_steps(b):
+    W = np.zeros((4, 70), dtype=np.float32)
+    W[0] = [0.0, -0.0, 0.49, 0.5, 0.99, 1.0, 7.0, -1e-30, -0.5, -0.51, -1.0, -1.01, -9.0, np.inf] * 5
+    W[1] = np.float32(1e-40)
+    W[2] = -np.float32(1e-40)
+    W[3] = np.random.default_rng(3).standard_normal(70).astype(np.float32)
+    X = np.maximum(np.random.default_rng(4).standard_normal((70, 67)), 0).astype(np.float32) * 2
+    check_2_2(b, W, np.float32(0.5), X, np.float32(0.75), tag="boundaries")
+    check_2_2(b, W, np.float32(1e6), X, np.float32(0.75), tag="every weight in the two middle cells")
+    check_2_2(b, W, np.float32(1e-6), X, np.float32(1e-3), tag="every weight and activation saturated")
+
+
+@pytest.mark.parametrize("name", ["C2", "C3_r05_b2", "C5a"])
+def test_benchmark_shapes(b, name):
+    cfg = synth.CONFIGS[name]
+    W, _, X, step = synth.make_layer(cfg)
+    step_w = np.float32(np.std(W))
+    check_2_2(b, W, step_w, X, step, tag=name)
+
+
+def test_largest_shape_on_sampled_rows(b):
+    cfg = synth.CONFIGS["C5b"]
+    W, _, X, step = synth.make_layer(cfg)
+    rows = np.random.default_rng(55).choice(cfg.N, size=24, replace=False)
+    check_2_2(b, W, np.float32(np.std(W)), X, step, rows=np.sort(rows), tag="C5b, 24 sampled rows")
