@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--workload", default="C2", help="name in paper_2306_08960_amd.synth.CONFIGS")
     ap.add_argument("--all", action="store_true", help="also time every other benchmark layer (reported in 'others')")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--routine", default="apb", choices=["apb", "gemm_2_2"],
+                    help="apb: the APB layer forward (the headline metric); gemm_2_2: the 2-bit x 2-bit "
+                         "product of Sec. IV on the same shapes (weights packed offline)")
     return ap.parse_args()
 
 
@@ -147,6 +150,75 @@ def run_workload(name, steps, warmup):
     return res, (cfg, W, delta, X, step)
 
 
+def run_gemm_2_2(name, steps, warmup):
+    """Step = apb_quantize_acts (2 bits) + apb_gemm_2_2 on the workload's W and X; weights packed once."""
+    import torch
+    from paper_2306_08960_amd import binding as b
+    from paper_2306_08960_amd import synth
+
+    cfg = synth.CONFIGS[name]
+    W, _, X, step = synth.make_layer(cfg)
+    N, K, M = cfg.N, cfg.K, cfg.M
+    step_w = float(np.std(W))
+    w2 = b.apb_w2_pack(torch.from_numpy(W).cuda(), step_w)
+    Xd = torch.from_numpy(X).cuda()
+    packed = b.alloc_packed(K, M, 2)
+    Y = torch.empty((N, M), dtype=torch.float32, device="cuda")
+    s = float(step)
+
+    def quant():
+        b.apb_quantize_acts(Xd, 2, s, packed=packed)
+
+    def gemm():
+        b.apb_gemm_2_2(w2, packed, M, s, Y=Y)
+
+    for _ in range(warmup):
+        quant()
+        gemm()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        quant()
+        gemm()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / steps
+    ms_quant, ms_gemm, ms_event_record = time_in_step(quant, gemm, steps, ms_step)
+    ops = 2.0 * N * K * M
+    Kw, Mp = (K + 31) // 32, 64 * ((M + 63) // 64)
+    gemm_bytes = 8.0 * N * Kw + 8.0 * Kw * Mp + 4.0 * Mp + 4.0 * N * M
+    t_hbm, t_mfma = gemm_bytes / (HBM_PEAK_GBS * 1e9), ops / (MFMA_FP4_PEAK_TFLOPS * 1e12)
+    t = ms_gemm * 1e-3
+    if t_hbm >= t_mfma:
+        roof = {"kernel": "k_binary_mfma<2,2,...>", "bound": "hbm", "achieved": gemm_bytes / t / 1e9,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    else:
+        roof = {"kernel": "k_binary_mfma<2,2,...>", "bound": "mfma", "achieved": ops / t / 1e12,
+                "peak": MFMA_FP4_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    roof |= {"frac": roof["achieved"] / roof["peak"], "traffic": None, "ms": ms_gemm,
+             "floor_us": {"hbm": t_hbm * 1e6, "mfma_fp4": t_mfma * 1e6}}
+    w2.free()
+    res = {"workload": name, "N": N, "K": K, "M": M, "ms_per_step": ms_step, "ms_quantize": ms_quant, "ms_gemm": ms_gemm,
+           "ms_event_record_removed": ms_event_record, "gops_step": ops / (ms_step * 1e-3) / 1e9,
+           "gops_gemm": ops / t / 1e9, "roofline_gemm": roof}
+    del Xd, packed, Y
+    torch.cuda.empty_cache()
+    return res, (cfg, W, step_w, X, step)
+
+
+def cpu_baseline_2_2(cfg, W, step_w, X, step):
+    """The CPU oracle of the 2/2 routine (quantize both operands, integer product, scaling) on the
+    first columns of the workload; the product is a float64 library matmul on all host cores."""
+    from oracle import apb_oracle as o
+    cores = max(1, len(os.sched_getaffinity(0)))
+    m = int(max(64, min(cfg.M, 20e9 * cores ** 0.5 / (2.0 * cfg.N * cfg.K))))
+    Xs = np.ascontiguousarray(X[:, :m])
+    t0 = time.perf_counter()
+    o.gemm_2_2(o.quantize_weights_2bit(W, step_w), o.quantize(Xs, 2, step), step_w, step)
+    dt = time.perf_counter() - t0
+    return {"value": 2.0 * cfg.N * cfg.K * m / dt / 1e9, "unit": "GOPS", "cores": cores, "kind": "oracle",
+            "sample": f"first {m} of {cfg.M} columns of {cfg.name}, one pass (quantize both operands + product), {dt:.2f} s"}
+
+
 def cpu_baseline(cfg, W, delta, X, step):
     """The CPU oracle (quantize, pack, popcount integer part, CSR part, epilogue) on the first
     columns of the same workload, all host cores this process may use."""
@@ -187,6 +259,30 @@ def main():
     if args.workload not in synth.CONFIGS:
         print(f"bench.py: unknown workload {args.workload}; choose from {sorted(synth.CONFIGS)}", file=sys.stderr)
         sys.exit(2)
+
+    if args.routine == "gemm_2_2":
+        res, inputs = run_gemm_2_2(args.workload, args.steps, args.warmup)
+        cfg = inputs[0]
+        quant_bytes = 4.0 * cfg.K * cfg.M + 8.0 * ((cfg.K + 31) // 32) * 64 * ((cfg.M + 63) // 64) + 4.0 * 64 * ((cfg.M + 63) // 64)
+        roof_q = {"kernel": "k_quantize_pack", "bound": "hbm", "achieved": quant_bytes / (res["ms_quantize"] * 1e-3) / 1e9,
+                  "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": None, "ms": res["ms_quantize"]}
+        roof_q["frac"] = roof_q["achieved"] / roof_q["peak"]
+        out = {
+            "metric": "2/2 GEMM (2-bit weights x 2-bit activations, Sec. IV) GOPS", "value": res["gops_step"],
+            "unit": "GOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "fp4 (exact 2-bit codes) on MFMA, f32 out", "data": "synthetic",
+            "config": {"workload": f"{cfg.name}: {cfg.note}", "N": cfg.N, "K": cfg.K, "M": cfg.M,
+                       "step": "apb_quantize_acts (2 bits) + apb_gemm_2_2, inputs resident in HBM, weights packed offline"},
+            "ms_quantize": res["ms_quantize"], "ms_gemm": res["ms_gemm"], "gops_gemm_only": res["gops_gemm"],
+            "ms_event_record_removed": res["ms_event_record_removed"],
+            "roofline": roof_q if res["ms_quantize"] >= res["ms_gemm"] else res["roofline_gemm"],
+            "roofline_gemm": res["roofline_gemm"], "roofline_quantize": roof_q,
+        }
+        if not args.no_cpu_baseline:
+            out["cpu_baseline"] = cpu_baseline_2_2(*inputs)
+        print(json.dumps(out))
+        return
 
     res, inputs = run_workload(args.workload, args.steps, args.warmup)
     cfg = inputs[0]
