@@ -1,14 +1,17 @@
-// Sparse part and epilogue of apb_forward (Sec. III Eqs. 12-13):
+// The forward kernel of apb_forward (Sec. III Eqs. 12-13):
 //     Y[n,m] = s * ( alpha * D[n,m] + sum_{j in row n} val_j * c[col_j, m] )
-// The matrix-core kernel has left the raw binary product P in the output buffer; this kernel turns
-// it into D, adds the residual part in float64 and overwrites the same elements with Y (every lane
-// reads and writes only its own outputs, so the pass is in place).
+// In its fused mode (workgroups of 4 or 8 waves) the kernel first computes the binary product of its
+// tile on the matrix cores (binary_tile_to_lds below), starts its float64 row sums at alpha * D,
+// adds the residual part and writes Y: nothing but Y goes to HBM.  In its other mode (layers of at
+// most 32 rows) the stand-alone matrix-core kernel has left the raw product P in the output buffer
+// and this kernel overwrites the same elements with Y (every lane reads and writes only its own
+// outputs, so the pass is in place).
 //
-// Mapping: lanes run along m, so residual columns and values are wave-uniform and arrive through
-// the scalar path.  A workgroup (up to 8 waves, each owning a tile of 16 weight rows in launch-slot
-// order) shares one strip of 64 output columns and walks K in chunks of 256:
+// Mapping of the residual part: lanes run along m, so residual columns and values are wave-uniform
+// and arrive through the scalar path.  A workgroup (up to 8 waves, each owning a tile of 16 weight
+// rows in launch-slot order) shares one strip of 64 output columns and walks K in chunks of 256:
 //   1. the waves expand the chunk's activation bit-planes into a byte-per-activation code table in
-//      LDS (row = output column, 256 codes + 4 pad bytes, so the 64 lanes of a wave hit distinct
+//      LDS (row = output column, 256 bytes + 4 pad bytes, so the 64 lanes of a wave hit distinct
 //      banks when they read the same k);
 //   2. after a barrier each wave streams the residuals of its 16 rows that fall in the chunk.  They
 //      were laid out at compress time as ONE flat run per (tile, chunk), padded to whole blocks of
@@ -16,8 +19,8 @@
 //      consecutive vector registers, and the multiply-add of a residual addresses its row's pair
 //      through the register-index mode: one scalar instruction (index <- low byte of the entry
 //      key = 2*row) and one v_fma_f64.  With the address add (column taken straight from byte 1 of
-//      the key), the ds_read_u8 and the convert that is five instructions per residual and wave,
-//      and no branch.
+//      the key) and a ds_read_u8_d16_hi whose result is the float64 multiplicand as it stands
+//      (see kCodeBytes), that is four instructions per residual and wave, and no branch.
 // Tiles are filled by dealing rows in order of residual count (see balanced_slots), so the skewed
 // rows of pruned layers are spread over the waves instead of serialising one of them.
 #include "apb_fp4_expand.h"
