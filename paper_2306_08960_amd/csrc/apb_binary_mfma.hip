@@ -185,30 +185,33 @@ void launch_shape(MfmaParams p, int waves_m, hipStream_t s) {
                        p);
 }
 
-struct TileChoice {
-    int rn, rm;
-    int cycles;      // issue cycles per K step of 64 for one wave (expansion + loads + MFMA issue), 2-bit
-};
-
-// Picks the wave tile that minimises (rounds of waves over 1024 SIMDs) x (cycles per K step of that
-// tile) and launches kernel variant (WBITS, BITS, EPI).
+// Wave tile.  Small tiles put more waves on the chip (a lone wave per SIMD keeps neither the matrix
+// pipe nor the store path busy) but re-read the packed operands from L2 more often: a wave fetches
+// 256 * (WBITS*rn + BITS*rm) bytes per K step.  Measured on the benchmark shapes, the kernel slows
+// down once that re-read traffic passes roughly 200 MB (about 30 us at the L2
+// rate it sustains here), so: the smallest tile that stays under it, else the one that reads least.
 template <int WBITS, int BITS, int EPI>
 int launch_best_tile(MfmaParams p, int N, hipStream_t s) {
     if ((long long)2 * N >= (1LL << 30) || (long long)2 * p.Mp >= (1LL << 30)) return APB_ERR_SHAPE;
-    static const TileChoice menu[] = {{4, 2, 336}, {2, 4, 408}, {2, 2, 256}, {2, 1, 180}, {1, 1, 144}};
+    static const int menu[5][2] = {{1, 1}, {2, 1}, {2, 2}, {2, 4}, {4, 2}};    // smallest first
+    constexpr double kL2Budget = 200e6;
+    const double steps = (p.Kw + 1) / 2;
     int best = 0;
-    double best_cost = 1e300;
+    double best_bytes = 1e300;
     for (int c = 0; c < 5; ++c) {
-        const long long waves = (long long)((N + 32 * menu[c].rn - 1) / (32 * menu[c].rn)) *
-                                ((p.Mp + 32 * menu[c].rm - 1) / (32 * menu[c].rm));
-        const double rounds = (double)((waves + 1023) / 1024);
-        const double cost = rounds * menu[c].cycles;
-        if (cost < best_cost) {
-            best_cost = cost;
+        const double waves = (double)((N + 32 * menu[c][0] - 1) / (32 * menu[c][0])) *
+                             ((p.Mp + 32 * menu[c][1] - 1) / (32 * menu[c][1]));
+        const double bytes = waves * steps * 256.0 * (WBITS * menu[c][0] + BITS * menu[c][1]);
+        if (bytes <= kL2Budget) {
+            best = c;
+            break;
+        }
+        if (bytes < best_bytes) {
+            best_bytes = bytes;
             best = c;
         }
     }
-    const int rn = menu[best].rn, rm = menu[best].rm;
+    const int rn = menu[best][0], rm = menu[best][1];
     // Waves of a workgroup: two along n when the layer has the rows for them, the rest along m.
     const int waves_n = 32 * rn * 2 <= N ? 2 : 1;
     const int waves_m = 4 / waves_n;
