@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--workload", default="C2", help="name in paper_2306_08960_amd.synth.CONFIGS")
     ap.add_argument("--all", action="store_true", help="also time every other benchmark layer (reported in 'others')")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="square-matrix sweep of the three bitwise products (1/1, 1/2, 2/2; Sec. V protocol): one JSON "
+                         "line with the time of the product alone at each size")
     ap.add_argument("--routine", default="apb", choices=["apb", "gemm_2_2"],
                     help="apb: the APB layer forward (the headline metric); gemm_2_2: the 2-bit x 2-bit "
                          "product of Sec. IV on the same shapes (weights packed offline)")
@@ -205,6 +208,49 @@ def run_gemm_2_2(name, steps, warmup):
     return res, (cfg, W, step_w, X, step)
 
 
+def run_square_sweep(sizes=(512, 1024, 2048, 4096, 8192), iters=30):
+    """The paper's efficiency protocol (square matrices, the product alone, operands already packed) for
+    its three bitwise routines: 1/1 and 1/2 are a binary layer without residuals (integer part D through
+    apb_forward_int), 2/2 is apb_gemm_2_2_int.  Seeded normal weights, ReLU-normal activations."""
+    import torch
+    from paper_2306_08960_amd import binding as b
+    rows = []
+    for n in sizes:
+        g = torch.Generator(device="cuda").manual_seed(230608960 + n)
+        W = torch.randn((n, n), generator=g, device="cuda") * 0.05
+        X = torch.relu(torch.randn((n, n), generator=g, device="cuda"))
+        layer = b.apb_compress(W, float("inf"), alpha=0.05)
+        w2 = b.apb_w2_pack(W, 0.05)
+        p1 = b.apb_quantize_acts(X - 0.5, 1, 1.0)
+        p2 = b.apb_quantize_acts(X, 2, 0.75)
+        D = torch.empty((n, n), dtype=torch.int32, device="cuda")
+
+        def timed(fn):
+            for _ in range(3):
+                fn()
+            a, c = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            a.record()
+            for _ in range(iters):
+                fn()
+            c.record()
+            c.synchronize()
+            return a.elapsed_time(c) / iters
+
+        t11 = timed(lambda: b.apb_forward_int(layer, p1, n, 1, D=D))
+        t12 = timed(lambda: b.apb_forward_int(layer, p2, n, 2, D=D))
+        t22 = timed(lambda: b.apb_gemm_2_2_int(w2, p2, n, D=D))
+        ops = 2.0 * n ** 3
+        rows.append({"n": n, "ms_1_1": t11, "ms_1_2": t12, "ms_2_2": t22,
+                     "tops_1_1": ops / t11 / 1e9, "tops_1_2": ops / t12 / 1e9, "tops_2_2": ops / t22 / 1e9,
+                     "cost_1_2_over_1_1": t12 / t11, "cost_2_2_over_1_1": t22 / t11})
+        layer.free()
+        w2.free()
+        del W, X, p1, p2, D
+        torch.cuda.empty_cache()
+    return rows
+
+
 def cpu_baseline_2_2(cfg, W, step_w, X, step):
     """The CPU oracle of the 2/2 routine (quantize both operands, integer product, scaling) on the
     first columns of the workload; the product is a float64 library matmul on all host cores."""
@@ -260,6 +306,13 @@ def main():
         print(f"bench.py: unknown workload {args.workload}; choose from {sorted(synth.CONFIGS)}", file=sys.stderr)
         sys.exit(2)
 
+    if args.sweep:
+        print(json.dumps({"metric": "square-matrix sweep of the bitwise products (integer part alone, operands packed)",
+                          "unit": "TOPS (2*n^3 / time)", "n_gpus": 1, "data": "synthetic",
+                          "note": "1/1 and 1/2: apb_forward_int = k_binary_mfma + k_finalize_int; 2/2: apb_gemm_2_2_int; "
+                                  "the paper predicts cost ratios 2 and 8 on a popcount machine",
+                          "sweep": run_square_sweep()}))
+        return
     if args.routine == "gemm_2_2":
         res, inputs = run_gemm_2_2(args.workload, args.steps, args.warmup)
         cfg = inputs[0]
