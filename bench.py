@@ -292,8 +292,8 @@ def cpu_baseline(cfg, W, delta, X, step):
 def main():
     args = parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path shards over M with no exchange; "
-              "see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the layer shards over the columns of X with no "
+              "exchange between GPUs, so one GPU shows the whole path). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2306_08960_amd import binding as b
