@@ -309,7 +309,7 @@ def main():
     if args.sweep:
         print(json.dumps({"metric": "square-matrix sweep of the bitwise products (integer part alone, operands packed)",
                           "unit": "TOPS (2*n^3 / time)", "n_gpus": 1, "data": "synthetic",
-                          "note": "1/1 and 1/2: apb_forward_int = k_binary_mfma + k_finalize_int; 2/2: apb_gemm_2_2_int; "
+                          "note": "1/1 and 1/2: apb_forward_int on a layer without residuals; 2/2: apb_gemm_2_2_int; "
                                   "the paper predicts cost ratios 2 and 8 on a popcount machine",
                           "sweep": run_square_sweep()}))
         return

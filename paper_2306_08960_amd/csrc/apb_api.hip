@@ -322,8 +322,7 @@ static int forward_common(const apb_layer* layer, const void* packed, int M, int
     const int32_t* colsum = reinterpret_cast<const int32_t*>(planes + (size_t)bits * d.Kw * Mp);
     hipStream_t s = as_stream(stream);
     if (kind == kFwdIntMfma) {
-        const int rc = launch_binary_mfma(d, planes, M, bits, D, s);
-        return rc != APB_OK ? rc : launch_finalize_int(d, colsum, M, bits, D, s);
+        return launch_binary_mfma(d, planes, colsum, M, bits, D, s);
     }
     if (kind == kFwdFull) {
         // Layers of at most 32 rows (fewer than four 16-row tiles): the raw binary product is left in the output buffer itself
@@ -331,7 +330,7 @@ static int forward_common(const apb_layer* layer, const void* packed, int M, int
         // workspace, no allocation.
         // Workgroups of 4 or 8 waves compute the product themselves (one kernel, nothing but Y written).
         if (sparse_epilogue_can_fuse(d)) return launch_sparse_epilogue(d, planes, colsum, M, bits, step, Y, true, s);
-        const int rc = launch_binary_mfma(d, planes, M, bits, reinterpret_cast<int32_t*>(Y), s);
+        const int rc = launch_binary_mfma(d, planes, nullptr, M, bits, reinterpret_cast<int32_t*>(Y), s);
         return rc != APB_OK ? rc : launch_sparse_epilogue(d, planes, colsum, M, bits, step, Y, false, s);
     }
     return launch_forward_popcount(d, planes, colsum, M, bits, step, Y, D, s);

@@ -31,12 +31,13 @@ namespace apb {
 
 namespace {
 
-enum Epilogue { kRawProduct = 0, kInt22 = 1, kFloat22 = 2 };
+enum Epilogue { kRawProduct = 0, kInt22 = 1, kFloat22 = 2, kIntD = 3 };   // kIntD: D of the binary layer
 
 struct MfmaParams {
     const uint32_t* __restrict__ signT;   // [wbits][Kw2][Np]  word j of row n, rows in the layer's own order
     const uint32_t* __restrict__ planes;  // [bits][Kw][Mp]
-    const int32_t* __restrict__ colsum;   // [Mp]   (2/2 epilogues)
+    const int32_t* __restrict__ colsum;   // [Mp]   (every epilogue but kRawProduct)
+    const int32_t* __restrict__ rowsum;   // [N]    (kIntD with 1-bit activations)
     void* __restrict__ out;               // [N][M] int32 (kRawProduct, kInt22) or float (kFloat22)
     double scale;                         // kFloat22: s_w * s_a / 2
     size_t wplane_stride;                 // words between the weight planes
@@ -157,22 +158,14 @@ __global__ __launch_bounds__(256) void k_binary_mfma(const MfmaParams p) {
                 const size_t at = out0 + (size_t)row * p.M + 32 * u;
                 const int P = (int)(acc[t][u][r] * 4.0f);
                 if (EPI == kRawProduct) static_cast<int32_t*>(p.out)[at] = P;
+                else if (EPI == kIntD)
+                    static_cast<int32_t*>(p.out)[at] =
+                        BITS == 2 ? 2 * P - cs[u] : 4 * P - p.rowsum[slot_base + 4 * g + row] - 2 * cs[u];
                 else if (EPI == kInt22) static_cast<int32_t*>(p.out)[at] = 2 * P - 3 * cs[u];
                 else static_cast<float*>(p.out)[at] = (float)(p.scale * (double)(2 * P - 3 * cs[u]));
             }
         }
     }
-}
-
-// P -> D in place (see the header of this file).
-template <int BITS>
-__global__ __launch_bounds__(256) void k_finalize_int(int32_t* __restrict__ PD, const int32_t* __restrict__ colsum,
-                                                      const int32_t* __restrict__ rowsum, int N, int M) {
-    const int m = blockIdx.x * 256 + threadIdx.x, n = blockIdx.y;
-    if (m >= M) return;
-    const size_t t = (size_t)n * M + m;
-    const int P = PD[t];
-    PD[t] = BITS == 2 ? 2 * P - colsum[m] : 4 * P - rowsum[n] - 2 * colsum[m];
 }
 
 template <int WBITS, int BITS, int RN, int RM, int EPI>
@@ -229,16 +222,20 @@ int launch_best_tile(MfmaParams p, int N, hipStream_t s) {
 
 }  // namespace
 
-// Raw product P (see above) of a binary layer into `P` (N*M int32).
-int launch_binary_mfma(const LayerDev& L, const uint32_t* planes, int M, int bits, int32_t* P, hipStream_t s) {
+// Binary layer: the raw product P (colsum == nullptr) or the integer part D into `out` (N*M int32).
+int launch_binary_mfma(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
+                       int32_t* out, hipStream_t s) {
     MfmaParams p{};
     p.signT = L.signC;                                        // rows in the layer's own order
     p.planes = planes;
-    p.out = P;
+    p.colsum = colsum;
+    p.rowsum = L.rowsum;
+    p.out = out;
     p.Np = L.N;
     p.Kw = L.Kw;
     p.Mp = kWave * ((M + kWave - 1) / kWave);
     p.M = M;
+    if (colsum) return bits == 1 ? launch_best_tile<1, 1, kIntD>(p, L.N, s) : launch_best_tile<1, 2, kIntD>(p, L.N, s);
     return bits == 1 ? launch_best_tile<1, 1, kRawProduct>(p, L.N, s) : launch_best_tile<1, 2, kRawProduct>(p, L.N, s);
 }
 
@@ -257,15 +254,6 @@ int launch_gemm_2_2(const uint32_t* wplanesC, int N, int Kw, const uint32_t* pla
     p.Mp = kWave * ((M + kWave - 1) / kWave);
     p.M = M;
     return Y ? launch_best_tile<2, 2, kFloat22>(p, N, s) : launch_best_tile<2, 2, kInt22>(p, N, s);
-}
-
-int launch_finalize_int(const LayerDev& L, const int32_t* colsum, int M, int bits, int32_t* PD, hipStream_t s) {
-    if (L.N > 65535) return APB_ERR_SHAPE;
-    const dim3 grid((unsigned)((M + 255) / 256), (unsigned)L.N);
-    if (bits == 1) hipLaunchKernelGGL(k_finalize_int<1>, grid, dim3(256), 0, s, PD, colsum, L.rowsum, L.N, M);
-    else hipLaunchKernelGGL(k_finalize_int<2>, grid, dim3(256), 0, s, PD, colsum, L.rowsum, L.N, M);
-    APB_HIP(hipGetLastError());
-    return APB_OK;
 }
 
 }  // namespace apb

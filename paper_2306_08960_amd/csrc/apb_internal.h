@@ -85,9 +85,9 @@ bool sparse_epilogue_can_fuse(const LayerDev& L);
 int launch_sparse_epilogue(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
                            float step, float* Y, bool fused, hipStream_t s);
 
-// binary part on the matrix cores: raw product P, and P -> D in place
-int launch_binary_mfma(const LayerDev& L, const uint32_t* planes, int M, int bits, int32_t* P, hipStream_t s);
-int launch_finalize_int(const LayerDev& L, const int32_t* colsum, int M, int bits, int32_t* PD, hipStream_t s);
+// binary part on the matrix cores: the raw product P (colsum == nullptr) or the integer part D
+int launch_binary_mfma(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
+                       int32_t* out, hipStream_t s);
 
 // 2/2 routine: quantize + pack 2-bit weights (canonical [2][N][Kw] and word-major [2][Kw2][N], Kw2 =
 // Kw rounded up to even with a zero pad row), and the product itself (D22 when Y == nullptr)
