@@ -142,20 +142,19 @@ __device__ __forceinline__ void batch(v16d& acc, v8d& pairs, const uint32_t* __r
     for (int h = 0; h < NB; ++h) accumulate8(acc, pairs, k[h], v[h], table_off);
 }
 
-// Fused mode, first phase: the raw binary product P = sum_k bit * code of the workgroup's
-// (16 * WAVES rows) x 64 columns on the matrix cores, left in LDS as int32 [16 * WAVES][64].  Wave w
-// computes the 32 x 32 tile (w / 2, w % 2) with one FP4 MFMA per 64 values of k (see
-// apb_fp4_expand.h); rows are launch slots, read from the slot-major sign words (padding slots and
+// Fused mode, first phase: the raw binary product P = sum_k bit * code of a workgroup's rows x 64
+// columns on the matrix cores, left in LDS as int32 [rows][64].  A wave computes the 32 x 32 tile
+// (tn, tm) over the K steps [s_begin, s_end) (a step is 64 values of k) with one FP4 MFMA per step
+// (see apb_fp4_expand.h); rows are launch slots, read from the slot-major sign words (padding slots and
 // the pad word row past an odd Kw are zero).  The upper lane half of the last step of an odd Kw
 // reads one activation row past its plane -- still inside the packed buffer (the next plane, or the
 // column sums) and multiplied by zero weights.  Words are fetched four steps ahead.
-template <int BITS, int WAVES>
+template <int BITS>
 __device__ __forceinline__ void binary_tile_to_lds(const uint32_t* __restrict__ signT,
                                                    const uint32_t* __restrict__ planes, int Np, int Kw, int Mp,
-                                                   int slot_base, int m_base, int wave, int lane, int32_t* tile) {
-    static_assert(WAVES % 2 == 0, "two waves side by side cover the 64 columns");
+                                                   int slot_base, int m_base, int tn, int tm, int s_begin, int s_end,
+                                                   int lane, int32_t* tile) {
     const int i = lane & 31, g = lane >> 5;
-    const int tn = wave >> 1, tm = wave & 1;
     const unsigned aoff = (unsigned)(g * Np + slot_base + 32 * tn + i);
     const unsigned boff = (unsigned)(g * Mp + m_base + 32 * tm + i);
     const size_t plane_stride = (size_t)Kw * Mp;
@@ -175,7 +174,7 @@ __device__ __forceinline__ void binary_tile_to_lds(const uint32_t* __restrict__ 
 #pragma unroll
     for (int r = 0; r < 16; ++r) c[r] = 0.0f;
 #pragma unroll
-    for (int q = 0; q < kRing; ++q) load_words(q, aw[q], bw[q]);
+    for (int q = 0; q < kRing; ++q) load_words(s_begin + q, aw[q], bw[q]);
     expand<1, BITS, 1, 1>(aw[0], bw[0], f[0]);
     auto one_step = [&](int st, int q) {
         const Frag<1, 1>& cur = f[q & 1];
@@ -183,14 +182,14 @@ __device__ __forceinline__ void binary_tile_to_lds(const uint32_t* __restrict__ 
         expand<1, BITS, 1, 1>(aw[(q + 1) % kRing], bw[(q + 1) % kRing], f[(q + 1) & 1]);
         c = mfma_fp4(cur.a[0], cur.b[0], c);
     };
-    int s0 = 0;
-    for (; s0 + kRing <= steps; s0 += kRing) {
+    int s0 = s_begin;
+    for (; s0 + kRing <= s_end; s0 += kRing) {
 #pragma unroll
         for (int q = 0; q < kRing; ++q) one_step(s0 + q, q);
     }
 #pragma unroll
     for (int q = 0; q < kRing - 1; ++q)
-        if (s0 + q < steps) one_step(s0 + q, q);
+        if (s0 + q < s_end) one_step(s0 + q, q);
     // C layout of the 32x32 tile: lane (i, g), register r  ->  row 8*(r/4) + 4*g + (r%4), column i.
 #pragma unroll
     for (int r = 0; r < 16; ++r)
@@ -237,8 +236,8 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
         // 1-bit activations, whose sum is doubled at the end).  The tile shares LDS with the code
         // tables, hence the second barrier.
         int32_t* tile_lds = reinterpret_cast<int32_t*>(lds);
-        binary_tile_to_lds<BITS, (waves >= 2 ? waves : 2)>(signT, planes, p.Np, p.Kw, p.Mp, rg * waves * TN, strip * kWave,
-                                                          wave, lane, tile_lds);
+        binary_tile_to_lds<BITS>(signT, planes, p.Np, p.Kw, p.Mp, rg * waves * TN, strip * kWave, wave >> 1, wave & 1, 0,
+                                 (p.Kw + 1) / 2, lane, tile_lds);
         __syncthreads();
         int P[TN];
 #pragma unroll
@@ -347,6 +346,164 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
     }
 }
 
+// The same forward for launches that would leave most of the chip idle (few column strips, few row
+// groups): the 8 waves of a workgroup are KS parts of K times 8/KS tiles, so a workgroup covers fewer
+// rows and there are KS times as many waves, each with 1/KS of the chunks of its tile.  Part kp of
+// K = chunks [kp*H, (kp+1)*H), H = ceil(nchunks / KS), and the K steps [kp*SP, (kp+1)*SP) of the
+// binary product.  Every part has its own code table (KS buffers, rebuilt together once per round by
+// all 8 waves: wave w expands word w of each), the partial binary products meet in LDS before the
+// residual loop (part 0 starts its sums at alpha*D, the others at zero) and the partial float64 sums
+// meet in LDS after it, added in a fixed order by part 0, which writes Y.  All waves run the same
+// number of barriers whatever their run lengths.
+template <int BITS, int KS>
+__global__ __launch_bounds__(kWave* kChunkWords) __attribute__((amdgpu_waves_per_eu(4, 8))) void k_forward_ksplit(
+    const uint32_t* __restrict__ planes, const int32_t* __restrict__ colsum, const int32_t* __restrict__ rowsum,
+    const int32_t* __restrict__ perm, const int32_t* __restrict__ seg_ptr, const uint32_t* __restrict__ ent,
+    const double* __restrict__ slot_valsum, const uint32_t* __restrict__ signT, float* __restrict__ Y,
+    const SparseParams p) {
+    extern __shared__ __align__(16) uint8_t lds[];
+    constexpr int TW = kChunkWords / KS;                         // tiles (of 16 rows) per workgroup
+    static_assert(KS == 2 || KS == 4, "two or four parts of K");
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    int task = blockIdx.x;
+    if ((p.blocks & 7) == 0) task = (blockIdx.x & 7) * (p.blocks >> 3) + (blockIdx.x >> 3);
+    const int rg = task % p.row_groups;                          // row group of TW tiles
+    const int strip = task / p.row_groups;
+    const int tl = wave % TW, kp = wave / TW;
+    const int tile = rg * TW + tl;
+    const int slot0 = tile * TN;
+    const int m = strip * kWave + lane;
+    const int m_off = m * 4;
+    const int H = (p.nchunks + KS - 1) / KS;
+
+    // binary part: wave (tl, kp) computes 32 x 32 tile tl of the workgroup's 16*TW x 64 block over
+    // its share of the K steps
+    int32_t* part_lds = reinterpret_cast<int32_t*>(lds);        // [KS][16 * TW][64]
+    {
+        const int steps = (p.Kw + 1) / 2;
+        const int SP = (steps + KS - 1) / KS;
+        const int s_begin = min(steps, kp * SP), s_end = min(steps, s_begin + SP);
+        binary_tile_to_lds<BITS>(signT, planes, p.Np, p.Kw, p.Mp, rg * TW * TN, strip * kWave, tl >> 1, tl & 1, s_begin,
+                                 s_end, lane, part_lds + kp * (TN * TW * kWave));
+    }
+    __syncthreads();
+    v16d acc;
+    if (kp == 0) {
+        int P[TN];
+#pragma unroll
+        for (int r = 0; r < TN; ++r) {
+            P[r] = 0;
+#pragma unroll
+            for (int q = 0; q < KS; ++q) P[r] += part_lds[q * (TN * TW * kWave) + (tl * TN + r) * kWave + lane];
+        }
+        const int cs = colsum[m];
+        const double a0 = p.alpha * (BITS == 1 ? 0.5 : 1.0) * (1.0 / kSumUnscale);
+#pragma unroll
+        for (int r = 0; r < TN; ++r) {
+            const int nr = perm[slot0 + r];
+            const int d = BITS == 1 ? 4 * P[r] - rowsum[max(nr, 0)] - 2 * cs : 2 * P[r] - cs;
+            acc[r] = a0 * (double)d;
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < TN; ++r) acc[r] = 0.0;
+    }
+    v8d pairs;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) pairs[r] = 0.0;
+    __syncthreads();                                            // the partial products are read; tables may overwrite them
+
+    const size_t plane_stride = (size_t)p.Kw * p.Mp;
+    uint8_t* my_row = lds + lane * kTablePitch;
+    const uint32_t my_row_off = (uint32_t)(uintptr_t)(lds_u8*)my_row;
+    const int32_t* seg = seg_ptr + (size_t)tile * (p.nchunks + 1);
+
+    // word `wave` of chunk q*H + i for every part q, fetched one round ahead
+    uint32_t xw[BITS][KS];
+    auto fetch = [&](int i) {
+#pragma unroll
+        for (int q = 0; q < KS; ++q) {
+            const int j = (q * H + i) * kChunkWords + wave;
+#pragma unroll
+            for (int b = 0; b < BITS; ++b) {
+                const uint32_t* row = planes + (b * plane_stride + (size_t)min(j, p.Kw - 1) * p.Mp);
+                const __amdgpu_buffer_rsrc_t rsrc =
+                    __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(row), 0, p.Mp * 4, kBufferFlags);
+                xw[b][q] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, m_off, 0, 0);
+            }
+        }
+    };
+    fetch(0);
+    for (int i = 0; i < H; ++i) {
+        if (i > 0) __syncthreads();                             // every wave has finished reading the tables
+#pragma unroll
+        for (int q = 0; q < KS; ++q) {
+            const int c = q * H + i;
+            if (c < p.nchunks && c * kChunkWords + wave < p.Kw)
+                expand_word<BITS>(xw[0][q], xw[BITS - 1][q], my_row + q * kTableBytes + 32 * wave);
+        }
+        if (i + 1 < H) fetch(i + 1);
+        const int c = min(kp * H + i, p.nchunks);               // past the end: an empty run
+        int e = seg[c];
+        const int e1 = seg[min(c + 1, p.nchunks)];
+        __syncthreads();                                        // the tables of this round are complete
+        const uint32_t table_off = my_row_off + kp * kTableBytes;
+        for (; e + 2 <= e1; e += 2) batch<2>(acc, pairs, ent, e, table_off);
+        if (e < e1) batch<1>(acc, pairs, ent, e, table_off);
+    }
+
+    // the partial sums of parts 1.. go through LDS to part 0
+    __syncthreads();                                            // every wave is done with the tables
+    double* red = reinterpret_cast<double*>(lds);               // [KS - 1][TW][16][64]
+    if (kp > 0) {
+#pragma unroll
+        for (int r = 0; r < TN; ++r) red[(((kp - 1) * TW + tl) * TN + r) * kWave + lane] = acc[r];
+    }
+    __syncthreads();
+    if (kp > 0) return;
+#pragma unroll
+    for (int q = 1; q < KS; ++q)
+#pragma unroll
+        for (int r = 0; r < TN; ++r) acc[r] += red[(((q - 1) * TW + tl) * TN + r) * kWave + lane];
+
+    const bool col_ok = m < p.M;
+#pragma unroll
+    for (int r = 0; r < TN; ++r) {
+        const int n = perm[slot0 + r];
+        // 1-bit activations: the table holds (c+1)/2 in {0,1}: sum val*c = 2*sum val*code - sum val.
+        const double sum = acc[r] * kSumUnscale;
+        const double sparse = BITS == 1 ? 2.0 * sum - slot_valsum[slot0 + r] : sum;
+        if (col_ok && n >= 0) Y[(size_t)n * p.M + m] = (float)(sparse * p.step);   // alpha * D is in the sum
+    }
+}
+
+template <int KS>
+constexpr int ksplit_lds_bytes() {
+    constexpr int tables = KS * kTableBytes;
+    constexpr int partial_products = KS * TN * (kChunkWords / KS) * kWave * 4;
+    constexpr int partial_sums = (KS - 1) * (kChunkWords / KS) * TN * kWave * 8;
+    return tables > partial_products ? (tables > partial_sums ? tables : partial_sums)
+                                     : (partial_products > partial_sums ? partial_products : partial_sums);
+}
+
+template <int BITS, int KS>
+int launch_ksplit(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, float* Y, SparseParams p,
+                  hipStream_t s) {
+    constexpr int TW = kChunkWords / KS;
+    constexpr int kLds = ksplit_lds_bytes<KS>();
+    p.row_groups = L.Np / (TN * TW);
+    const long long blocks = (long long)p.row_groups * (p.Mp / kWave);
+    if (blocks > 0x7fffffffLL) return APB_ERR_SHAPE;
+    p.blocks = (int)blocks;
+    if (kLds > 64 * 1024)                                       // more LDS than a launch gets without asking
+        APB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_forward_ksplit<BITS, KS>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
+    hipLaunchKernelGGL((k_forward_ksplit<BITS, KS>), dim3((unsigned)p.blocks), dim3(kWave * kChunkWords), kLds, s, planes,
+                       colsum, L.rowsum, L.perm, L.seg_ptr, L.ent, L.slot_valsum, L.signT, Y, p);
+    return APB_OK;
+}
+
 template <int BITS, int WPW, bool FUSED>
 void launch_one(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, float* Y, const SparseParams& p,
                 hipStream_t s) {
@@ -394,8 +551,17 @@ int launch_sparse_epilogue(const LayerDev& L, const uint32_t* planes, const int3
     const long long blocks = (long long)p.row_groups * (Mp / kWave);
     if (blocks > 0x7fffffffLL || (long long)Mp * 4 >= (1LL << 31)) return APB_ERR_SHAPE;
     p.blocks = (int)blocks;
-    const int rc = bits == 1 ? launch_bits<1>(L, planes, colsum, Y, p, fused, s)
-                             : launch_bits<2>(L, planes, colsum, Y, p, fused, s);
+    int rc;
+    // Fused launches of 8-wave workgroups that would put fewer than ~3000 waves on the chip split K
+    // two or four ways inside the workgroup instead (see k_forward_ksplit).
+    int ks = 1;
+    if (fused && L.waves == 8) {
+        if (blocks * 8 < 3000 && L.nchunks >= 2) ks = 2;
+        if (blocks * 16 < 3000 && L.nchunks >= 4) ks = 4;
+    }
+    if (ks == 2) rc = bits == 1 ? launch_ksplit<1, 2>(L, planes, colsum, Y, p, s) : launch_ksplit<2, 2>(L, planes, colsum, Y, p, s);
+    else if (ks == 4) rc = bits == 1 ? launch_ksplit<1, 4>(L, planes, colsum, Y, p, s) : launch_ksplit<2, 4>(L, planes, colsum, Y, p, s);
+    else rc = bits == 1 ? launch_bits<1>(L, planes, colsum, Y, p, fused, s) : launch_bits<2>(L, planes, colsum, Y, p, fused, s);
     if (rc != APB_OK) return rc;
     APB_HIP(hipGetLastError());
     return APB_OK;
