@@ -449,7 +449,12 @@ __global__ __launch_bounds__(kWave* kChunkWords) __attribute__((amdgpu_waves_per
         const int e1 = seg[min(c + 1, p.nchunks)];
         __syncthreads();                                        // the tables of this round are complete
         const uint32_t table_off = my_row_off + kp * kTableBytes;
-        for (; e + 2 <= e1; e += 2) batch<2>(acc, pairs, ent, e, table_off);
+        // (three blocks per scalar round trip: at this occupancy the scalar registers are there)
+        for (; e + 3 <= e1; e += 3) batch<3>(acc, pairs, ent, e, table_off);
+        if (e + 2 <= e1) {
+            batch<2>(acc, pairs, ent, e, table_off);
+            e += 2;
+        }
         if (e < e1) batch<1>(acc, pairs, ent, e, table_off);
     }
 
