@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--workload", default="C2", help="name in paper_2306_08960_amd.synth.CONFIGS")
     ap.add_argument("--all", action="store_true", help="also time every other benchmark layer (reported in 'others')")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="before the steps, copy X into a buffer of the same size three times: a plain copy kernel of "
+                         "known size, against which FETCH_SIZE / WRITE_SIZE of a rocprofv3 --pmc run are scaled")
     ap.add_argument("--sweep", action="store_true",
                     help="square-matrix sweep of the three bitwise products (1/1, 1/2, 2/2; Sec. V protocol): one JSON "
                          "line with the time of the product alone at each size")
@@ -75,7 +78,7 @@ def time_in_step(quant, fwd, iters, ms_step_plain):
     return tq, tf, per_record          # ms
 
 
-def run_workload(name, steps, warmup):
+def run_workload(name, steps, warmup, calibration_copy=False):
     import torch
     from paper_2306_08960_amd import binding as b
     from paper_2306_08960_amd import synth
@@ -90,6 +93,12 @@ def run_workload(name, steps, warmup):
     packed = b.alloc_packed(K, M, bits)
     Y = torch.empty((N, M), dtype=torch.float32, device="cuda")
     s = float(step)
+    if calibration_copy:
+        Xc = torch.empty_like(Xd)
+        for _ in range(3):
+            Xc.copy_(Xd)                     # reads and writes 4*K*M bytes
+        torch.cuda.synchronize()
+        del Xc
 
     def quant():
         b.apb_quantize_acts(Xd, bits, s, packed=packed)
@@ -346,7 +355,7 @@ def main():
         print(json.dumps(out))
         return
 
-    res, inputs = run_workload(args.workload, args.steps, args.warmup)
+    res, inputs = run_workload(args.workload, args.steps, args.warmup, args.calibration_copy)
     cfg = inputs[0]
     out = {
         "metric": "APB layer forward GOPS (binary+sparse) and % of MI355X roofline",
