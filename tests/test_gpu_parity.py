@@ -173,3 +173,43 @@ def test_errors_and_reuse(b):
     assert torch.equal(y1, y2) and torch.equal(packed, p2)
     layer.free()
     layer.free()
+
+
+def test_step_can_be_captured_in_a_graph_and_replayed(b):
+    """quantize + forward allocate nothing and record no memset: a captured graph of the step must
+    reproduce the eager result on every replay, with eager work and synchronizations in between."""
+    W, delta, X, step = synth.random_case(4242, 70, 300, 5000, 2, rho=0.03)
+    Wd = torch.from_numpy(W).cuda()
+    Xd = torch.from_numpy(X).cuda()
+    layer = b.apb_compress(Wd, float(delta))
+    packed = b.alloc_packed(300, 5000, 2)
+    Y = torch.empty((70, 5000), dtype=torch.float32, device="cuda")
+
+    def one_step():
+        b.apb_quantize_acts(Xd, 2, float(step), packed=packed)
+        b.apb_forward(layer, packed, 5000, 2, float(step), Y=Y)
+
+    one_step()
+    torch.cuda.synchronize()
+    y_ref = Y.clone()
+    p_ref = packed.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        one_step()                                       # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        one_step()
+    for _ in range(3):
+        Y.zero_()
+        packed.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(packed, p_ref)
+        assert torch.equal(Y, y_ref)
+        one_step()                                       # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(Y, y_ref)
+    layer.free()
