@@ -32,13 +32,15 @@ namespace {
 
 constexpr int TN = kRowTile;
 constexpr int kTablePitch = kChunkK + 4;                       // bytes per column row of the code table
-constexpr int kTableBytes = kWave * kTablePitch;               // one buffer; two are used alternately
+constexpr int kTableBytes = kWave * kTablePitch;               // one table (see table_buffers for how many a workgroup keeps)
 
 typedef __attribute__((address_space(3))) uint8_t lds_u8;
 
 // Fourth word of a raw buffer descriptor on gfx9-family parts: 32-bit data format, no swizzle.
 constexpr int kBufferFlags = 0x00020000;
 
+// 8-wave workgroups alternate between two tables (one barrier per chunk); smaller ones keep one, so
+// that twice as many fit a CU, and pay a second barrier per chunk.
 __host__ __device__ constexpr int table_buffers(int wpw) { return wpw == 1 ? 2 : 1; }
 
 struct SparseParams {
@@ -123,7 +125,7 @@ __device__ __forceinline__ void accumulate8(v16d& acc, v8d& pairs, const uint32_
 #undef APB_SDWA
 }
 
-// NB (1 or 2) blocks of 8 entries starting at block b.  Keys and values of a block sit side by side,
+// NB (1 to 3) blocks of 8 entries starting at block b.  Keys and values of a block sit side by side,
 // so all the scalar loads of a batch leave together and cost one round trip.
 template <int NB>
 __device__ __forceinline__ void batch(v16d& acc, v8d& pairs, const uint32_t* __restrict__ ent, int b,
