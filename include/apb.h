@@ -25,7 +25,7 @@
  *    4-byte aligned; the caller owns them.  The library owns only what lives
  *    inside an apb_layer.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *    apb_quantize_acts / apb_forward / apb_forward_int only enqueue work and
+ *    apb_quantize_acts / apb_forward / apb_forward_requant / apb_forward_int only enqueue work and
  *    return; apb_compress and apb_layer_export synchronize the stream.
  *  - Non-finite values in W or X give unspecified numbers but never touch
  *    memory out of bounds (a NaN activation quantizes to code 0 / sign -).
@@ -113,6 +113,21 @@ int apb_quantize_acts(const float* X, int K, int M, int bits, float step, void* 
  *   Y       DEVICE, N*M floats row-major, fully overwritten.
  * Asynchronous on `stream`. */
 int apb_forward(const apb_layer* layer, const void* packed, int M, int bits, float step, float* Y, void* stream);
+
+/* Two layers in a row without the float round trip: Eq. 13 of this layer followed directly by the
+ * activation quantizer (Sec. IV) of the layer it feeds, whose K is this layer's N.  The result is
+ * the packed buffer that apb_quantize_acts(Z, N, M, bits_out, step_out) would write for
+ *      Z[n,m] = scale[n] * Y[n,m] + shift[n]          (a folded batch normalization; Z = Y without)
+ * with Y as apb_forward computes it; Z is formed in float64 from the float64 Y and rounded once to
+ * float, then quantized exactly as apb_quantize_acts does (for bits_out = 2 the clamp at 0 is the
+ * ReLU).  Neither Y nor Z is written to memory.
+ *   scale, shift  DEVICE, N floats each, read-only; both NULL for Z = Y (one NULL: APB_ERR_NULL).
+ *   bits_out, step_out  the next layer's activation format (as `bits`, `step` of apb_quantize_acts).
+ *   packed_out    DEVICE, apb_acts_bytes(N, M, bits_out) bytes, fully overwritten; must not overlap `packed`.
+ * Asynchronous on `stream`. */
+int apb_forward_requant(const apb_layer* layer, const void* packed, int M, int bits, float step,
+                        const float* scale, const float* shift, int bits_out, float step_out, void* packed_out,
+                        void* stream);
 
 /* Test hook: the integer part D (N*M int32, row-major, DEVICE) alone, computed by the stand-alone
  * matrix-core kernel (the same bit expansion and matrix instruction as apb_forward's first

@@ -24,6 +24,9 @@ What is computed, and where it is defined:
                   printed equation leaves out, plus the zero-centering term
                   mu * sum(w), mu = 3s/2
   forward         Sec. III Eq. 13:  C = A^bin * B + A^full * B
+  forward_requant Eq. 13 of one layer followed by the activation quantizer
+                  (Sec. IV) of the layer it feeds, with an optional per-row
+                  affine map in between (a folded batch normalization)
   dot_2_2_mbm     Sec. IV "2/2": the 1/2 routine applied twice -- four mbm terms
                   under the and of the two masks, with the level weights 9/4,
                   3/4, 3/4, 1/4 that the printed equation leaves out (and the
@@ -290,6 +293,25 @@ def forward(layer: dict, c: np.ndarray, step) -> dict:
     D = int_part_unpacked(layer["bit"], c)
     R = sparse_part(layer["row_ptr"], layer["col_idx"], layer["val"], c, step)
     return {"D": D, "R": R, "Y": epilogue(layer["alpha"], step, D, R)}
+
+
+def requant(alpha, step, D: np.ndarray, R: np.ndarray, bits_out: int, step_out, scale=None, shift=None) -> dict:
+    """The activations the next layer sees, from the two parts of Eq. 13: Z = scale[n]*Y + shift[n]
+    (Z = Y without scale) formed in float64 from the float64 Y = alpha*s*D + R, rounded once to float32
+    and then quantized as any other activation matrix (N x M: this layer's rows are the next layer's K)."""
+    y = np.float64(np.float32(alpha)) * np.float64(np.float32(step)) * D.astype(np.float64) + R
+    if scale is not None:
+        y = np.asarray(scale, dtype=np.float32).astype(np.float64)[:, None] * y \
+            + np.asarray(shift, dtype=np.float32).astype(np.float64)[:, None]
+    Z = y.astype(np.float32)
+    c_out = quantize(Z, bits_out, step_out)
+    return {"Z": Z, "c": c_out, "packed": pack_acts(c_out, bits_out)}
+
+
+def forward_requant(layer: dict, c: np.ndarray, step, bits_out: int, step_out, scale=None, shift=None) -> dict:
+    D = int_part_unpacked(layer["bit"], c)
+    R = sparse_part(layer["row_ptr"], layer["col_idx"], layer["val"], c, step)
+    return requant(layer["alpha"], step, D, R, bits_out, step_out, scale, shift)
 
 
 def brute_force(W: np.ndarray, delta, alpha, X: np.ndarray, bits: int, step) -> np.ndarray:

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libapb.so")
 
 EXPORTS = (
     "apb_compress", "apb_layer_info", "apb_layer_export", "apb_layer_free", "apb_acts_bytes",
-    "apb_quantize_acts", "apb_forward", "apb_forward_int", "apb_forward_int_popcount", "apb_forward_popcount",
+    "apb_quantize_acts", "apb_forward", "apb_forward_requant", "apb_forward_int", "apb_forward_int_popcount", "apb_forward_popcount",
     "apb_w2_pack", "apb_w2_export", "apb_w2_free", "apb_gemm_2_2_int", "apb_gemm_2_2",
     "apb_strerror", "apb_last_hip_error",
 )
@@ -62,6 +62,8 @@ def load() -> ctypes.CDLL:
     lib.apb_quantize_acts.restype = ci
     lib.apb_forward.argtypes = [vp, vp, ci, ci, cf, vp, vp]
     lib.apb_forward.restype = ci
+    lib.apb_forward_requant.argtypes = [vp, vp, ci, ci, cf, vp, vp, ci, cf, vp, vp]
+    lib.apb_forward_requant.restype = ci
     lib.apb_forward_int.argtypes = [vp, vp, ci, ci, vp, vp]
     lib.apb_forward_int.restype = ci
     lib.apb_forward_int_popcount.argtypes = [vp, vp, ci, ci, vp, vp]
@@ -218,6 +220,29 @@ def apb_forward(layer: ApbLayer, packed: torch.Tensor, M: int, bits: int, step: 
     _check(load().apb_forward(layer.handle, _dev_ptr(packed, torch.int32, "packed"), int(M), int(bits),
                               float(step), _dev_ptr(Y, torch.float32, "Y"), _stream(stream)), "apb_forward")
     return Y
+
+
+def apb_forward_requant(layer: ApbLayer, packed: torch.Tensor, M: int, bits: int, step: float, bits_out: int,
+                        step_out: float, scale: Optional[torch.Tensor] = None, shift: Optional[torch.Tensor] = None,
+                        packed_out: Optional[torch.Tensor] = None,
+                        stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """The layer's output, quantized for the next layer and packed (its K = this layer's N)."""
+    N, _ = _check_packed(layer, packed, M, bits)
+    if (scale is None) != (shift is None):
+        raise ValueError("scale and shift go together")
+    for name, t in (("scale", scale), ("shift", shift)):
+        if t is not None and t.numel() != N:
+            raise ValueError(f"{name} must hold N floats")
+    if packed_out is None:
+        packed_out = alloc_packed(N, M, bits_out, packed.device)
+    elif packed_out.numel() * packed_out.element_size() < apb_acts_bytes(N, M, bits_out):
+        raise ValueError("packed_out smaller than apb_acts_bytes(N, M, bits_out)")
+    _check(load().apb_forward_requant(layer.handle, _dev_ptr(packed, torch.int32, "packed"), int(M), int(bits),
+                                      float(step), None if scale is None else _dev_ptr(scale, torch.float32, "scale"),
+                                      None if shift is None else _dev_ptr(shift, torch.float32, "shift"),
+                                      int(bits_out), float(step_out), _dev_ptr(packed_out, torch.int32, "packed_out"),
+                                      _stream(stream)), "apb_forward_requant")
+    return packed_out
 
 
 def apb_forward_int(layer: ApbLayer, packed: torch.Tensor, M: int, bits: int,

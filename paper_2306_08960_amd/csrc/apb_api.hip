@@ -54,6 +54,9 @@ std::vector<int32_t> balanced_slots(const std::vector<int32_t>& counts, int Np) 
         const int t = (round & 1) ? tiles - 1 - pos : pos;
         perm[t * kRowTile + fill[t]++] = order[i];
     }
+    // Inside a tile the order of the rows is free: ascending, so that rows sharing a 32-row word of
+    // a packed output sit next to each other.
+    for (int t = 0; t < tiles; ++t) std::sort(perm.begin() + t * kRowTile, perm.begin() + t * kRowTile + fill[t]);
     return perm;
 }
 
@@ -110,7 +113,7 @@ int compress_impl(const float* W, int N, int K, float delta, float alpha, hipStr
     d.N = N;
     d.K = K;
     d.Kw = (K + 31) / 32;
-    d.waves = 1;                                       // workgroup = up to 8 waves of kRowTile rows each
+    d.waves = 2;                                       // workgroup = 2, 4 or 8 waves of kRowTile rows each
     while (d.waves < kMaxWavesPerBlock && d.waves * kRowTile < N) d.waves *= 2;
     const int rows_per_block = kRowTile * d.waves;
     d.Np = rows_per_block * ((N + rows_per_block - 1) / rows_per_block);
@@ -325,13 +328,7 @@ static int forward_common(const apb_layer* layer, const void* packed, int M, int
         return launch_binary_mfma(d, planes, colsum, M, bits, D, s);
     }
     if (kind == kFwdFull) {
-        // Layers of at most 32 rows (fewer than four 16-row tiles): the raw binary product is left in the output buffer itself
-        // (same size, int32 bits) and turned into Y in place by the sparse/epilogue kernel: no
-        // workspace, no allocation.
-        // Workgroups of 4 or 8 waves compute the product themselves (one kernel, nothing but Y written).
-        if (sparse_epilogue_can_fuse(d)) return launch_sparse_epilogue(d, planes, colsum, M, bits, step, Y, true, s);
-        const int rc = launch_binary_mfma(d, planes, nullptr, M, bits, reinterpret_cast<int32_t*>(Y), s);
-        return rc != APB_OK ? rc : launch_sparse_epilogue(d, planes, colsum, M, bits, step, Y, false, s);
+        return launch_forward(d, planes, colsum, M, bits, step, Y, s);
     }
     return launch_forward_popcount(d, planes, colsum, M, bits, step, Y, D, s);
 }
@@ -339,6 +336,24 @@ static int forward_common(const apb_layer* layer, const void* packed, int M, int
 int apb_forward(const apb_layer* layer, const void* packed, int M, int bits, float step, float* Y, void* stream) {
     if (!Y) return APB_ERR_NULL;
     return forward_common(layer, packed, M, bits, step, Y, nullptr, stream, kFwdFull);
+}
+
+int apb_forward_requant(const apb_layer* layer, const void* packed, int M, int bits, float step, const float* scale,
+                        const float* shift, int bits_out, float step_out, void* packed_out, void* stream) {
+    if (!layer || !packed || !packed_out || (scale == nullptr) != (shift == nullptr)) return APB_ERR_NULL;
+    const LayerDev& d = layer->d;
+    if (bad_shape_acts(d.K, M) || bad_shape_acts(d.N, M) || (long long)d.N * M >= (1LL << 40)) return APB_ERR_SHAPE;
+    if ((bits != 1 && bits != 2) || (bits_out != 1 && bits_out != 2)) return APB_ERR_BITS;
+    if (!std::isfinite(step) || !(step > 0.0f) || !std::isfinite(step_out) || !(step_out > 0.0f)) return APB_ERR_VALUE;
+    const size_t Mp = (size_t)kWave * (((size_t)M + kWave - 1) / kWave);
+    const uint32_t* planes = static_cast<const uint32_t*>(packed);
+    const int32_t* colsum = reinterpret_cast<const int32_t*>(planes + (size_t)bits * d.Kw * Mp);
+    hipStream_t s = as_stream(stream);
+    uint32_t* out = static_cast<uint32_t*>(packed_out);
+    const size_t out_words = ((size_t)bits_out * (((size_t)d.N + 31) / 32) + 1) * Mp;     // planes + colsum
+    const int rc = launch_zero_words(out, out_words, s);
+    if (rc != APB_OK) return rc;
+    return launch_forward_requant(d, planes, colsum, M, bits, step, scale, shift, bits_out, 1.0f / step_out, out, s);
 }
 
 int apb_forward_popcount(const apb_layer* layer, const void* packed, int M, int bits, float step, float* Y,

@@ -31,14 +31,14 @@ namespace apb {
 
 namespace {
 
-enum Epilogue { kRawProduct = 0, kInt22 = 1, kFloat22 = 2, kIntD = 3 };   // kIntD: D of the binary layer
+enum Epilogue { kInt22 = 1, kFloat22 = 2, kIntD = 3 };   // kIntD: D of the binary layer
 
 struct MfmaParams {
     const uint32_t* __restrict__ signT;   // [wbits][Kw2][Np]  word j of row n, rows in the layer's own order
     const uint32_t* __restrict__ planes;  // [bits][Kw][Mp]
-    const int32_t* __restrict__ colsum;   // [Mp]   (every epilogue but kRawProduct)
+    const int32_t* __restrict__ colsum;   // [Mp]
     const int32_t* __restrict__ rowsum;   // [N]    (kIntD with 1-bit activations)
-    void* __restrict__ out;               // [N][M] int32 (kRawProduct, kInt22) or float (kFloat22)
+    void* __restrict__ out;               // [N][M] int32 (kIntD, kInt22) or float (kFloat22)
     double scale;                         // kFloat22: s_w * s_a / 2
     size_t wplane_stride;                 // words between the weight planes
     int Np, Kw, Mp, M;
@@ -145,7 +145,7 @@ __global__ __launch_bounds__(256) void k_binary_mfma(const MfmaParams p) {
     const size_t out0 = (size_t)(slot_base + 4 * g) * p.M + m_base + i;
     int cs[RM];
 #pragma unroll
-    for (int u = 0; u < RM; ++u) cs[u] = EPI == kRawProduct ? 0 : p.colsum[min(m_base + 32 * u + i, p.Mp - 1)];
+    for (int u = 0; u < RM; ++u) cs[u] = p.colsum[min(m_base + 32 * u + i, p.Mp - 1)];
 #pragma unroll
     for (int t = 0; t < RN; ++t) {
 #pragma unroll
@@ -157,8 +157,7 @@ __global__ __launch_bounds__(256) void k_binary_mfma(const MfmaParams p) {
                 if (m_base + 32 * u + i >= p.M) continue;
                 const size_t at = out0 + (size_t)row * p.M + 32 * u;
                 const int P = (int)(acc[t][u][r] * 4.0f);
-                if (EPI == kRawProduct) static_cast<int32_t*>(p.out)[at] = P;
-                else if (EPI == kIntD)
+                if (EPI == kIntD)
                     static_cast<int32_t*>(p.out)[at] =
                         BITS == 2 ? 2 * P - cs[u] : 4 * P - p.rowsum[slot_base + 4 * g + row] - 2 * cs[u];
                 else if (EPI == kInt22) static_cast<int32_t*>(p.out)[at] = 2 * P - 3 * cs[u];
@@ -222,7 +221,7 @@ int launch_best_tile(MfmaParams p, int N, hipStream_t s) {
 
 }  // namespace
 
-// Binary layer: the raw product P (colsum == nullptr) or the integer part D into `out` (N*M int32).
+// Binary layer: the integer part D into `out` (N*M int32).
 int launch_binary_mfma(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
                        int32_t* out, hipStream_t s) {
     MfmaParams p{};
@@ -235,8 +234,7 @@ int launch_binary_mfma(const LayerDev& L, const uint32_t* planes, const int32_t*
     p.Kw = L.Kw;
     p.Mp = kWave * ((M + kWave - 1) / kWave);
     p.M = M;
-    if (colsum) return bits == 1 ? launch_best_tile<1, 1, kIntD>(p, L.N, s) : launch_best_tile<1, 2, kIntD>(p, L.N, s);
-    return bits == 1 ? launch_best_tile<1, 1, kRawProduct>(p, L.N, s) : launch_best_tile<1, 2, kRawProduct>(p, L.N, s);
+    return bits == 1 ? launch_best_tile<1, 1, kIntD>(p, L.N, s) : launch_best_tile<1, 2, kIntD>(p, L.N, s);
 }
 
 // 2/2 routine: D22 (int32) when Y == nullptr, else Y = scale * D22 (float).

@@ -21,7 +21,7 @@ constexpr int kEntBlockWords = 24;   // one block of 8 residual entries: 8 key w
 struct LayerDev {
     int N = 0, K = 0, Kw = 0;    // Kw = ceil(K/32)
     int Np = 0;                  // launch slots: N rounded up to a multiple of kRowTile * waves
-    int waves = 1;               // waves per workgroup of the forward kernel (1, 2, 4 or 8)
+    int waves = 2;               // waves per workgroup of the forward kernel (2, 4 or 8)
     int nchunks = 0;             // ceil(Kw / kChunkWords)
     long long nnz = 0;
     float alpha = 0.f;
@@ -46,6 +46,12 @@ struct LayerDev {
 };
 
 void set_last_hip_error(hipError_t e);
+
+// The 2-bit activation quantizer (Sec. IV "1/2"): p = clamp(rint(x / s), 0, 3) with one float
+// multiply by the precomputed 1/s, ties to even; NaN -> 0.
+__device__ __forceinline__ uint32_t code2(float x, float inv_step) {
+    return (uint32_t)(int)fminf(3.0f, fmaxf(0.0f, rintf(x * inv_step)));
+}
 
 #define APB_HIP(expr)                                 \
     do {                                              \
@@ -73,19 +79,22 @@ int launch_slot_tables(const int32_t* perm, const int32_t* row_ptr, const int32_
 // activations
 int launch_quantize(const float* X, int K, int M, int bits, float inv_step, uint32_t* planes, int32_t* colsum,
                     hipStream_t s);
+int launch_zero_words(uint32_t* p, size_t count, hipStream_t s);
 
 // forward
-// vector-ALU kernels: popcount formulation (Y, or D alone when D != nullptr), and the sparse part +
-// epilogue that turns the raw matrix-core product left in Y into the final output, in place
+// the popcount formulation on the vector ALU (Y, or D alone when D != nullptr)
 int launch_forward_popcount(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
                             float step, float* Y, int32_t* D, hipStream_t s);
-// fused: the kernel computes the binary part itself (workgroups of 4 or 8 waves only) instead of
-// reading the raw product from Y
-bool sparse_epilogue_can_fuse(const LayerDev& L);
-int launch_sparse_epilogue(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
-                           float step, float* Y, bool fused, hipStream_t s);
+// the forward kernel: binary part on the matrix cores, residual part and epilogue, one launch
+int launch_forward(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
+                   float* Y, hipStream_t s);
+// the same with the next layer's quantizer applied to scale[n] * Y + shift[n] (scale, shift nullable) and
+// the codes packed into `packed_out` (K = L.N, same M), which must have been zero-filled on `s`
+int launch_forward_requant(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
+                           const float* scale, const float* shift, int bits_out, float inv_step_out, uint32_t* packed_out,
+                           hipStream_t s);
 
-// binary part on the matrix cores: the raw product P (colsum == nullptr) or the integer part D
+// binary part alone on the matrix cores: the integer part D
 int launch_binary_mfma(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
                        int32_t* out, hipStream_t s);
 

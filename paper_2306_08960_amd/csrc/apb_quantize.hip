@@ -20,14 +20,8 @@ namespace {
 
 constexpr int kMaxWaves = 16;
 
-__global__ __launch_bounds__(256) void k_zero_i32(int32_t* __restrict__ p, int count) {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i < count) p[i] = 0;
-}
-
-// p = clamp(rint(x / s), 0, 3): one float multiply by the precomputed 1/s, ties to even; NaN -> 0.
-__device__ __forceinline__ uint32_t code2(float x, float inv_step) {
-    return (uint32_t)(int)fminf(3.0f, fmaxf(0.0f, rintf(x * inv_step)));
+__global__ __launch_bounds__(256) void k_zero_words(uint32_t* __restrict__ p, size_t count) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (size_t)gridDim.x * 256) p[i] = 0u;
 }
 
 template <int CPL>
@@ -144,6 +138,15 @@ void launch_pack(const float* X, int K, int M, int Kw, int Mp, float inv_step, u
 
 }  // namespace
 
+// A fill kernel rather than a memset node: the launch may be recorded into a graph.
+int launch_zero_words(uint32_t* p, size_t count, hipStream_t s) {
+    if (count == 0) return APB_OK;
+    const size_t blocks = (count + 255) / 256;
+    hipLaunchKernelGGL(k_zero_words, dim3((unsigned)(blocks < 65536 ? blocks : 65536)), dim3(256), 0, s, p, count);
+    APB_HIP(hipGetLastError());
+    return APB_OK;
+}
+
 int launch_quantize(const float* X, int K, int M, int bits, float inv_step, uint32_t* planes, int32_t* colsum,
                     hipStream_t s) {
     const int Kw = (K + 31) / 32;
@@ -174,8 +177,8 @@ int launch_quantize(const float* X, int K, int M, int bits, float inv_step, uint
         }
     }
     if (slabs > 1) {
-        hipLaunchKernelGGL(k_zero_i32, dim3((Mp + 255) / 256), dim3(256), 0, s, colsum, Mp);
-        APB_HIP(hipGetLastError());
+        const int rc = launch_zero_words(reinterpret_cast<uint32_t*>(colsum), (size_t)Mp, s);
+        if (rc != APB_OK) return rc;
     }
 #define APB_PACK(B, C) launch_pack<B, C>(X, K, M, Kw, Mp, inv_step, planes, colsum, strips, slabs, words_per_slab, waves, s)
     if (bits == 1) {

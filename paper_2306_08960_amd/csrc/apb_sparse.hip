@@ -1,11 +1,9 @@
 // The forward kernel of apb_forward (Sec. III Eqs. 12-13):
 //     Y[n,m] = s * ( alpha * D[n,m] + sum_{j in row n} val_j * c[col_j, m] )
-// In its fused mode (workgroups of 4 or 8 waves) the kernel first computes the binary product of its
-// tile on the matrix cores (binary_tile_to_lds below), starts its float64 row sums at alpha * D,
-// adds the residual part and writes Y: nothing but Y goes to HBM.  In its other mode (layers of at
-// most 32 rows) the stand-alone matrix-core kernel has left the raw product P in the output buffer
-// and this kernel overwrites the same elements with Y (every lane reads and writes only its own
-// outputs, so the pass is in place).
+// A workgroup (2, 4 or 8 waves) first computes the binary product of its tile on the matrix cores
+// (binary_tile_to_lds below), starts its float64 row sums at alpha * D, adds the residual part and
+// writes its outputs: nothing else goes to HBM.  The outputs are Y, or -- for a layer that feeds
+// another one -- the packed codes of the next layer's quantizer applied to Y (see write_rows).
 //
 // Mapping of the residual part: lanes run along m, so residual columns and values are wave-uniform
 // and arrive through the scalar path.  A workgroup (up to 8 waves, each owning a tile of 16 weight
@@ -48,6 +46,9 @@ struct SparseParams {
     int Np, Kw, Mp, M, nchunks;
     int row_groups;                          // Np / (TN * waves)
     int blocks;                              // row_groups * strips
+    int out_bits;                            // 0: float Y;  1 or 2: packed codes of the next layer
+    int out_Kw;                              // ceil(N / 32), words per column of a packed output plane
+    float out_inv_step;                      // 1 / step of the 2-bit output quantizer
 };
 
 // Spread the 4 low bits of `nib` to the least significant bits of the 4 bytes of a word.
@@ -198,10 +199,67 @@ __device__ __forceinline__ void binary_tile_to_lds(const uint32_t* __restrict__ 
         tile[(32 * tn + 8 * (r / 4) + 4 * g + (r % 4)) * kWave + 32 * tm + i] = (int)(c[r] * 4.0f);
 }
 
+// Epilogue of both kernels: a lane holds, for its column m, the 16 scaled float64 sums of the tile's
+// rows (alpha * D included).
+//   out_bits == 0: Y[n, m] = float(sum * step).
+//   otherwise `out` is the packed activation buffer of the NEXT layer, whose K is this layer's N
+//   (planes [out_bits][out_Kw][Mp], then colsum [Mp]; zero-filled before the launch): the value
+//   z = scale[n] * y + shift[n] (float64, rounded once to float; z = y without scale) is quantized
+//   exactly as apb_quantize_acts does and its code bits are OR-ed into word n / 32 of column m.  The
+//   rows of a tile are ascending, so the bits of rows that share a word are gathered in registers
+//   and leave as one atomic; rows of other tiles and workgroups add theirs to the same words, in any
+//   order (integer OR and add commute).
+template <int BITS>
+__device__ __forceinline__ void write_rows(const v16d& acc, int slot0, int m, const int32_t* __restrict__ perm,
+                                           const double* __restrict__ slot_valsum, const float* __restrict__ scale,
+                                           const float* __restrict__ shift, float* out, const SparseParams& p) {
+    const bool col_ok = m < p.M;
+    int n[TN];
+    double y[TN];
+#pragma unroll
+    for (int r = 0; r < TN; ++r) n[r] = perm[slot0 + r];
+#pragma unroll
+    for (int r = 0; r < TN; ++r) {
+        // 1-bit activations: the table holds (c+1)/2 in {0,1}: sum val*c = 2*sum val*code - sum val.
+        const double sum = acc[r] * kSumUnscale;
+        y[r] = (BITS == 1 ? 2.0 * sum - slot_valsum[slot0 + r] : sum) * p.step;
+    }
+    if (p.out_bits == 0) {
+#pragma unroll
+        for (int r = 0; r < TN; ++r)
+            if (col_ok && n[r] >= 0) out[(size_t)n[r] * p.M + m] = (float)y[r];
+        return;
+    }
+    uint32_t* words = reinterpret_cast<uint32_t*>(out);
+    const size_t plane = (size_t)p.out_Kw * p.Mp;
+    uint32_t w0 = 0, w1 = 0;
+    int total = 0;
+#pragma unroll
+    for (int r = 0; r < TN; ++r) {
+        if (n[r] < 0) continue;                                 // padding slot (wave-uniform)
+        double z = y[r];
+        if (scale) z = fma((double)scale[n[r]], z, (double)shift[n[r]]);
+        const float zf = (float)z;
+        uint32_t code = p.out_bits == 1 ? (zf >= 0.0f ? 1u : 0u) : code2(zf, p.out_inv_step);
+        if (!col_ok) code = 0;
+        w0 |= (code & 1u) << (n[r] & 31);
+        w1 |= (code >> 1) << (n[r] & 31);
+        total += (int)code;
+        const bool last_of_word = r == TN - 1 || n[r + 1] < 0 || (n[r + 1] >> 5) != (n[r] >> 5);
+        if (last_of_word) {
+            const size_t at = (size_t)(n[r] >> 5) * p.Mp + m;
+            if (w0) __hip_atomic_fetch_or(words + at, w0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (w1) __hip_atomic_fetch_or(words + plane + at, w1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            w0 = w1 = 0;
+        }
+    }
+    if (total)
+        __hip_atomic_fetch_add(reinterpret_cast<int32_t*>(words + p.out_bits * plane) + m, total, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // WPW = words of a chunk each wave expands = 8 / waves per workgroup.
-// FUSED: the binary part is computed here as well (first phase, see binary_tile_to_lds) and never
-// leaves the chip; otherwise the raw product is read from Y, where the matrix-core kernel left it.
-template <int BITS, int WPW, bool FUSED>
+template <int BITS, int WPW>
 __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_waves_per_eu(WPW <= 2 ? 8 : 4, 8))) void k_sparse_epilogue(
     // Separate restrict-qualified arguments (not struct members) so that the compiler knows the
     // read-only arrays cannot alias Y and keeps the wave-uniform loads on the scalar path.
@@ -210,8 +268,9 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
     const int32_t* __restrict__ seg_ptr,     // [tiles][nchunks+1] first entry block of (tile, chunk)
     const uint32_t* __restrict__ ent,        // blocks of 8 keys + 8 scaled residuals
     const double* __restrict__ slot_valsum,
-    const uint32_t* __restrict__ signT,      // [Kw rounded up to even][Np] slot-major sign words (FUSED)
-    float* Y,                                // not FUSED: holds P (int32 bits) on entry; Y on exit
+    const uint32_t* __restrict__ signT,      // [Kw rounded up to even][Np] slot-major sign words
+    const float* __restrict__ scale, const float* __restrict__ shift,   // [N] each or both null (packed output)
+    float* __restrict__ out,                 // Y, or the packed buffer of the next layer (see write_rows)
     const SparseParams p) {
     extern __shared__ __align__(16) uint8_t lds[];
     constexpr int waves = kChunkWords / WPW;
@@ -232,7 +291,7 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
 
     static_assert(TN == 16, "row field of an entry key addresses 16 register pairs");
     v16d acc;
-    if (FUSED) {
+    {
         // Binary part first; every lane then picks up the 16 products of its column and starts its
         // float64 sums at alpha * D (in the scaled domain of the residual products, and halved for
         // 1-bit activations, whose sum is doubled at the end).  The tile shares LDS with the code
@@ -253,9 +312,6 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
             const int d = BITS == 1 ? 4 * P[r] - rowsum[max(nr, 0)] - 2 * cs : 2 * P[r] - cs;
             acc[r] = a0 * (double)d;
         }
-    } else {
-#pragma unroll
-        for (int r = 0; r < TN; ++r) acc[r] = 0.0;
     }
     v8d pairs;
 #pragma unroll
@@ -314,38 +370,10 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
         // now, after every wave has passed the next barrier, i.e. has finished reading it.
     }
 
-    // Epilogue.  Everything is read before anything is written: row numbers, then the 16 raw products
-    // of this lane in one volley (rows of padding slots and columns past M re-read a valid element
-    // instead of branching), then the arithmetic and the stores.
     // (The column is recomputed from the lane number here rather than kept in a register -- or
     // spilled -- through the loops above.)
     const int m_e = strip * kWave + (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
-    const bool col_ok = m_e < p.M;
-    const int mc = min(m_e, p.M - 1);
-    const int cs = colsum[m_e];
-    int n[TN], P[TN];
-#pragma unroll
-    for (int r = 0; r < TN; ++r) n[r] = perm[slot0 + r];
-    if (!FUSED) {
-#pragma unroll
-        for (int r = 0; r < TN; ++r)
-            P[r] = reinterpret_cast<const int32_t*>(Y)[(size_t)max(n[r], 0) * p.M + mc];
-    }
-#pragma unroll
-    for (int r = 0; r < TN; ++r) {
-        // 1-bit activations: the table holds (c+1)/2 in {0,1}: sum val*c = 2*sum val*code - sum val.
-        const double sum = acc[r] * kSumUnscale;
-        const double sparse = BITS == 1 ? 2.0 * sum - slot_valsum[slot0 + r] : sum;
-        double y;
-        if (FUSED) {
-            y = sparse * p.step;                                // alpha * D is already in the sum
-        } else {
-            // raw matrix-core product P = sum_k b*code  ->  D (b = sign bit, code = stored code)
-            const int d = BITS == 1 ? 4 * P[r] - rowsum[max(n[r], 0)] - 2 * cs : 2 * P[r] - cs;
-            y = fma(p.alpha, (double)d, sparse) * p.step;
-        }
-        if (col_ok && n[r] >= 0) Y[(size_t)n[r] * p.M + m_e] = (float)y;
-    }
+    write_rows<BITS>(acc, slot0, m_e, perm, slot_valsum, scale, shift, out, p);
 }
 
 // The same forward for launches that would leave most of the chip idle (few column strips, few row
@@ -361,8 +389,8 @@ template <int BITS, int KS>
 __global__ __launch_bounds__(kWave* kChunkWords) __attribute__((amdgpu_waves_per_eu(4, 8))) void k_forward_ksplit(
     const uint32_t* __restrict__ planes, const int32_t* __restrict__ colsum, const int32_t* __restrict__ rowsum,
     const int32_t* __restrict__ perm, const int32_t* __restrict__ seg_ptr, const uint32_t* __restrict__ ent,
-    const double* __restrict__ slot_valsum, const uint32_t* __restrict__ signT, float* __restrict__ Y,
-    const SparseParams p) {
+    const double* __restrict__ slot_valsum, const uint32_t* __restrict__ signT, const float* __restrict__ scale,
+    const float* __restrict__ shift, float* __restrict__ out, const SparseParams p) {
     extern __shared__ __align__(16) uint8_t lds[];
     constexpr int TW = kChunkWords / KS;                         // tiles (of 16 rows) per workgroup
     static_assert(KS == 2 || KS == 4, "two or four parts of K");
@@ -474,15 +502,7 @@ __global__ __launch_bounds__(kWave* kChunkWords) __attribute__((amdgpu_waves_per
 #pragma unroll
         for (int r = 0; r < TN; ++r) acc[r] += red[(((q - 1) * TW + tl) * TN + r) * kWave + lane];
 
-    const bool col_ok = m < p.M;
-#pragma unroll
-    for (int r = 0; r < TN; ++r) {
-        const int n = perm[slot0 + r];
-        // 1-bit activations: the table holds (c+1)/2 in {0,1}: sum val*c = 2*sum val*code - sum val.
-        const double sum = acc[r] * kSumUnscale;
-        const double sparse = BITS == 1 ? 2.0 * sum - slot_valsum[slot0 + r] : sum;
-        if (col_ok && n >= 0) Y[(size_t)n * p.M + m] = (float)(sparse * p.step);   // alpha * D is in the sum
-    }
+    write_rows<BITS>(acc, slot0, m, perm, slot_valsum, scale, shift, out, p);
 }
 
 template <int KS>
@@ -494,8 +514,14 @@ constexpr int ksplit_lds_bytes() {
                                      : (partial_products > partial_sums ? partial_products : partial_sums);
 }
 
+struct OutArgs {
+    const float* scale;
+    const float* shift;
+    float* out;
+};
+
 template <int BITS, int KS>
-int launch_ksplit(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, float* Y, SparseParams p,
+int launch_ksplit(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, const OutArgs& o, SparseParams p,
                   hipStream_t s) {
     constexpr int TW = kChunkWords / KS;
     constexpr int kLds = ksplit_lds_bytes<KS>();
@@ -507,44 +533,32 @@ int launch_ksplit(const LayerDev& L, const uint32_t* planes, const int32_t* cols
         APB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_forward_ksplit<BITS, KS>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
     hipLaunchKernelGGL((k_forward_ksplit<BITS, KS>), dim3((unsigned)p.blocks), dim3(kWave * kChunkWords), kLds, s, planes,
-                       colsum, L.rowsum, L.perm, L.seg_ptr, L.ent, L.slot_valsum, L.signT, Y, p);
+                       colsum, L.rowsum, L.perm, L.seg_ptr, L.ent, L.slot_valsum, L.signT, o.scale, o.shift, o.out, p);
     return APB_OK;
 }
 
-template <int BITS, int WPW, bool FUSED>
-void launch_one(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, float* Y, const SparseParams& p,
+template <int BITS, int WPW>
+void launch_one(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, const OutArgs& o, const SparseParams& p,
                 hipStream_t s) {
-    hipLaunchKernelGGL((k_sparse_epilogue<BITS, WPW, FUSED>), dim3((unsigned)p.blocks), dim3(kWave * kChunkWords / WPW),
+    hipLaunchKernelGGL((k_sparse_epilogue<BITS, WPW>), dim3((unsigned)p.blocks), dim3(kWave * kChunkWords / WPW),
                        table_buffers(WPW) * kTableBytes, s, planes, colsum, L.rowsum, L.perm, L.seg_ptr, L.ent,
-                       L.slot_valsum, L.signT, Y, p);
+                       L.slot_valsum, L.signT, o.scale, o.shift, o.out, p);
 }
 
 template <int BITS>
-int launch_bits(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, float* Y, const SparseParams& p,
-                bool fused, hipStream_t s) {
+int launch_bits(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, const OutArgs& o, const SparseParams& p,
+                hipStream_t s) {
     switch (L.waves) {
-        case 8:
-            if (fused) launch_one<BITS, 1, true>(L, planes, colsum, Y, p, s);
-            else launch_one<BITS, 1, false>(L, planes, colsum, Y, p, s);
-            break;
-        case 4:
-            if (fused) launch_one<BITS, 2, true>(L, planes, colsum, Y, p, s);
-            else launch_one<BITS, 2, false>(L, planes, colsum, Y, p, s);
-            break;
-        case 2: launch_one<BITS, 4, false>(L, planes, colsum, Y, p, s); break;
-        case 1: launch_one<BITS, 8, false>(L, planes, colsum, Y, p, s); break;
+        case 8: launch_one<BITS, 1>(L, planes, colsum, o, p, s); break;
+        case 4: launch_one<BITS, 2>(L, planes, colsum, o, p, s); break;
+        case 2: launch_one<BITS, 4>(L, planes, colsum, o, p, s); break;
         default: return APB_ERR_SHAPE;
     }
     return APB_OK;
 }
 
-}  // namespace
-
-bool sparse_epilogue_can_fuse(const LayerDev& L) { return L.waves >= 4; }
-
-int launch_sparse_epilogue(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
-                           float step, float* Y, bool fused, hipStream_t s) {
-    if (fused && !sparse_epilogue_can_fuse(L)) return APB_ERR_SHAPE;
+int launch_any(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
+               const OutArgs& o, int out_bits, float out_inv_step, hipStream_t s) {
     const int Mp = kWave * ((M + kWave - 1) / kWave);
     SparseParams p;
     p.alpha = (double)L.alpha;
@@ -554,24 +568,42 @@ int launch_sparse_epilogue(const LayerDev& L, const uint32_t* planes, const int3
     p.Mp = Mp;
     p.M = M;
     p.nchunks = L.nchunks;
+    p.out_bits = out_bits;
+    p.out_Kw = (L.N + 31) / 32;
+    p.out_inv_step = out_inv_step;
     p.row_groups = L.Np / (TN * L.waves);
     const long long blocks = (long long)p.row_groups * (Mp / kWave);
     if (blocks > 0x7fffffffLL || (long long)Mp * 4 >= (1LL << 31)) return APB_ERR_SHAPE;
     p.blocks = (int)blocks;
     int rc;
-    // Fused launches of 8-wave workgroups that would put fewer than ~3000 waves on the chip split K
-    // two or four ways inside the workgroup instead (see k_forward_ksplit).
+    // Launches of 8-wave workgroups that would put fewer than ~3000 waves on the chip split K two or
+    // four ways inside the workgroup instead (see k_forward_ksplit).
     int ks = 1;
-    if (fused && L.waves == 8) {
+    if (L.waves == 8) {
         if (blocks * 8 < 3000 && L.nchunks >= 2) ks = 2;
         if (blocks * 16 < 3000 && L.nchunks >= 4) ks = 4;
     }
-    if (ks == 2) rc = bits == 1 ? launch_ksplit<1, 2>(L, planes, colsum, Y, p, s) : launch_ksplit<2, 2>(L, planes, colsum, Y, p, s);
-    else if (ks == 4) rc = bits == 1 ? launch_ksplit<1, 4>(L, planes, colsum, Y, p, s) : launch_ksplit<2, 4>(L, planes, colsum, Y, p, s);
-    else rc = bits == 1 ? launch_bits<1>(L, planes, colsum, Y, p, fused, s) : launch_bits<2>(L, planes, colsum, Y, p, fused, s);
+    if (ks == 2) rc = bits == 1 ? launch_ksplit<1, 2>(L, planes, colsum, o, p, s) : launch_ksplit<2, 2>(L, planes, colsum, o, p, s);
+    else if (ks == 4) rc = bits == 1 ? launch_ksplit<1, 4>(L, planes, colsum, o, p, s) : launch_ksplit<2, 4>(L, planes, colsum, o, p, s);
+    else rc = bits == 1 ? launch_bits<1>(L, planes, colsum, o, p, s) : launch_bits<2>(L, planes, colsum, o, p, s);
     if (rc != APB_OK) return rc;
     APB_HIP(hipGetLastError());
     return APB_OK;
+}
+
+}  // namespace
+
+int launch_forward(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
+                   float* Y, hipStream_t s) {
+    return launch_any(L, planes, colsum, M, bits, step, OutArgs{nullptr, nullptr, Y}, 0, 0.0f, s);
+}
+
+// packed_out: the next layer's packed activation buffer (K = L.N), zero-filled on `s` before this launch.
+int launch_forward_requant(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
+                           const float* scale, const float* shift, int bits_out, float inv_step_out, uint32_t* packed_out,
+                           hipStream_t s) {
+    return launch_any(L, planes, colsum, M, bits, step, OutArgs{scale, shift, reinterpret_cast<float*>(packed_out)},
+                      bits_out, inv_step_out, s);
 }
 
 }  // namespace apb

@@ -422,3 +422,57 @@ def test_2_2_gemm_matches_the_plain_definition():
     Yb = o.brute_force_2_2(W, sw, X, sa)
     assert np.allclose(G["Y"], Yb, rtol=1e-6, atol=1e-9)
     assert np.abs(G["D"]).max() <= 3 * 3 * 130
+
+
+# --------------------------------------------------------------------------- two layers in a row
+def test_forward_requant_on_exactly_representable_values():
+    """Weights +-1/4 with a few outliers at multiples of 1/2, activations p/2: every Y is a multiple
+    of 1/8, so Z and the level index are exact and can be written down with Python's fractions
+    (round() on a Fraction rounds halves to even, as the quantizer must)."""
+    from fractions import Fraction as Fr
+    r = np.random.default_rng(77)
+    N, K, M = 7, 45, 9
+    W = np.where(r.random((N, K)) < 0.5, 0.25, -0.25).astype(np.float32)
+    for (n, k, v) in [(0, 3, 1.5), (0, 44, -2.0), (2, 0, 2.5), (6, 17, -1.5), (6, 18, 3.0)]:
+        W[n, k] = v
+    p_in = r.integers(0, 4, (K, M))
+    X = (p_in * 0.5).astype(np.float32)
+    L = o.compress(W, np.float32(0.25), alpha=np.float32(0.25))
+    assert np.diff(L["row_ptr"]).tolist() == [2, 0, 1, 0, 0, 0, 2]
+    c = o.quantize(X, 2, np.float32(0.5))
+    assert np.array_equal(c, p_in)
+    scale = np.array([1, 0.5, 2, 1, -1, 0.25, 1], dtype=np.float32)
+    shift = np.array([0, 0.25, -1, 0.125, 3, 0, -0.5], dtype=np.float32)
+    for sc, sh in ((None, None), (scale, shift)):
+        for bits_out, step_out in ((2, 1.0), (2, 0.25), (1, 1.0)):
+            got = o.forward_requant(L, c, np.float32(0.5), bits_out, np.float32(step_out), sc, sh)
+            want = np.zeros((N, M), dtype=np.int64)
+            for n in range(N):
+                for m in range(M):
+                    y = sum(Fr(float(W[n, k])) * Fr(int(p_in[k, m]), 2) for k in range(K))
+                    z = y if sc is None else Fr(float(sc[n])) * y + Fr(float(sh[n]))
+                    assert float(got["Z"][n, m]) == float(z)
+                    want[n, m] = (1 if z >= 0 else -1) if bits_out == 1 else min(3, max(0, round(z / Fr(step_out))))
+            assert np.array_equal(got["c"], want)
+            assert np.array_equal(got["packed"], o.pack_acts(want.astype(np.int8), bits_out))
+    # ties really occur in this case (otherwise the rounding rule would go untested)
+    Z = o.forward_requant(L, c, np.float32(0.5), 2, np.float32(0.25))["Z"].astype(np.float64)
+    assert np.any(np.abs(Z / 0.25 - np.floor(Z / 0.25) - 0.5) == 0.0)
+
+
+def test_two_layer_chain_equals_the_dense_definition():
+    """forward_requant of layer 1 feeding forward of layer 2 == APB(W2) @ dequantize(quantize(APB(W1) @ X^))."""
+    W1, d1, X, step = _case(12, 70, 10, 2, 0.1, 901)
+    W2, d2, _, _ = _case(5, 12, 10, 2, 0.1, 902)
+    L1, L2 = o.compress(W1, d1), o.compress(W2, d2)
+    c1 = o.quantize(X, 2, step)
+    s2 = np.float32(0.05)
+    hop = o.forward_requant(L1, c1, step, 2, s2)
+    Y2 = o.forward(L2, hop["c"], s2)["Y"]
+    Y1 = o.brute_force(W1, d1, L1["alpha"], X, 2, step)                 # float64, the definition
+    lvl = Y1.astype(np.float32).astype(np.float64) / np.float64(s2)
+    assert np.min(np.abs(lvl - np.floor(lvl) - 0.5)) > 1e-4            # no near-tie: the codes are unambiguous
+    c2 = np.clip(np.rint(lvl), 0, 3)
+    assert np.array_equal(hop["c"], c2)
+    want = o.apb_dense(W2, d2, L2["alpha"]) @ (c2 * np.float64(s2))
+    assert np.allclose(Y2, want, rtol=1e-6, atol=1e-9)
