@@ -47,7 +47,7 @@ def parse_args():
     ap.add_argument("--sweep", action="store_true",
                     help="square-matrix sweep of the three bitwise products (1/1, 1/2, 2/2; Sec. V protocol): one JSON "
                          "line with the time of the product alone at each size")
-    ap.add_argument("--routine", default="apb", choices=["apb", "gemm_2_2"],
+    ap.add_argument("--routine", default="apb", choices=["apb", "gemm_2_2", "chain"],
                     help="apb: the APB layer forward (the headline metric); gemm_2_2: the 2-bit x 2-bit "
                          "product of Sec. IV on the same shapes (weights packed offline)")
     return ap.parse_args()
@@ -129,8 +129,8 @@ def run_workload(name, steps, warmup, calibration_copy=False):
                   "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": MEASURED_TRAFFIC_BYTES.get((name, "k_quantize_pack")),
                   "algorithmic_bytes": quant_bytes, "ms": ms_quant}
     roof_quant["frac"] = roof_quant["achieved"] / roof_quant["peak"]
-    # forward = k_sparse_epilogue in fused mode (binary tile on the matrix cores + residual part + epilogue;
-    # layers of at most 32 rows: k_binary_mfma + k_sparse_epilogue).  Its floor is the largest of: the bytes it has to move
+    # forward = one kernel (binary tile on the matrix cores + residual part + epilogue).  Its floor is the
+    # largest of: the bytes it has to move
     # (sign words, bit-planes, residual entries, Y), the FP4 matrix-core time of the binary product and
     # the float64 vector time of the residual multiply-adds.
     fwd_bytes = 4.0 * N * Kw + 4.0 * bits * Kw * Mp + 4.0 * Mp + 12.0 * nnz + 4.0 * N * M
@@ -224,6 +224,105 @@ def run_gemm_2_2(name, steps, warmup):
     del Xd, packed, Y
     torch.cuda.empty_cache()
     return res, (cfg, W, step_w, X, step)
+
+
+def run_chain(name, steps, warmup):
+    """A layer in the middle of a network: its input arrives packed (written by the layer before) and its
+    output leaves packed for the layer after.  Step = apb_forward_requant alone; beside it the two-call route
+    to the same buffer, apb_forward (float Y to HBM) + apb_quantize_acts (Y read back)."""
+    import torch
+    from paper_2306_08960_amd import binding as b
+    from paper_2306_08960_amd import synth
+
+    cfg = synth.CONFIGS[name]
+    W, delta, X, step = synth.make_layer(cfg)
+    N, K, M, bits = cfg.N, cfg.K, cfg.M, cfg.bits
+    layer = b.apb_compress(torch.from_numpy(W).cuda(), float(delta))
+    nnz = layer.info()["nnz"]
+    packed = b.apb_quantize_acts(torch.from_numpy(X).cuda(), bits, float(step))
+    s = float(step)
+    bits_out = bits
+    step_out = float(0.03 * np.sqrt(K)) if bits_out == 2 else 1.0       # spreads Y over the four levels
+    out_a = b.alloc_packed(N, M, bits_out)
+    out_b = b.alloc_packed(N, M, bits_out)
+    Y = torch.empty((N, M), dtype=torch.float32, device="cuda")
+
+    def chained():
+        b.apb_forward_requant(layer, packed, M, bits, s, bits_out, step_out, packed_out=out_a)
+
+    def two_calls():
+        b.apb_forward(layer, packed, M, bits, s, Y=Y)
+        b.apb_quantize_acts(Y, bits_out, step_out, packed=out_b)
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    ms_chain, ms_two = timed(chained), timed(two_calls)
+    # the chained call alone between HIP events on its stream, the cost of the records taken off as in time_in_step
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for a, c in ev:
+        a.record()
+        chained()
+        c.record()
+    torch.cuda.synchronize()
+    per_record = max(0.0, ((time.perf_counter() - t0) * 1e3 / steps - ms_chain) / 2.0)
+    ms_call = sum(a.elapsed_time(c) for a, c in ev) / steps - per_record
+    same = bool(torch.equal(out_a, out_b))
+    differing = int((out_a != out_b).sum().item())
+    ops = 2.0 * N * K * M + 2.0 * nnz * M
+    Kw, Mp, Nw = (K + 31) // 32, 64 * ((M + 63) // 64), (N + 31) // 32
+    out_bytes = 4.0 * (bits_out * Nw + 1) * Mp
+    # sign words, bit-planes, residual entries in; the packed output is zero-filled, then read-modify-written
+    fwd_bytes = 4.0 * N * Kw + 4.0 * bits * Kw * Mp + 4.0 * Mp + 12.0 * nnz + 3.0 * out_bytes
+    t_hbm = fwd_bytes / (HBM_PEAK_GBS * 1e9)
+    t_mfma = 2.0 * N * K * M / (MFMA_FP4_PEAK_TFLOPS * 1e12)
+    t_f64 = 2.0 * nnz * M / (FP64_VECTOR_PEAK_TFLOPS * 1e12)
+    t = ms_call * 1e-3
+    if t_hbm >= max(t_mfma, t_f64):
+        roof = {"bound": "hbm", "achieved": fwd_bytes / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    elif t_mfma >= t_f64:
+        roof = {"bound": "mfma", "achieved": 2.0 * N * K * M / t / 1e12, "peak": MFMA_FP4_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    else:
+        roof = {"bound": "alu", "achieved": 2.0 * nnz * M / t / 1e12, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    roof = {"kernel": "forward kernel with the packed-output epilogue (+ zero fill)"} | roof
+    roof |= {"frac": roof["achieved"] / roof["peak"], "traffic": None, "ms": ms_call,
+             "floor_us": {"hbm": t_hbm * 1e6, "mfma_fp4": t_mfma * 1e6, "fp64_vector": t_f64 * 1e6}}
+    res = {"workload": name, "N": N, "K": K, "M": M, "act_bits": bits, "nnz": int(nnz), "ms_per_step": ms_chain,
+           "gops_step": ops / (ms_chain * 1e-3) / 1e9, "ms_forward_plus_quantize": ms_two, "gops_forward_plus_quantize": ops / (ms_two * 1e-3) / 1e9,
+           "same_packed_output": same, "words_differing": differing, "roofline": roof, "bits_out": bits_out, "step_out": step_out}
+    layer.free()
+    return res, (cfg, W, delta, X, step, bits_out, step_out)
+
+
+def cpu_baseline_chain(cfg, W, delta, X, step, bits_out, step_out):
+    """The CPU oracle of the chained step (forward from packed codes, re-quantize, pack) on the first columns."""
+    from oracle import apb_oracle as o
+    from oracle import capi
+    cores = max(1, min(len(os.sched_getaffinity(0)), capi.max_threads()))
+    L = o.compress(W, delta)
+    nnz = int(L["row_ptr"][-1])
+    per_col = 2.0 * cfg.N * cfg.K + 2.0 * nnz
+    m = int(max(64, min(cfg.M, 60e9 * cores ** 0.5 / per_col)))
+    c = o.quantize(np.ascontiguousarray(X[:, :m]), cfg.bits, step)
+    packed = o.pack_acts(c, cfg.bits)
+    passes, dt = 0, 0.0
+    while passes == 0 or (dt < 1.0 and passes < 20):
+        t0 = time.perf_counter()
+        F = capi.forward(L, packed, c, cfg.bits, step, threads=cores)
+        o.requant(L["alpha"], step, F["D"], F["R"], bits_out, np.float32(step_out))
+        dt += time.perf_counter() - t0
+        passes += 1
+    return {"value": per_col * m * passes / dt / 1e9, "unit": "GOPS", "cores": cores, "kind": "oracle",
+            "sample": f"first {m} of {cfg.M} columns of {cfg.name}, {passes} passes (forward+requantize+pack), {dt:.2f} s"}
 
 
 def run_square_sweep(sizes=(512, 1024, 2048, 4096, 8192), iters=30):
@@ -352,6 +451,27 @@ def main():
         }
         if not args.no_cpu_baseline:
             out["cpu_baseline"] = cpu_baseline_2_2(*inputs)
+        print(json.dumps(out))
+        return
+
+    if args.routine == "chain":
+        res, inputs = run_chain(args.workload, args.steps, args.warmup)
+        cfg = inputs[0]
+        out = {
+            "metric": "APB layer forward GOPS, chained (packed activations in, packed activations out)",
+            "value": res["gops_step"], "unit": "GOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "fp4 (exact 0/1 and 2-bit codes) on MFMA + f64 accumulate, packed codes in/out", "data": "synthetic",
+            "config": {"workload": f"{cfg.name}: {cfg.note}", "N": cfg.N, "K": cfg.K, "M": cfg.M, "act_bits": cfg.bits,
+                       "outlier_rate": cfg.rho, "nnz": res["nnz"], "bits_out": res["bits_out"], "step_out": res["step_out"],
+                       "step": "apb_forward_requant, packed input resident in HBM"},
+            "ms_forward_plus_quantize": res["ms_forward_plus_quantize"],
+            "gops_forward_plus_quantize": res["gops_forward_plus_quantize"],
+            "same_packed_output_as_two_calls": res["same_packed_output"], "words_differing": res["words_differing"],
+            "roofline": res["roofline"],
+        }
+        if not args.no_cpu_baseline:
+            out["cpu_baseline"] = cpu_baseline_chain(*inputs)
         print(json.dumps(out))
         return
 
