@@ -27,6 +27,8 @@ What is computed, and where it is defined:
   forward_requant Eq. 13 of one layer followed by the activation quantizer
                   (Sec. IV) of the layer it feeds, with an optional per-row
                   affine map in between (a folded batch normalization)
+  im2col_codes    Sec. III, footnote on convolutions: a convolution is the matrix
+                  product of the layer with the im2col matrix of its input map
   dot_2_2_mbm     Sec. IV "2/2": the 1/2 routine applied twice -- four mbm terms
                   under the and of the two masks, with the level weights 9/4,
                   3/4, 3/4, 1/4 that the printed equation leaves out (and the
@@ -312,6 +314,18 @@ def forward_requant(layer: dict, c: np.ndarray, step, bits_out: int, step_out, s
     D = int_part_unpacked(layer["bit"], c)
     R = sparse_part(layer["row_ptr"], layer["col_idx"], layer["val"], c, step)
     return requant(layer["alpha"], step, D, R, bits_out, step_out, scale, shift)
+
+
+def im2col_codes(c_map: np.ndarray, B: int, H: int, W: int, bits: int) -> np.ndarray:
+    """Patch matrix [9*C, B*H*W] of a 3x3 convolution (stride 1, padding 1) over the integer activation
+    values of a feature map [C, B*H*W] (column = (b*H + y)*W + x).  Row tap*C + ch with tap = 3*ky + kx;
+    column (b, y, x) holds the value at (b, y + ky - 1, x + kx - 1), and outside the image the value
+    whose stored code is 0: 0 for 2-bit activations (zero padding), -1 for 1-bit ones."""
+    C, P = c_map.shape
+    assert P == B * H * W
+    padded = np.full((C, B, H + 2, W + 2), 0 if bits == 2 else -1, dtype=c_map.dtype)
+    padded[:, :, 1:H + 1, 1:W + 1] = c_map.reshape(C, B, H, W)
+    return np.concatenate([padded[:, :, ky:ky + H, kx:kx + W].reshape(C, P) for ky in range(3) for kx in range(3)], axis=0)
 
 
 def brute_force(W: np.ndarray, delta, alpha, X: np.ndarray, bits: int, step) -> np.ndarray:

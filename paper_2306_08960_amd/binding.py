@@ -20,7 +20,8 @@ LIB_PATH = os.path.join(_HERE, "libapb.so")
 
 EXPORTS = (
     "apb_compress", "apb_layer_info", "apb_layer_export", "apb_layer_free", "apb_acts_bytes",
-    "apb_quantize_acts", "apb_forward", "apb_forward_requant", "apb_forward_int", "apb_forward_int_popcount", "apb_forward_popcount",
+    "apb_quantize_acts", "apb_forward", "apb_forward_requant", "apb_forward_conv3x3", "apb_forward_conv3x3_requant",
+    "apb_forward_int", "apb_forward_int_popcount", "apb_forward_popcount",
     "apb_w2_pack", "apb_w2_export", "apb_w2_free", "apb_gemm_2_2_int", "apb_gemm_2_2",
     "apb_strerror", "apb_last_hip_error",
 )
@@ -64,6 +65,10 @@ def load() -> ctypes.CDLL:
     lib.apb_forward.restype = ci
     lib.apb_forward_requant.argtypes = [vp, vp, ci, ci, cf, vp, vp, ci, cf, vp, vp]
     lib.apb_forward_requant.restype = ci
+    lib.apb_forward_conv3x3.argtypes = [vp, vp, ci, ci, ci, ci, cf, vp, vp]
+    lib.apb_forward_conv3x3.restype = ci
+    lib.apb_forward_conv3x3_requant.argtypes = [vp, vp, ci, ci, ci, ci, cf, vp, vp, ci, cf, vp, vp]
+    lib.apb_forward_conv3x3_requant.restype = ci
     lib.apb_forward_int.argtypes = [vp, vp, ci, ci, vp, vp]
     lib.apb_forward_int.restype = ci
     lib.apb_forward_int_popcount.argtypes = [vp, vp, ci, ci, vp, vp]
@@ -243,6 +248,53 @@ def apb_forward_requant(layer: ApbLayer, packed: torch.Tensor, M: int, bits: int
                                       int(bits_out), float(step_out), _dev_ptr(packed_out, torch.int32, "packed_out"),
                                       _stream(stream)), "apb_forward_requant")
     return packed_out
+
+
+def _check_fmap(layer: ApbLayer, fmap: torch.Tensor, B: int, H: int, W: int, bits: int) -> Tuple[int, int]:
+    i = apb_layer_info(layer)
+    if i["K"] % 9:
+        raise ValueError("the layer's K is not 9 * C")
+    P = int(B) * int(H) * int(W)
+    need = apb_acts_bytes(i["K"] // 9, P, bits)
+    if need and fmap.numel() * fmap.element_size() < need:
+        raise ValueError("fmap smaller than apb_acts_bytes(C, B*H*W, bits)")
+    return i["N"], P
+
+
+def apb_forward_conv3x3(layer: ApbLayer, fmap: torch.Tensor, B: int, H: int, W: int, bits: int, step: float,
+                        Y: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """3x3 convolution over a packed feature map [C, B*H*W]; Y is [N, B*H*W]."""
+    N, P = _check_fmap(layer, fmap, B, H, W, bits)
+    if Y is None:
+        Y = torch.empty((N, P), dtype=torch.float32, device=fmap.device)
+    elif tuple(Y.shape) != (N, P):
+        raise ValueError("Y must be [N, B*H*W]")
+    _check(load().apb_forward_conv3x3(layer.handle, _dev_ptr(fmap, torch.int32, "fmap"), int(B), int(H), int(W), int(bits),
+                                      float(step), _dev_ptr(Y, torch.float32, "Y"), _stream(stream)),
+           "apb_forward_conv3x3")
+    return Y
+
+
+def apb_forward_conv3x3_requant(layer: ApbLayer, fmap: torch.Tensor, B: int, H: int, W: int, bits: int, step: float,
+                                bits_out: int, step_out: float, scale: Optional[torch.Tensor] = None,
+                                shift: Optional[torch.Tensor] = None, fmap_out: Optional[torch.Tensor] = None,
+                                stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    N, P = _check_fmap(layer, fmap, B, H, W, bits)
+    if (scale is None) != (shift is None):
+        raise ValueError("scale and shift go together")
+    for name, t in (("scale", scale), ("shift", shift)):
+        if t is not None and t.numel() != N:
+            raise ValueError(f"{name} must hold N floats")
+    if fmap_out is None:
+        fmap_out = alloc_packed(N, P, bits_out, fmap.device)
+    elif fmap_out.numel() * fmap_out.element_size() < apb_acts_bytes(N, P, bits_out):
+        raise ValueError("fmap_out smaller than apb_acts_bytes(N, B*H*W, bits_out)")
+    _check(load().apb_forward_conv3x3_requant(
+        layer.handle, _dev_ptr(fmap, torch.int32, "fmap"), int(B), int(H), int(W), int(bits), float(step),
+        None if scale is None else _dev_ptr(scale, torch.float32, "scale"),
+        None if shift is None else _dev_ptr(shift, torch.float32, "shift"), int(bits_out), float(step_out),
+        _dev_ptr(fmap_out, torch.int32, "fmap_out"), _stream(stream)), "apb_forward_conv3x3_requant")
+    return fmap_out
 
 
 def apb_forward_int(layer: ApbLayer, packed: torch.Tensor, M: int, bits: int,

@@ -328,7 +328,7 @@ static int forward_common(const apb_layer* layer, const void* packed, int M, int
         return launch_binary_mfma(d, planes, colsum, M, bits, D, s);
     }
     if (kind == kFwdFull) {
-        return launch_forward(d, planes, colsum, M, bits, step, Y, s);
+        return launch_forward(d, planes, colsum, M, bits, step, nullptr, Y, s);
     }
     return launch_forward_popcount(d, planes, colsum, M, bits, step, Y, D, s);
 }
@@ -353,7 +353,55 @@ int apb_forward_requant(const apb_layer* layer, const void* packed, int M, int b
     const size_t out_words = ((size_t)bits_out * (((size_t)d.N + 31) / 32) + 1) * Mp;     // planes + colsum
     const int rc = launch_zero_words(out, out_words, s);
     if (rc != APB_OK) return rc;
-    return launch_forward_requant(d, planes, colsum, M, bits, step, scale, shift, bits_out, 1.0f / step_out, out, s);
+    return launch_forward_requant(d, planes, colsum, M, bits, step, nullptr, scale, shift, bits_out, 1.0f / step_out, out, s);
+}
+
+// Shape checks shared by the two convolution entry points; fills `conv` and the pixel count.
+static int conv_shape(const LayerDev& d, int B, int H, int W, ConvShape& conv, int& P) {
+    if (B <= 0 || H <= 0 || W <= 0 || d.K % 9 != 0 || (d.K / 9) % 64 != 0) return APB_ERR_SHAPE;
+    if (d.K / 9 > 16384) return APB_ERR_SHAPE;                 // the kernels' row -> tap arithmetic is exact up to here
+    const long long pixels = (long long)B * H * W;
+    if (pixels >= (1LL << 28) || (long long)d.N * pixels >= (1LL << 40)) return APB_ERR_SHAPE;
+    conv = ConvShape{d.K / 9, H, W};
+    P = (int)pixels;
+    return APB_OK;
+}
+
+int apb_forward_conv3x3(const apb_layer* layer, const void* fmap, int B, int H, int W, int bits, float step, float* Y,
+                        void* stream) {
+    if (!layer || !fmap || !Y) return APB_ERR_NULL;
+    const LayerDev& d = layer->d;
+    ConvShape conv;
+    int P;
+    const int rc = conv_shape(d, B, H, W, conv, P);
+    if (rc != APB_OK) return rc;
+    if (bits != 1 && bits != 2) return APB_ERR_BITS;
+    if (!std::isfinite(step) || !(step > 0.0f)) return APB_ERR_VALUE;
+    const size_t Pp = (size_t)kWave * (((size_t)P + kWave - 1) / kWave);
+    const uint32_t* planes = static_cast<const uint32_t*>(fmap);
+    const int32_t* pixsum = reinterpret_cast<const int32_t*>(planes + (size_t)bits * (conv.C / 32) * Pp);
+    return launch_forward(d, planes, pixsum, P, bits, step, &conv, Y, as_stream(stream));
+}
+
+int apb_forward_conv3x3_requant(const apb_layer* layer, const void* fmap, int B, int H, int W, int bits, float step,
+                                const float* scale, const float* shift, int bits_out, float step_out, void* fmap_out,
+                                void* stream) {
+    if (!layer || !fmap || !fmap_out || (scale == nullptr) != (shift == nullptr)) return APB_ERR_NULL;
+    const LayerDev& d = layer->d;
+    ConvShape conv;
+    int P;
+    int rc = conv_shape(d, B, H, W, conv, P);
+    if (rc != APB_OK) return rc;
+    if ((bits != 1 && bits != 2) || (bits_out != 1 && bits_out != 2)) return APB_ERR_BITS;
+    if (!std::isfinite(step) || !(step > 0.0f) || !std::isfinite(step_out) || !(step_out > 0.0f)) return APB_ERR_VALUE;
+    const size_t Pp = (size_t)kWave * (((size_t)P + kWave - 1) / kWave);
+    const uint32_t* planes = static_cast<const uint32_t*>(fmap);
+    const int32_t* pixsum = reinterpret_cast<const int32_t*>(planes + (size_t)bits * (conv.C / 32) * Pp);
+    hipStream_t s = as_stream(stream);
+    uint32_t* out = static_cast<uint32_t*>(fmap_out);
+    const size_t out_words = ((size_t)bits_out * (((size_t)d.N + 31) / 32) + 1) * Pp;
+    if ((rc = launch_zero_words(out, out_words, s)) != APB_OK) return rc;
+    return launch_forward_requant(d, planes, pixsum, P, bits, step, &conv, scale, shift, bits_out, 1.0f / step_out, out, s);
 }
 
 int apb_forward_popcount(const apb_layer* layer, const void* packed, int M, int bits, float step, float* Y,

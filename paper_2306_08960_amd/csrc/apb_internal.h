@@ -85,14 +85,20 @@ int launch_zero_words(uint32_t* p, size_t count, hipStream_t s);
 // the popcount formulation on the vector ALU (Y, or D alone when D != nullptr)
 int launch_forward_popcount(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
                             float step, float* Y, int32_t* D, hipStream_t s);
-// the forward kernel: binary part on the matrix cores, residual part and epilogue, one launch
+// the forward kernel: binary part on the matrix cores, residual part and epilogue, one launch.
+// conv == nullptr: `planes` is the packed K x M matrix; otherwise a packed feature map of conv->C channels
+// (L.K = 9 * C, C a multiple of 64) with M = B * H * W pixels, read through an implicit im2col (3 x 3,
+// stride 1, padding 1).
+struct ConvShape {
+    int C, H, W;
+};
 int launch_forward(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
-                   float* Y, hipStream_t s);
+                   const ConvShape* conv, float* Y, hipStream_t s);
 // the same with the next layer's quantizer applied to scale[n] * Y + shift[n] (scale, shift nullable) and
 // the codes packed into `packed_out` (K = L.N, same M), which must have been zero-filled on `s`
 int launch_forward_requant(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
-                           const float* scale, const float* shift, int bits_out, float inv_step_out, uint32_t* packed_out,
-                           hipStream_t s);
+                           const ConvShape* conv, const float* scale, const float* shift, int bits_out,
+                           float inv_step_out, uint32_t* packed_out, hipStream_t s);
 
 // binary part alone on the matrix cores: the integer part D
 int launch_binary_mfma(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,

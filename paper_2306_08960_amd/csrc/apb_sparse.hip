@@ -49,7 +49,38 @@ struct SparseParams {
     int out_bits;                            // 0: float Y;  1 or 2: packed codes of the next layer
     int out_Kw;                              // ceil(N / 32), words per column of a packed output plane
     float out_inv_step;                      // 1 / step of the 2-bit output quantizer
+    // Implicit im2col (CONV kernels): the activations are a packed feature map [bits][Cw][Mp] (+ per-pixel
+    // code sums), a column m is the pixel (b, y, x) = (m / (H*W), (m / W) % H, m % W), and word row
+    // j = tap * Cw + cw of the patch matrix is word row cw of the map at the pixel shifted by tap
+    // (dy, dx) = (tap / 3 - 1, tap % 3 - 1), or zero outside the image.
+    int conv_Cw, conv_H, conv_W;
+    float conv_inv_Cw;
 };
+
+// Bit t of the result: tap t of pixel m lies inside the image (never for columns >= M).
+__device__ __forceinline__ uint32_t tap_mask(int m, const SparseParams& p) {
+    const int x = m % p.conv_W, y = (m / p.conv_W) % p.conv_H;
+    uint32_t vm = 0;
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+        const int yy = y + t / 3 - 1, xx = x + t % 3 - 1;
+        if (m < p.M && yy >= 0 && yy < p.conv_H && xx >= 0 && xx < p.conv_W) vm |= 1u << t;
+    }
+    return vm;
+}
+
+// Tap of word row j (exact for j * Cw < 2^22) and the pixel shift of a tap.
+__device__ __forceinline__ int tap_of_row(int j, const SparseParams& p) { return (int)(((float)j + 0.5f) * p.conv_inv_Cw); }
+__device__ __forceinline__ int tap_shift(int tap, int W) {
+    const int t3 = (tap * 11) >> 5;                              // tap / 3 for tap < 12
+    return (t3 - 1) * W + (tap - 3 * t3 - 1);
+}
+
+// A lane's byte offset into a row of the map for tap `tap`: its shifted pixel, or an offset beyond any
+// buffer range (a buffer load out of range returns zero: that is the zero padding).
+__device__ __forceinline__ int tap_offset(uint32_t vm, int tap, int m, int shift) {
+    return ((vm >> tap) & 1u) ? (m + shift) * 4 : (int)0x80000000u;
+}
 
 // Spread the 4 low bits of `nib` to the least significant bits of the 4 bytes of a word.
 __device__ __forceinline__ uint32_t spread4(uint32_t nib) { return (nib * 0x00204081u) & 0x01010101u; }
@@ -152,15 +183,24 @@ __device__ __forceinline__ void batch(v16d& acc, v8d& pairs, const uint32_t* __r
 // the pad word row past an odd Kw are zero).  The upper lane half of the last step of an odd Kw
 // reads one activation row past its plane -- still inside the packed buffer (the next plane, or the
 // column sums) and multiplied by zero weights.  Words are fetched four steps ahead.
-template <int BITS>
+// CONV: the activation words come from a packed feature map through the implicit im2col (see
+// SparseParams); vm is the tap mask of this lane's column m_base + 32*tm + (lane & 31).  Cw is even, so
+// the two word rows of a step belong to the same tap.
+template <int BITS, bool CONV>
 __device__ __forceinline__ void binary_tile_to_lds(const uint32_t* __restrict__ signT,
                                                    const uint32_t* __restrict__ planes, int Np, int Kw, int Mp,
                                                    int slot_base, int m_base, int tn, int tm, int s_begin, int s_end,
-                                                   int lane, int32_t* tile) {
+                                                   int lane, int32_t* tile, const SparseParams& p, uint32_t vm) {
     const int i = lane & 31, g = lane >> 5;
     const unsigned aoff = (unsigned)(g * Np + slot_base + 32 * tn + i);
     const unsigned boff = (unsigned)(g * Mp + m_base + 32 * tm + i);
-    const size_t plane_stride = (size_t)Kw * Mp;
+    const size_t plane_stride = (size_t)(CONV ? p.conv_Cw : Kw) * Mp;
+    // running (tap, word row of the map) of the next step to be loaded
+    int ld_tap = 0, ld_cw = 0;
+    if (CONV) {
+        ld_tap = tap_of_row(2 * s_begin, p);
+        ld_cw = 2 * s_begin - ld_tap * p.conv_Cw;
+    }
     const int steps = (Kw + 1) / 2;
     constexpr int kRing = 4;
     uint32_t aw[kRing][1][1], bw[kRing][BITS][1];
@@ -170,8 +210,26 @@ __device__ __forceinline__ void binary_tile_to_lds(const uint32_t* __restrict__ 
     auto load_words = [&](int st, uint32_t (&a)[1][1], uint32_t (&b)[BITS][1]) {
         const int ss = min(st, steps - 1);                      // past the end: harmless re-read, never used
         a[0][0] = (signT + (size_t)(2 * ss) * Np)[aoff];
+        if (!CONV) {
 #pragma unroll
-        for (int pl = 0; pl < BITS; ++pl) b[pl][0] = (planes + pl * plane_stride + (size_t)(2 * ss) * Mp)[boff];
+            for (int pl = 0; pl < BITS; ++pl) b[pl][0] = (planes + pl * plane_stride + (size_t)(2 * ss) * Mp)[boff];
+        } else {
+            // rows ld_cw (lower lane half) and ld_cw + 1 of the map, shifted by the tap; past the last
+            // step the tap runs past 8, whose mask bits are clear: zeros, never used
+            const int off = tap_offset(vm, ld_tap, (int)boff, tap_shift(ld_tap, p.conv_W));
+#pragma unroll
+            for (int pl = 0; pl < BITS; ++pl) {
+                const uint32_t* rows = planes + (pl * plane_stride + (size_t)ld_cw * Mp);
+                const __amdgpu_buffer_rsrc_t rsrc =
+                    __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(rows), 0, 2 * Mp * 4, kBufferFlags);
+                b[pl][0] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, off, 0, 0);
+            }
+            ld_cw += 2;
+            if (ld_cw >= p.conv_Cw) {
+                ld_cw = 0;
+                ++ld_tap;
+            }
+        }
     };
     v16f c;
 #pragma unroll
@@ -258,8 +316,46 @@ __device__ __forceinline__ void write_rows(const v16d& acc, int slot0, int m, co
                                __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Sum of the codes of column m: read as it stands, or (CONV) added up over the taps of the patch from
+// the per-pixel sums of the feature map.
+template <bool CONV>
+__device__ __forceinline__ int column_code_sum(const int32_t* __restrict__ colsum, int m, uint32_t vm,
+                                               const SparseParams& p) {
+    if (!CONV) return colsum[m];
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(colsum), 0, p.Mp * 4, kBufferFlags);
+    int cs = 0;
+#pragma unroll
+    for (int t = 0; t < 9; ++t)
+        cs += (int)__builtin_amdgcn_raw_buffer_load_b32(rsrc, tap_offset(vm, t, m, tap_shift(t, p.conv_W)), 0, 0);
+    return cs;
+}
+
+// Word row j of the activations for this lane's column (byte offset m_off = 4 * m), plane b: a buffer
+// load whose descriptor carries the wave-uniform row (range = one row of Mp words) and to which the
+// lane adds its 32-bit offset.  Rows past Kw re-read the last row (plain matrix) or return zero
+// (CONV: their tap has no mask bit); they are never expanded.  The load is unconditional and unmasked
+// so that the wait for it can sit at the next chunk.
+template <bool CONV>
+__device__ __forceinline__ uint32_t load_act_word(const uint32_t* __restrict__ planes, size_t plane_stride, int b, int j,
+                                                  int m_off, uint32_t vm, const SparseParams& p) {
+    if (!CONV) {
+        const uint32_t* row = planes + (b * plane_stride + (size_t)min(j, p.Kw - 1) * p.Mp);
+        const __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(row), 0, p.Mp * 4, kBufferFlags);
+        return __builtin_amdgcn_raw_buffer_load_b32(rsrc, m_off, 0, 0);
+    }
+    const int tap = tap_of_row(j, p);
+    const int cw = j - tap * p.conv_Cw;
+    const uint32_t* row = planes + (b * plane_stride + (size_t)cw * p.Mp);
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(row), 0, p.Mp * 4, kBufferFlags);
+    return __builtin_amdgcn_raw_buffer_load_b32(rsrc, tap_offset(vm, tap, m_off >> 2, tap_shift(tap, p.conv_W)), 0, 0);
+}
+
 // WPW = words of a chunk each wave expands = 8 / waves per workgroup.
-template <int BITS, int WPW>
+// CONV: 3x3 convolution over a packed feature map (implicit im2col, see SparseParams).
+template <int BITS, int WPW, bool CONV>
 __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_waves_per_eu(WPW <= 2 ? 8 : 4, 8))) void k_sparse_epilogue(
     // Separate restrict-qualified arguments (not struct members) so that the compiler knows the
     // read-only arrays cannot alias Y and keeps the wave-uniform loads on the scalar path.
@@ -290,6 +386,7 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
     const int m_off = m * 4;                                    // the launcher keeps 4 * Mp below 2^31
 
     static_assert(TN == 16, "row field of an entry key addresses 16 register pairs");
+    const uint32_t vm = CONV ? tap_mask(m, p) : 0u;
     v16d acc;
     {
         // Binary part first; every lane then picks up the 16 products of its column and starts its
@@ -297,14 +394,17 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
         // 1-bit activations, whose sum is doubled at the end).  The tile shares LDS with the code
         // tables, hence the second barrier.
         int32_t* tile_lds = reinterpret_cast<int32_t*>(lds);
-        binary_tile_to_lds<BITS>(signT, planes, p.Np, p.Kw, p.Mp, rg * waves * TN, strip * kWave, wave >> 1, wave & 1, 0,
-                                 (p.Kw + 1) / 2, lane, tile_lds);
+        // (the binary tile's column of a lane is column 32 * (wave & 1) + (lane & 31) of the strip: its mask
+        // is that lane's)
+        const uint32_t vm_tile = CONV ? (uint32_t)__shfl((int)vm, 32 * (wave & 1) + (lane & 31)) : 0u;
+        binary_tile_to_lds<BITS, CONV>(signT, planes, p.Np, p.Kw, p.Mp, rg * waves * TN, strip * kWave, wave >> 1, wave & 1,
+                                       0, (p.Kw + 1) / 2, lane, tile_lds, p, vm_tile);
         __syncthreads();
         int P[TN];
 #pragma unroll
         for (int r = 0; r < TN; ++r) P[r] = tile_lds[(wave * TN + r) * kWave + lane];
         __syncthreads();
-        const int cs = colsum[m];
+        const int cs = column_code_sum<CONV>(colsum, m, vm, p);
         const double a0 = p.alpha * (BITS == 1 ? 0.5 : 1.0) * (1.0 / kSumUnscale);
 #pragma unroll
         for (int r = 0; r < TN; ++r) {
@@ -317,7 +417,7 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
 #pragma unroll
     for (int r = 0; r < 8; ++r) pairs[r] = 0.0;
 
-    const size_t plane_stride = (size_t)p.Kw * p.Mp;
+    const size_t plane_stride = (size_t)(CONV ? p.conv_Cw : p.Kw) * p.Mp;
     uint8_t* my_row = lds + lane * kTablePitch;
     const uint32_t my_row_off = (uint32_t)(uintptr_t)(lds_u8*)my_row;   // the same row as an LDS byte address
     const int32_t* seg = seg_ptr + (size_t)tile * (p.nchunks + 1);
@@ -330,16 +430,7 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
         for (int i = 0; i < WPW; ++i) {
             const int j = c * kChunkWords + wave + i * waves;
 #pragma unroll
-            for (int b = 0; b < BITS; ++b) {
-                // Buffer load: the descriptor carries the wave-uniform row (scalar registers, range =
-                // one row of Mp words), the lane adds its 32-bit byte offset.  Words past Kw re-read
-                // the last row and are never expanded; leaving the load unconditional and unmasked
-                // keeps the wait for it at the next chunk.
-                const uint32_t* row = planes + (b * plane_stride + (size_t)min(j, p.Kw - 1) * p.Mp);
-                const __amdgpu_buffer_rsrc_t rsrc =
-                    __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(row), 0, p.Mp * 4, kBufferFlags);
-                xw[b][i] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, m_off, 0, 0);
-            }
+            for (int b = 0; b < BITS; ++b) xw[b][i] = load_act_word<CONV>(planes, plane_stride, b, j, m_off, vm, p);
         }
     };
     fetch(0);
@@ -385,7 +476,7 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
 // residual loop (part 0 starts its sums at alpha*D, the others at zero) and the partial float64 sums
 // meet in LDS after it, added in a fixed order by part 0, which writes Y.  All waves run the same
 // number of barriers whatever their run lengths.
-template <int BITS, int KS>
+template <int BITS, int KS, bool CONV>
 __global__ __launch_bounds__(kWave* kChunkWords) __attribute__((amdgpu_waves_per_eu(4, 8))) void k_forward_ksplit(
     const uint32_t* __restrict__ planes, const int32_t* __restrict__ colsum, const int32_t* __restrict__ rowsum,
     const int32_t* __restrict__ perm, const int32_t* __restrict__ seg_ptr, const uint32_t* __restrict__ ent,
@@ -406,6 +497,7 @@ __global__ __launch_bounds__(kWave* kChunkWords) __attribute__((amdgpu_waves_per
     const int m = strip * kWave + lane;
     const int m_off = m * 4;
     const int H = (p.nchunks + KS - 1) / KS;
+    const uint32_t vm = CONV ? tap_mask(m, p) : 0u;
 
     // binary part: wave (tl, kp) computes 32 x 32 tile tl of the workgroup's 16*TW x 64 block over
     // its share of the K steps
@@ -414,8 +506,9 @@ __global__ __launch_bounds__(kWave* kChunkWords) __attribute__((amdgpu_waves_per
         const int steps = (p.Kw + 1) / 2;
         const int SP = (steps + KS - 1) / KS;
         const int s_begin = min(steps, kp * SP), s_end = min(steps, s_begin + SP);
-        binary_tile_to_lds<BITS>(signT, planes, p.Np, p.Kw, p.Mp, rg * TW * TN, strip * kWave, tl >> 1, tl & 1, s_begin,
-                                 s_end, lane, part_lds + kp * (TN * TW * kWave));
+        const uint32_t vm_tile = CONV ? (uint32_t)__shfl((int)vm, 32 * (tl & 1) + (lane & 31)) : 0u;
+        binary_tile_to_lds<BITS, CONV>(signT, planes, p.Np, p.Kw, p.Mp, rg * TW * TN, strip * kWave, tl >> 1, tl & 1,
+                                       s_begin, s_end, lane, part_lds + kp * (TN * TW * kWave), p, vm_tile);
     }
     __syncthreads();
     v16d acc;
@@ -427,7 +520,7 @@ __global__ __launch_bounds__(kWave* kChunkWords) __attribute__((amdgpu_waves_per
 #pragma unroll
             for (int q = 0; q < KS; ++q) P[r] += part_lds[q * (TN * TW * kWave) + (tl * TN + r) * kWave + lane];
         }
-        const int cs = colsum[m];
+        const int cs = column_code_sum<CONV>(colsum, m, vm, p);
         const double a0 = p.alpha * (BITS == 1 ? 0.5 : 1.0) * (1.0 / kSumUnscale);
 #pragma unroll
         for (int r = 0; r < TN; ++r) {
@@ -444,7 +537,7 @@ __global__ __launch_bounds__(kWave* kChunkWords) __attribute__((amdgpu_waves_per
     for (int r = 0; r < 8; ++r) pairs[r] = 0.0;
     __syncthreads();                                            // the partial products are read; tables may overwrite them
 
-    const size_t plane_stride = (size_t)p.Kw * p.Mp;
+    const size_t plane_stride = (size_t)(CONV ? p.conv_Cw : p.Kw) * p.Mp;
     uint8_t* my_row = lds + lane * kTablePitch;
     const uint32_t my_row_off = (uint32_t)(uintptr_t)(lds_u8*)my_row;
     const int32_t* seg = seg_ptr + (size_t)tile * (p.nchunks + 1);
@@ -456,12 +549,7 @@ __global__ __launch_bounds__(kWave* kChunkWords) __attribute__((amdgpu_waves_per
         for (int q = 0; q < KS; ++q) {
             const int j = (q * H + i) * kChunkWords + wave;
 #pragma unroll
-            for (int b = 0; b < BITS; ++b) {
-                const uint32_t* row = planes + (b * plane_stride + (size_t)min(j, p.Kw - 1) * p.Mp);
-                const __amdgpu_buffer_rsrc_t rsrc =
-                    __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(row), 0, p.Mp * 4, kBufferFlags);
-                xw[b][q] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, m_off, 0, 0);
-            }
+            for (int b = 0; b < BITS; ++b) xw[b][q] = load_act_word<CONV>(planes, plane_stride, b, j, m_off, vm, p);
         }
     };
     fetch(0);
@@ -520,7 +608,7 @@ struct OutArgs {
     float* out;
 };
 
-template <int BITS, int KS>
+template <int BITS, int KS, bool CONV>
 int launch_ksplit(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, const OutArgs& o, SparseParams p,
                   hipStream_t s) {
     constexpr int TW = kChunkWords / KS;
@@ -530,35 +618,38 @@ int launch_ksplit(const LayerDev& L, const uint32_t* planes, const int32_t* cols
     if (blocks > 0x7fffffffLL) return APB_ERR_SHAPE;
     p.blocks = (int)blocks;
     if (kLds > 64 * 1024)                                       // more LDS than a launch gets without asking
-        APB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_forward_ksplit<BITS, KS>),
+        APB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_forward_ksplit<BITS, KS, CONV>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
-    hipLaunchKernelGGL((k_forward_ksplit<BITS, KS>), dim3((unsigned)p.blocks), dim3(kWave * kChunkWords), kLds, s, planes,
-                       colsum, L.rowsum, L.perm, L.seg_ptr, L.ent, L.slot_valsum, L.signT, o.scale, o.shift, o.out, p);
+    hipLaunchKernelGGL((k_forward_ksplit<BITS, KS, CONV>), dim3((unsigned)p.blocks), dim3(kWave * kChunkWords), kLds, s,
+                       planes, colsum, L.rowsum, L.perm, L.seg_ptr, L.ent, L.slot_valsum, L.signT, o.scale, o.shift, o.out,
+                       p);
     return APB_OK;
 }
 
-template <int BITS, int WPW>
+template <int BITS, int WPW, bool CONV>
 void launch_one(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, const OutArgs& o, const SparseParams& p,
                 hipStream_t s) {
-    hipLaunchKernelGGL((k_sparse_epilogue<BITS, WPW>), dim3((unsigned)p.blocks), dim3(kWave * kChunkWords / WPW),
+    hipLaunchKernelGGL((k_sparse_epilogue<BITS, WPW, CONV>), dim3((unsigned)p.blocks), dim3(kWave * kChunkWords / WPW),
                        table_buffers(WPW) * kTableBytes, s, planes, colsum, L.rowsum, L.perm, L.seg_ptr, L.ent,
                        L.slot_valsum, L.signT, o.scale, o.shift, o.out, p);
 }
 
-template <int BITS>
+template <int BITS, bool CONV>
 int launch_bits(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, const OutArgs& o, const SparseParams& p,
-                hipStream_t s) {
+                int ks, hipStream_t s) {
+    if (ks == 2) return launch_ksplit<BITS, 2, CONV>(L, planes, colsum, o, p, s);
+    if (ks == 4) return launch_ksplit<BITS, 4, CONV>(L, planes, colsum, o, p, s);
     switch (L.waves) {
-        case 8: launch_one<BITS, 1>(L, planes, colsum, o, p, s); break;
-        case 4: launch_one<BITS, 2>(L, planes, colsum, o, p, s); break;
-        case 2: launch_one<BITS, 4>(L, planes, colsum, o, p, s); break;
+        case 8: launch_one<BITS, 1, CONV>(L, planes, colsum, o, p, s); break;
+        case 4: launch_one<BITS, 2, CONV>(L, planes, colsum, o, p, s); break;
+        case 2: launch_one<BITS, 4, CONV>(L, planes, colsum, o, p, s); break;
         default: return APB_ERR_SHAPE;
     }
     return APB_OK;
 }
 
 int launch_any(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
-               const OutArgs& o, int out_bits, float out_inv_step, hipStream_t s) {
+               const ConvShape* conv, const OutArgs& o, int out_bits, float out_inv_step, hipStream_t s) {
     const int Mp = kWave * ((M + kWave - 1) / kWave);
     SparseParams p;
     p.alpha = (double)L.alpha;
@@ -571,11 +662,14 @@ int launch_any(const LayerDev& L, const uint32_t* planes, const int32_t* colsum,
     p.out_bits = out_bits;
     p.out_Kw = (L.N + 31) / 32;
     p.out_inv_step = out_inv_step;
+    p.conv_Cw = conv ? conv->C / 32 : 0;
+    p.conv_H = conv ? conv->H : 0;
+    p.conv_W = conv ? conv->W : 0;
+    p.conv_inv_Cw = conv ? 1.0f / (float)(conv->C / 32) : 0.0f;
     p.row_groups = L.Np / (TN * L.waves);
     const long long blocks = (long long)p.row_groups * (Mp / kWave);
-    if (blocks > 0x7fffffffLL || (long long)Mp * 4 >= (1LL << 31)) return APB_ERR_SHAPE;
+    if (blocks > 0x7fffffffLL || (long long)Mp * 8 >= (1LL << 31)) return APB_ERR_SHAPE;
     p.blocks = (int)blocks;
-    int rc;
     // Launches of 8-wave workgroups that would put fewer than ~3000 waves on the chip split K two or
     // four ways inside the workgroup instead (see k_forward_ksplit).
     int ks = 1;
@@ -583,9 +677,9 @@ int launch_any(const LayerDev& L, const uint32_t* planes, const int32_t* colsum,
         if (blocks * 8 < 3000 && L.nchunks >= 2) ks = 2;
         if (blocks * 16 < 3000 && L.nchunks >= 4) ks = 4;
     }
-    if (ks == 2) rc = bits == 1 ? launch_ksplit<1, 2>(L, planes, colsum, o, p, s) : launch_ksplit<2, 2>(L, planes, colsum, o, p, s);
-    else if (ks == 4) rc = bits == 1 ? launch_ksplit<1, 4>(L, planes, colsum, o, p, s) : launch_ksplit<2, 4>(L, planes, colsum, o, p, s);
-    else rc = bits == 1 ? launch_bits<1>(L, planes, colsum, o, p, s) : launch_bits<2>(L, planes, colsum, o, p, s);
+    int rc;
+    if (conv) rc = bits == 1 ? launch_bits<1, true>(L, planes, colsum, o, p, ks, s) : launch_bits<2, true>(L, planes, colsum, o, p, ks, s);
+    else rc = bits == 1 ? launch_bits<1, false>(L, planes, colsum, o, p, ks, s) : launch_bits<2, false>(L, planes, colsum, o, p, ks, s);
     if (rc != APB_OK) return rc;
     APB_HIP(hipGetLastError());
     return APB_OK;
@@ -593,16 +687,18 @@ int launch_any(const LayerDev& L, const uint32_t* planes, const int32_t* colsum,
 
 }  // namespace
 
+// conv == nullptr: `planes` is the packed K x M matrix.  Otherwise it is a packed feature map of conv->C
+// channels (L.K = 9 * C, C a multiple of 64) and M = B * H * W pixels, read through the implicit im2col.
 int launch_forward(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
-                   float* Y, hipStream_t s) {
-    return launch_any(L, planes, colsum, M, bits, step, OutArgs{nullptr, nullptr, Y}, 0, 0.0f, s);
+                   const ConvShape* conv, float* Y, hipStream_t s) {
+    return launch_any(L, planes, colsum, M, bits, step, conv, OutArgs{nullptr, nullptr, Y}, 0, 0.0f, s);
 }
 
 // packed_out: the next layer's packed activation buffer (K = L.N), zero-filled on `s` before this launch.
 int launch_forward_requant(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
-                           const float* scale, const float* shift, int bits_out, float inv_step_out, uint32_t* packed_out,
-                           hipStream_t s) {
-    return launch_any(L, planes, colsum, M, bits, step, OutArgs{scale, shift, reinterpret_cast<float*>(packed_out)},
+                           const ConvShape* conv, const float* scale, const float* shift, int bits_out,
+                           float inv_step_out, uint32_t* packed_out, hipStream_t s) {
+    return launch_any(L, planes, colsum, M, bits, step, conv, OutArgs{scale, shift, reinterpret_cast<float*>(packed_out)},
                       bits_out, inv_step_out, s);
 }
 

@@ -18,10 +18,10 @@ import torch
 from oracle import apb_oracle as o
 from oracle import capi
 from paper_2306_08960_amd import synth
+from requant_checks import REL_TOL, compare_codes, unpack
 
 pytestmark = pytest.mark.gpu
 
-REL_TOL = 1e-5
 THREADS = max(1, min(16, len(os.sched_getaffinity(0))))
 
 
@@ -31,21 +31,6 @@ def b():
     from paper_2306_08960_amd import binding
     binding.load()
     return binding
-
-
-def unpack(words: np.ndarray, K: int, M: int, bits: int):
-    """codes [K, M] and colsum [Mp] out of a packed buffer; asserts that the padding is zero."""
-    Kw, Mp = (K + 31) // 32, 64 * ((M + 63) // 64)
-    assert words.size == Mp * (bits * Kw + 1)
-    planes = words[: bits * Kw * Mp].reshape(bits, Kw, Mp)
-    colsum = words[bits * Kw * Mp:].view(np.int32)
-    assert not planes[:, :, M:].any() and not colsum[M:].any()
-    code = np.zeros((Kw * 32, M), dtype=np.int32)
-    for pl in range(bits):
-        for i in range(32):
-            code[i::32] += (((planes[pl, :, :M] >> np.uint32(i)) & 1) << pl).astype(np.int32)
-    assert not code[K:].any()
-    return code[:K], colsum
 
 
 def check_requant(b, W, delta, X, bits, step, bits_out, step_out, affine, tag="", W2=None, delta2=None):
@@ -74,24 +59,8 @@ def check_requant(b, W, delta, X, bits, step, bits_out, step_out, affine, tag=""
     code, colsum = unpack(got_words, N, M, bits_out)
     assert np.array_equal(colsum[:M], code.sum(axis=0)), "column sums of the codes written"
 
-    want = o.codes_of(ref["c"], bits_out).astype(np.int32)
-    diff = code != want
-    if diff.any():
-        # admissible only next to a decision boundary of the quantizer
-        a_s = np.float64(np.float32(L["alpha"])) * np.float64(np.float32(step))
-        mag = np.abs(a_s * F["D"]) + np.abs(F["R"])
-        if scale is not None:
-            mag = np.abs(scale.astype(np.float64))[:, None] * mag + np.abs(shift.astype(np.float64))[:, None]
-        Z = ref["Z"].astype(np.float64)
-        if bits_out == 1:
-            dist = np.abs(Z)
-        else:
-            lvl = Z / np.float64(np.float32(step_out))
-            dist = np.abs(lvl - np.floor(lvl) - 0.5) * np.float64(np.float32(step_out))
-        assert np.all(dist[diff] <= REL_TOL * mag[diff]), f"{int(diff.sum())} codes differ away from any boundary"
-        assert np.abs(code - want)[diff].max() == 1
-        assert diff.mean() < 1e-3
-    else:
+    n_diff = compare_codes(code, ref, L["alpha"], step, F["D"], F["R"], bits_out, step_out, scale, shift)
+    if n_diff == 0:
         assert np.array_equal(got_words, ref["packed"])
 
     if W2 is not None:
@@ -105,7 +74,7 @@ def check_requant(b, W, delta, X, bits, step, bits_out, step_out, affine, tag=""
         assert np.all(err <= REL_TOL * np.abs(F2["Y"].astype(np.float64)))
         layer2.free()
     layer.free()
-    return int(diff.sum())
+    return n_diff
 
 
 EDGE = [(1, 1, 1), (5, 33, 3), (16, 64, 64), (17, 100, 65), (33, 257, 130), (64, 300, 70), (70, 520, 129),

@@ -476,3 +476,34 @@ def test_two_layer_chain_equals_the_dense_definition():
     assert np.array_equal(hop["c"], c2)
     want = o.apb_dense(W2, d2, L2["alpha"]) @ (c2 * np.float64(s2))
     assert np.allclose(Y2, want, rtol=1e-6, atol=1e-9)
+
+
+# --------------------------------------------------------------------------- convolution as a product
+@pytest.mark.parametrize("bits", [1, 2])
+def test_im2col_forward_is_the_direct_convolution(bits):
+    """forward on im2col_codes == the textbook 3x3 cross-correlation (scipy) of the dequantized map with
+    the reconstructed weights, padded with the value of code 0."""
+    from scipy.signal import correlate2d
+    r = np.random.default_rng(31 + bits)
+    N, C, B, H, W = 3, 4, 2, 5, 6
+    Wt = (r.standard_normal((N, 9 * C)) * 0.05).astype(np.float32)
+    delta = np.float32(0.08)
+    step = np.float32(0.75 if bits == 2 else 0.5)
+    Xmap = r.standard_normal((C, B * H * W)).astype(np.float32)
+    if bits == 2:
+        Xmap = np.maximum(Xmap, 0)
+    L = o.compress(Wt, delta)
+    assert 0 < int(L["row_ptr"][-1]) < N * 9 * C
+    c_map = o.quantize(Xmap, bits, step)
+    patches = o.im2col_codes(c_map, B, H, W, bits)
+    assert patches.shape == (9 * C, B * H * W)
+    assert np.array_equal(patches[4 * C:5 * C], c_map)                  # the centre tap is the map itself
+    Y = o.forward(L, patches, step)["Y"].reshape(N, B, H, W)
+    dense = o.apb_dense(Wt, delta, L["alpha"]).reshape(N, 3, 3, C)      # [n][ky][kx][c]
+    xhat = o.dequantize(c_map, step).reshape(C, B, H, W)
+    fill = 0.0 if bits == 2 else -float(step)
+    for n in range(N):
+        for b_ in range(B):
+            want = sum(correlate2d(xhat[ch, b_], dense[n, :, :, ch], mode="same", boundary="fill", fillvalue=fill)
+                       for ch in range(C))
+            assert np.allclose(Y[n, b_], want, rtol=1e-6, atol=1e-9)
