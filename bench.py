@@ -47,7 +47,7 @@ def parse_args():
     ap.add_argument("--sweep", action="store_true",
                     help="square-matrix sweep of the three bitwise products (1/1, 1/2, 2/2; Sec. V protocol): one JSON "
                          "line with the time of the product alone at each size")
-    ap.add_argument("--routine", default="apb", choices=["apb", "gemm_2_2", "chain"],
+    ap.add_argument("--routine", default="apb", choices=["apb", "gemm_2_2", "chain", "conv_chain"],
                     help="apb: the APB layer forward (the headline metric); gemm_2_2: the 2-bit x 2-bit "
                          "product of Sec. IV on the same shapes (weights packed offline)")
     return ap.parse_args()
@@ -303,6 +303,108 @@ def run_chain(name, steps, warmup):
     return res, (cfg, W, delta, X, step, bits_out, step_out)
 
 
+# (batch, height, width) of the feature maps behind the benchmark's convolution layers (M = B*H*W, K = 9*C)
+CONV_GEOMETRY = {"C2": (128, 32, 32), "C4": (64, 28, 28), "C5b": (256, 7, 7)} | {
+    f"C3_r{r}_b{b_}": (128, 8, 8) for r in ("05", "20", "50") for b_ in (1, 2)}
+
+
+def run_conv_chain(name, steps, warmup):
+    """A 3x3 convolution layer in the middle of a network: packed feature map in, packed feature map out
+    (apb_forward_conv3x3_requant; implicit im2col, no float activations in memory).  Beside it: the same
+    layer as the benchmark's headline step runs it (apb_quantize_acts on the explicit float im2col matrix +
+    apb_forward), and the convolution with a float output."""
+    import torch
+    from paper_2306_08960_amd import binding as b
+    from paper_2306_08960_amd import synth
+
+    cfg = synth.CONFIGS[name]
+    B, H, W_ = CONV_GEOMETRY[name]
+    Wt, delta = synth.make_weights(cfg)
+    N, K, M, bits = cfg.N, cfg.K, cfg.M, cfg.bits
+    C = K // 9
+    assert M == B * H * W_ and K == 9 * C
+    layer = b.apb_compress(torch.from_numpy(Wt).cuda(), float(delta))
+    nnz = layer.info()["nnz"]
+    g = torch.Generator(device="cuda").manual_seed(synth.BASE_SEED + cfg.index)
+    Xmap = torch.randn((C, M), generator=g, device="cuda", dtype=torch.float32)
+    if bits == 2:
+        Xmap.clamp_(min=0)
+    s = float(cfg.step)
+    fmap = b.apb_quantize_acts(Xmap, bits, s)
+    bits_out = bits
+    step_out = float(0.03 * np.sqrt(K)) if bits_out == 2 else 1.0
+    fmap_out = b.alloc_packed(N, M, bits_out)
+    Y = torch.empty((N, M), dtype=torch.float32, device="cuda")
+    # the explicit route's input: the float im2col matrix [K, M]
+    pad = torch.full((C, B, H + 2, W_ + 2), 0.0 if bits == 2 else -1.0, device="cuda")
+    pad[:, :, 1:H + 1, 1:W_ + 1] = Xmap.view(C, B, H, W_)
+    X = torch.cat([pad[:, :, ky:ky + H, kx:kx + W_].reshape(C, M) for ky in range(3) for kx in range(3)], dim=0)
+    del pad
+    packed = b.alloc_packed(K, M, bits)
+
+    def chained():
+        b.apb_forward_conv3x3_requant(layer, fmap, B, H, W_, bits, s, bits_out, step_out, fmap_out=fmap_out)
+
+    def conv_float():
+        b.apb_forward_conv3x3(layer, fmap, B, H, W_, bits, s, Y=Y)
+
+    def explicit():
+        b.apb_quantize_acts(X, bits, s, packed=packed)
+        b.apb_forward(layer, packed, M, bits, s, Y=Y)
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    ms_chain, ms_float, ms_explicit = timed(chained), timed(conv_float), timed(explicit)
+    Y_conv = Y.clone()
+    conv_float()
+    same = bool(torch.equal(Y, Y_conv))                      # explicit and implicit routes, bit for bit
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for a, c in ev:
+        a.record()
+        chained()
+        c.record()
+    torch.cuda.synchronize()
+    per_record = max(0.0, ((time.perf_counter() - t0) * 1e3 / steps - ms_chain) / 2.0)
+    ms_call = sum(a.elapsed_time(c) for a, c in ev) / steps - per_record
+    ops = 2.0 * N * K * M + 2.0 * nnz * M
+    Kw, Mp, Cw, Nw = (K + 31) // 32, 64 * ((M + 63) // 64), C // 32, (N + 31) // 32
+    out_bytes = 4.0 * (bits_out * Nw + 1) * Mp
+    # sign words, the packed map (read once from HBM; its nine shifted views hit in cache), residual entries;
+    # the packed output is zero-filled, then read-modify-written
+    fwd_bytes = 4.0 * N * Kw + 4.0 * (bits * Cw + 1) * Mp + 12.0 * nnz + 3.0 * out_bytes
+    t_hbm = fwd_bytes / (HBM_PEAK_GBS * 1e9)
+    t_mfma = 2.0 * N * K * M / (MFMA_FP4_PEAK_TFLOPS * 1e12)
+    t_f64 = 2.0 * nnz * M / (FP64_VECTOR_PEAK_TFLOPS * 1e12)
+    t = ms_call * 1e-3
+    if t_hbm >= max(t_mfma, t_f64):
+        roof = {"bound": "hbm", "achieved": fwd_bytes / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    elif t_mfma >= t_f64:
+        roof = {"bound": "mfma", "achieved": 2.0 * N * K * M / t / 1e12, "peak": MFMA_FP4_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    else:
+        roof = {"bound": "alu", "achieved": 2.0 * nnz * M / t / 1e12, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    roof = {"kernel": "forward kernel, implicit im2col + packed-output epilogue (+ zero fill)"} | roof
+    roof |= {"frac": roof["achieved"] / roof["peak"], "traffic": None, "ms": ms_call,
+             "floor_us": {"hbm": t_hbm * 1e6, "mfma_fp4": t_mfma * 1e6, "fp64_vector": t_f64 * 1e6}}
+    t_valu = (2.0 * bits * N * Kw * M + float(nnz) * M) / VALU_LANE_OPS_PER_S
+    res = {"workload": name, "N": N, "C": C, "B": B, "H": H, "W": W_, "act_bits": bits, "nnz": int(nnz),
+           "ms_per_step": ms_chain, "gops_step": ops / (ms_chain * 1e-3) / 1e9,
+           "ms_conv_float_output": ms_float, "ms_explicit_im2col_quantize_plus_forward": ms_explicit,
+           "implicit_equals_explicit_bitwise": same, "roofline": roof, "bits_out": bits_out, "step_out": step_out,
+           "frac_of_valu_bitop_roof": t_valu / t}
+    layer.free()
+    return res, cfg
+
+
 def cpu_baseline_chain(cfg, W, delta, X, step, bits_out, step_out):
     """The CPU oracle of the chained step (forward from packed codes, re-quantize, pack) on the first columns."""
     from oracle import apb_oracle as o
@@ -454,6 +556,25 @@ def main():
         print(json.dumps(out))
         return
 
+    if args.routine == "conv_chain":
+        if args.workload not in CONV_GEOMETRY:
+            print(f"bench.py: {args.workload} is not a convolution layer; choose from {sorted(CONV_GEOMETRY)}", file=sys.stderr)
+            sys.exit(2)
+        res, cfg = run_conv_chain(args.workload, args.steps, args.warmup)
+        print(json.dumps({
+            "metric": "APB 3x3 conv layer GOPS, chained (packed feature map in, packed feature map out)",
+            "value": res["gops_step"], "unit": "GOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "fp4 (exact 0/1 and 2-bit codes) on MFMA + f64 accumulate, packed codes in/out", "data": "synthetic",
+            "config": {"workload": f"{cfg.name}: {cfg.note}", "N": res["N"], "C": res["C"], "B": res["B"], "H": res["H"],
+                       "W": res["W"], "act_bits": cfg.bits, "outlier_rate": cfg.rho, "nnz": res["nnz"],
+                       "bits_out": res["bits_out"], "step_out": res["step_out"],
+                       "step": "apb_forward_conv3x3_requant, packed input map resident in HBM"},
+            "ms_conv_float_output": res["ms_conv_float_output"],
+            "ms_explicit_im2col_quantize_plus_forward": res["ms_explicit_im2col_quantize_plus_forward"],
+            "implicit_equals_explicit_bitwise": res["implicit_equals_explicit_bitwise"],
+            "frac_of_valu_bitop_roof": res["frac_of_valu_bitop_roof"], "roofline": res["roofline"]}))
+        return
     if args.routine == "chain":
         res, inputs = run_chain(args.workload, args.steps, args.warmup)
         cfg = inputs[0]
