@@ -281,8 +281,9 @@ def run_chain(name, steps, warmup):
     ops = 2.0 * N * K * M + 2.0 * nnz * M
     Kw, Mp, Nw = (K + 31) // 32, 64 * ((M + 63) // 64), (N + 31) // 32
     out_bytes = 4.0 * (bits_out * Nw + 1) * Mp
-    # sign words, bit-planes, residual entries in; the packed output is zero-filled, then read-modify-written
-    fwd_bytes = 4.0 * N * Kw + 4.0 * bits * Kw * Mp + 4.0 * Mp + 12.0 * nnz + 3.0 * out_bytes
+    # sign words, bit-planes, residual entries in; the packed output is stored once (layers of at most 128 rows)
+    # or zero-filled, then read-modify-written
+    fwd_bytes = 4.0 * N * Kw + 4.0 * bits * Kw * Mp + 4.0 * Mp + 12.0 * nnz + (1.0 if N <= 128 else 3.0) * out_bytes
     t_hbm = fwd_bytes / (HBM_PEAK_GBS * 1e9)
     t_mfma = 2.0 * N * K * M / (MFMA_FP4_PEAK_TFLOPS * 1e12)
     t_f64 = 2.0 * nnz * M / (FP64_VECTOR_PEAK_TFLOPS * 1e12)
@@ -380,8 +381,8 @@ def run_conv_chain(name, steps, warmup):
     Kw, Mp, Cw, Nw = (K + 31) // 32, 64 * ((M + 63) // 64), C // 32, (N + 31) // 32
     out_bytes = 4.0 * (bits_out * Nw + 1) * Mp
     # sign words, the packed map (read once from HBM; its nine shifted views hit in cache), residual entries;
-    # the packed output is zero-filled, then read-modify-written
-    fwd_bytes = 4.0 * N * Kw + 4.0 * (bits * Cw + 1) * Mp + 12.0 * nnz + 3.0 * out_bytes
+    # the packed output is stored once (layers of at most 128 rows) or zero-filled, then read-modify-written
+    fwd_bytes = 4.0 * N * Kw + 4.0 * (bits * Cw + 1) * Mp + 12.0 * nnz + (1.0 if N <= 128 else 3.0) * out_bytes
     t_hbm = fwd_bytes / (HBM_PEAK_GBS * 1e9)
     t_mfma = 2.0 * N * K * M / (MFMA_FP4_PEAK_TFLOPS * 1e12)
     t_f64 = 2.0 * nnz * M / (FP64_VECTOR_PEAK_TFLOPS * 1e12)

@@ -350,9 +350,6 @@ int apb_forward_requant(const apb_layer* layer, const void* packed, int M, int b
     const int32_t* colsum = reinterpret_cast<const int32_t*>(planes + (size_t)bits * d.Kw * Mp);
     hipStream_t s = as_stream(stream);
     uint32_t* out = static_cast<uint32_t*>(packed_out);
-    const size_t out_words = ((size_t)bits_out * (((size_t)d.N + 31) / 32) + 1) * Mp;     // planes + colsum
-    const int rc = launch_zero_words(out, out_words, s);
-    if (rc != APB_OK) return rc;
     return launch_forward_requant(d, planes, colsum, M, bits, step, nullptr, scale, shift, bits_out, 1.0f / step_out, out, s);
 }
 
@@ -399,8 +396,6 @@ int apb_forward_conv3x3_requant(const apb_layer* layer, const void* fmap, int B,
     const int32_t* pixsum = reinterpret_cast<const int32_t*>(planes + (size_t)bits * (conv.C / 32) * Pp);
     hipStream_t s = as_stream(stream);
     uint32_t* out = static_cast<uint32_t*>(fmap_out);
-    const size_t out_words = ((size_t)bits_out * (((size_t)d.N + 31) / 32) + 1) * Pp;
-    if ((rc = launch_zero_words(out, out_words, s)) != APB_OK) return rc;
     return launch_forward_requant(d, planes, pixsum, P, bits, step, &conv, scale, shift, bits_out, 1.0f / step_out, out, s);
 }
 

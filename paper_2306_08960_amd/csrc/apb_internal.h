@@ -95,7 +95,7 @@ struct ConvShape {
 int launch_forward(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                    const ConvShape* conv, float* Y, hipStream_t s);
 // the same with the next layer's quantizer applied to scale[n] * Y + shift[n] (scale, shift nullable) and
-// the codes packed into `packed_out` (K = L.N, same M), which must have been zero-filled on `s`
+// the codes packed into `packed_out` (K = L.N, same M), fully overwritten
 int launch_forward_requant(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                            const ConvShape* conv, const float* scale, const float* shift, int bits_out,
                            float inv_step_out, uint32_t* packed_out, hipStream_t s);

@@ -47,6 +47,7 @@ struct SparseParams {
     int row_groups;                          // Np / (TN * waves)
     int blocks;                              // row_groups * strips
     int out_bits;                            // 0: float Y;  1 or 2: packed codes of the next layer
+    int out_exclusive;                       // packed output: the workgroup holds ALL rows of its columns
     int out_Kw;                              // ceil(N / 32), words per column of a packed output plane
     float out_inv_step;                      // 1 / step of the 2-bit output quantizer
     // Implicit im2col (CONV kernels): the activations are a packed feature map [bits][Cw][Mp] (+ per-pixel
@@ -267,10 +268,15 @@ __device__ __forceinline__ void binary_tile_to_lds(const uint32_t* __restrict__ 
 //   rows of a tile are ascending, so the bits of rows that share a word are gathered in registers
 //   and leave as one atomic; rows of other tiles and workgroups add theirs to the same words, in any
 //   order (integer OR and add commute).
+//   out_exclusive (layers of at most 128 rows in the plain kernel: one workgroup holds every row of its
+//   64 columns): the waves meet in LDS instead (`gather`, at most 2 * 4 + 1 rows of 64 words; every wave
+//   of the workgroup must make this call) and the finished words and column sums leave as plain,
+//   coalesced stores, so the buffer needs no zero fill.
 template <int BITS>
 __device__ __forceinline__ void write_rows(const v16d& acc, int slot0, int m, const int32_t* __restrict__ perm,
                                            const double* __restrict__ slot_valsum, const float* __restrict__ scale,
-                                           const float* __restrict__ shift, float* out, const SparseParams& p) {
+                                           const float* __restrict__ shift, float* out, const SparseParams& p,
+                                           uint32_t* gather = nullptr) {
     const bool col_ok = m < p.M;
     int n[TN];
     double y[TN];
@@ -290,6 +296,14 @@ __device__ __forceinline__ void write_rows(const v16d& acc, int slot0, int m, co
     }
     uint32_t* words = reinterpret_cast<uint32_t*>(out);
     const size_t plane = (size_t)p.out_Kw * p.Mp;
+    const bool excl = gather != nullptr && p.out_exclusive;
+    const int lane = m & (kWave - 1);
+    const int gather_rows = p.out_bits * p.out_Kw + 1;          // word rows of both planes, then the column sums
+    if (excl) {
+        __syncthreads();                                        // every wave is done with the code tables
+        for (int i = threadIdx.x; i < gather_rows * kWave; i += blockDim.x) gather[i] = 0u;
+        __syncthreads();
+    }
     uint32_t w0 = 0, w1 = 0;
     int total = 0;
 #pragma unroll
@@ -305,15 +319,33 @@ __device__ __forceinline__ void write_rows(const v16d& acc, int slot0, int m, co
         total += (int)code;
         const bool last_of_word = r == TN - 1 || n[r + 1] < 0 || (n[r + 1] >> 5) != (n[r] >> 5);
         if (last_of_word) {
-            const size_t at = (size_t)(n[r] >> 5) * p.Mp + m;
-            if (w0) __hip_atomic_fetch_or(words + at, w0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (w1) __hip_atomic_fetch_or(words + plane + at, w1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (excl) {
+                uint32_t* at = gather + (n[r] >> 5) * kWave + lane;
+                if (w0) __hip_atomic_fetch_or(at, w0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                if (w1) __hip_atomic_fetch_or(at + p.out_Kw * kWave, w1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            } else {
+                const size_t at = (size_t)(n[r] >> 5) * p.Mp + m;
+                if (w0) __hip_atomic_fetch_or(words + at, w0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (w1) __hip_atomic_fetch_or(words + plane + at, w1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
             w0 = w1 = 0;
         }
     }
+    if (!excl) {
+        if (total)
+            __hip_atomic_fetch_add(reinterpret_cast<int32_t*>(words + p.out_bits * plane) + m, total, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
     if (total)
-        __hip_atomic_fetch_add(reinterpret_cast<int32_t*>(words + p.out_bits * plane) + m, total, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(gather + (gather_rows - 1) * kWave + lane, (uint32_t)total, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_WORKGROUP);
+    __syncthreads();
+    // row i of `gather` is word row i of the packed output (planes one after the other, then the sums),
+    // columns of this workgroup's strip
+    const int m0 = m - lane;
+    for (int i = threadIdx.x; i < gather_rows * kWave; i += blockDim.x)
+        words[(size_t)(i / kWave) * p.Mp + m0 + (i & (kWave - 1))] = gather[i];
 }
 
 // Sum of the codes of column m: read as it stands, or (CONV) added up over the taps of the patch from
@@ -464,7 +496,7 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
     // (The column is recomputed from the lane number here rather than kept in a register -- or
     // spilled -- through the loops above.)
     const int m_e = strip * kWave + (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
-    write_rows<BITS>(acc, slot0, m_e, perm, slot_valsum, scale, shift, out, p);
+    write_rows<BITS>(acc, slot0, m_e, perm, slot_valsum, scale, shift, out, p, reinterpret_cast<uint32_t*>(lds));
 }
 
 // The same forward for launches that would leave most of the chip idle (few column strips, few row
@@ -660,6 +692,7 @@ int launch_any(const LayerDev& L, const uint32_t* planes, const int32_t* colsum,
     p.M = M;
     p.nchunks = L.nchunks;
     p.out_bits = out_bits;
+    p.out_exclusive = 0;
     p.out_Kw = (L.N + 31) / 32;
     p.out_inv_step = out_inv_step;
     p.conv_Cw = conv ? conv->C / 32 : 0;
@@ -678,6 +711,16 @@ int launch_any(const LayerDev& L, const uint32_t* planes, const int32_t* colsum,
         if (blocks * 16 < 3000 && L.nchunks >= 4) ks = 4;
     }
     int rc;
+    if (out_bits != 0) {
+        // One workgroup holds every row of its columns: it stores whole words, nothing to clear.  Otherwise
+        // the workgroups OR their bits into a buffer cleared here (a fill kernel, not a memset node: the
+        // call may be recorded into a graph).
+        p.out_exclusive = p.row_groups == 1 && ks == 1;
+        if (!p.out_exclusive) {
+            rc = launch_zero_words(reinterpret_cast<uint32_t*>(o.out), ((size_t)out_bits * p.out_Kw + 1) * Mp, s);
+            if (rc != APB_OK) return rc;
+        }
+    }
     if (conv) rc = bits == 1 ? launch_bits<1, true>(L, planes, colsum, o, p, ks, s) : launch_bits<2, true>(L, planes, colsum, o, p, ks, s);
     else rc = bits == 1 ? launch_bits<1, false>(L, planes, colsum, o, p, ks, s) : launch_bits<2, false>(L, planes, colsum, o, p, ks, s);
     if (rc != APB_OK) return rc;
@@ -694,7 +737,7 @@ int launch_forward(const LayerDev& L, const uint32_t* planes, const int32_t* col
     return launch_any(L, planes, colsum, M, bits, step, conv, OutArgs{nullptr, nullptr, Y}, 0, 0.0f, s);
 }
 
-// packed_out: the next layer's packed activation buffer (K = L.N), zero-filled on `s` before this launch.
+// packed_out: the next layer's packed activation buffer (K = L.N), fully overwritten.
 int launch_forward_requant(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                            const ConvShape* conv, const float* scale, const float* shift, int bits_out,
                            float inv_step_out, uint32_t* packed_out, hipStream_t s) {
