@@ -146,7 +146,7 @@ def run_workload(name, steps, warmup, calibration_copy=False):
     else:
         roof_fwd = {"bound": "alu", "achieved": 2.0 * nnz * M / t_fwd / 1e12, "peak": FP64_VECTOR_PEAK_TFLOPS,
                     "unit": "TFLOP/s"}
-    roof_fwd = {"kernel": "k_sparse_epilogue (fused forward)"} | roof_fwd
+    roof_fwd = {"kernel": "k_sparse_epilogue or k_forward_ksplit (the forward kernel)"} | roof_fwd
     roof_fwd |= {"frac": roof_fwd["achieved"] / roof_fwd["peak"], "traffic": None, "ms": ms_fwd,
                  "floor_us": {"hbm": t_hbm * 1e6, "mfma_fp4": t_mfma * 1e6, "fp64_vector": t_f64 * 1e6}}
     # The roof the benchmark spec names for the forward: the vector-ALU bit-op rate of the popcount
