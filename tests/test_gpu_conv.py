@@ -151,3 +151,54 @@ def test_full_size_conv_layers_equal_the_explicit_route(b, name, B, H, W):
     ref = F["Y"].astype(np.float64)
     assert np.all(np.abs(got - ref) <= REL_TOL * np.abs(ref))
     layer.free()
+
+
+def test_three_chained_convolutions_in_a_captured_graph(b):
+    """quantize -> conv+requant -> conv+requant -> conv (float) recorded into a graph: the chained entry
+    points allocate nothing and clear their output with a fill kernel, so every replay must reproduce the
+    eager result, with eager work between the replays.  One layer has more than 128 rows (zero fill +
+    atomics), the others at most 128 (plain stores)."""
+    B, H, W = 3, 9, 11
+    P = B * H * W
+    shapes = [(64, 64), (192, 64), (128, 192)]               # (N, C) of the three layers
+    layers = []
+    for i, (N, C) in enumerate(shapes):
+        Wt, delta, _, _ = synth.random_case(500 + i, N, 9 * C, 1, 2, rho=0.03)
+        layers.append(b.apb_compress(torch.from_numpy(Wt).cuda(), float(delta)))
+    Xmap = torch.from_numpy(np.maximum(np.random.default_rng(9).standard_normal((64, P)), 0).astype(np.float32)).cuda()
+    f0 = b.alloc_packed(64, P, 2)
+    f1 = b.alloc_packed(64, P, 2)
+    f2 = b.alloc_packed(192, P, 2)
+    Y = torch.empty((128, P), dtype=torch.float32, device="cuda")
+
+    def net():
+        b.apb_quantize_acts(Xmap, 2, 0.75, packed=f0)
+        b.apb_forward_conv3x3_requant(layers[0], f0, B, H, W, 2, 0.75, 2, 0.6, fmap_out=f1)
+        b.apb_forward_conv3x3_requant(layers[1], f1, B, H, W, 2, 0.6, 2, 0.9, fmap_out=f2)
+        b.apb_forward_conv3x3(layers[2], f2, B, H, W, 2, 0.9, Y=Y)
+
+    net()
+    torch.cuda.synchronize()
+    y_ref, f2_ref = Y.clone(), f2.clone()
+    assert f2_ref.any() and y_ref.abs().max() > 0
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        net()
+    torch.cuda.current_stream().wait_stream(side)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        net()
+    for _ in range(3):
+        Y.zero_()
+        f1.fill_(-1)
+        f2.fill_(-1)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(f2, f2_ref) and torch.equal(Y, y_ref)
+        net()
+        torch.cuda.synchronize()
+        assert torch.equal(Y, y_ref)
+    for layer in layers:
+        layer.free()
