@@ -406,6 +406,37 @@ def run_conv_chain(name, steps, warmup):
     return res, cfg
 
 
+def cpu_baseline_conv_chain(cfg, B, H, W_, bits_out, step_out):
+    """The CPU oracle of the chained convolution (im2col of the quantized map, forward, re-quantize, pack) on
+    the first images of the batch."""
+    from oracle import apb_oracle as o
+    from oracle import capi
+    from paper_2306_08960_amd import synth
+    cores = max(1, min(len(os.sched_getaffinity(0)), capi.max_threads()))
+    Wt, delta = synth.make_weights(cfg)
+    L = o.compress(Wt, delta)
+    nnz = int(L["row_ptr"][-1])
+    C = cfg.K // 9
+    per_col = 2.0 * cfg.N * cfg.K + 2.0 * nnz
+    images = int(max(1, min(B, 60e9 * cores ** 0.5 / per_col / (H * W_))))
+    m = images * H * W_
+    Xmap = np.random.default_rng(cfg.index).standard_normal((C, m)).astype(np.float32)
+    if cfg.bits == 2:
+        np.maximum(Xmap, 0, out=Xmap)
+    c_map = o.quantize(Xmap, cfg.bits, np.float32(cfg.step))
+    passes, dt = 0, 0.0
+    while passes == 0 or (dt < 1.0 and passes < 20):
+        t0 = time.perf_counter()
+        patches = o.im2col_codes(c_map, images, H, W_, cfg.bits)
+        F = capi.forward(L, o.pack_acts(patches, cfg.bits), patches, cfg.bits, np.float32(cfg.step), threads=cores)
+        o.requant(L["alpha"], np.float32(cfg.step), F["D"], F["R"], bits_out, np.float32(step_out))
+        dt += time.perf_counter() - t0
+        passes += 1
+    return {"value": per_col * m * passes / dt / 1e9, "unit": "GOPS", "cores": cores, "kind": "oracle",
+            "sample": f"first {images} of {B} images of {cfg.name}, {passes} passes (im2col of the codes + pack + forward + "
+                      f"requantize + pack), {dt:.2f} s"}
+
+
 def cpu_baseline_chain(cfg, W, delta, X, step, bits_out, step_out):
     """The CPU oracle of the chained step (forward from packed codes, re-quantize, pack) on the first columns."""
     from oracle import apb_oracle as o
@@ -562,6 +593,8 @@ def main():
             print(f"bench.py: {args.workload} is not a convolution layer; choose from {sorted(CONV_GEOMETRY)}", file=sys.stderr)
             sys.exit(2)
         res, cfg = run_conv_chain(args.workload, args.steps, args.warmup)
+        cpu = None if args.no_cpu_baseline else cpu_baseline_conv_chain(cfg, res["B"], res["H"], res["W"], res["bits_out"],
+                                                                         res["step_out"])
         print(json.dumps({
             "metric": "APB 3x3 conv layer GOPS, chained (packed feature map in, packed feature map out)",
             "value": res["gops_step"], "unit": "GOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -574,7 +607,8 @@ def main():
             "ms_conv_float_output": res["ms_conv_float_output"],
             "ms_explicit_im2col_quantize_plus_forward": res["ms_explicit_im2col_quantize_plus_forward"],
             "implicit_equals_explicit_bitwise": res["implicit_equals_explicit_bitwise"],
-            "frac_of_valu_bitop_roof": res["frac_of_valu_bitop_roof"], "roofline": res["roofline"]}))
+            "frac_of_valu_bitop_roof": res["frac_of_valu_bitop_roof"], "roofline": res["roofline"]}
+            | ({} if cpu is None else {"cpu_baseline": cpu})))
         return
     if args.routine == "chain":
         res, inputs = run_chain(args.workload, args.steps, args.warmup)

@@ -137,3 +137,26 @@ def test_fc_chain_at_full_size_sampled_columns(b):
     ref2 = o.requant(L["alpha"], step_out, F2["D"], F2["R"], 2, step_out)
     assert (code2[:, cols] != ref2["c"]).mean() < 1e-3
     layer.free()
+
+
+def test_argument_errors(b):
+    W, delta, X, step = synth.random_case(1, 20, 64, 10, 2)
+    layer = b.apb_compress(torch.from_numpy(W).cuda(), float(delta))
+    packed = b.apb_quantize_acts(torch.from_numpy(X).cuda(), 2, float(step))
+    out = b.alloc_packed(20, 10, 2)
+    lib = b.load()
+    ptr = lambda t: t.data_ptr()
+    f = torch.ones(20, device="cuda")
+    call = lambda *a: lib.apb_forward_requant(layer.handle, *a)
+    assert call(ptr(packed), 10, 2, 0.75, None, None, 3, 1.0, ptr(out), None) == b.APB_ERR_BITS
+    assert call(ptr(packed), 10, 3, 0.75, None, None, 2, 1.0, ptr(out), None) == b.APB_ERR_BITS
+    assert call(ptr(packed), 10, 2, 0.75, None, None, 2, 0.0, ptr(out), None) == b.APB_ERR_VALUE
+    assert call(ptr(packed), 10, 2, float("nan"), None, None, 2, 1.0, ptr(out), None) == b.APB_ERR_VALUE
+    assert call(ptr(packed), 10, 2, 0.75, ptr(f), None, 2, 1.0, ptr(out), None) == b.APB_ERR_NULL
+    assert call(ptr(packed), 10, 2, 0.75, None, None, 2, 1.0, None, None) == b.APB_ERR_NULL
+    assert call(ptr(packed), 0, 2, 0.75, None, None, 2, 1.0, ptr(out), None) == b.APB_ERR_SHAPE
+    with pytest.raises(ValueError):
+        b.apb_forward_requant(layer, packed, 10, 2, 0.75, 2, 1.0, scale=f)
+    with pytest.raises(ValueError):
+        b.apb_forward_requant(layer, packed, 10, 2, 0.75, 2, 1.0, packed_out=torch.empty(4, dtype=torch.int32, device="cuda"))
+    layer.free()
