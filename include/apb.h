@@ -25,8 +25,9 @@
  *    4-byte aligned; the caller owns them.  The library owns only what lives
  *    inside an apb_layer.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *    apb_quantize_acts / apb_forward / apb_forward_requant / apb_forward_int only enqueue work and
- *    return; apb_compress and apb_layer_export synchronize the stream.
+ *    apb_quantize_acts, the apb_forward* family and apb_gemm_2_2* only enqueue work and return
+ *    (none of them allocates, and none records a memset: a caller may capture them in a HIP
+ *    graph); apb_compress, apb_layer_export and apb_w2_export synchronize the stream.
  *  - Non-finite values in W or X give unspecified numbers but never touch
  *    memory out of bounds (a NaN activation quantizes to code 0 / sign -).
  *  - Distinct layers and buffers may be used from distinct host threads.
