@@ -106,20 +106,38 @@ def run_workload(name, steps, warmup, calibration_copy=False):
     def fwd():
         b.apb_forward(layer, packed, M, bits, s, Y=Y)
 
-    def one_step():
+    def two_calls():
         quant()
         fwd()
 
-    for _ in range(warmup):
-        one_step()
+    def one_call():                          # the step: quantize + forward through the single entry point
+        b.apb_quantize_forward(layer, Xd, bits, s, packed=packed, Y=Y)
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    one_kernel = b.apb_quantize_forward_is_one_kernel(layer, M, bits)
+    ms_two = timed(two_calls)
+    ms_quant, ms_fwd, ms_event_record = time_in_step(quant, fwd, steps, ms_two)
+    ms_step = timed(one_call)
+    # the single call between events on its stream (same treatment of the record cost as in time_in_step)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(steps):
-        one_step()
+    for a, c in ev:
+        a.record()
+        one_call()
+        c.record()
     torch.cuda.synchronize()
-    ms_step = (time.perf_counter() - t0) * 1e3 / steps
-
-    ms_quant, ms_fwd, ms_event_record = time_in_step(quant, fwd, steps, ms_step)
+    per_record = max(0.0, ((time.perf_counter() - t0) * 1e3 / steps - ms_step) / 2.0)
+    ms_one = sum(a.elapsed_time(c) for a, c in ev) / steps - per_record
 
     ops = 2.0 * N * K * M + 2.0 * nnz * M
     Kw, Mp = (K + 31) // 32, 64 * ((M + 63) // 64)
@@ -156,12 +174,21 @@ def run_workload(name, steps, warmup, calibration_copy=False):
     t_valu = (2.0 * bits * N * Kw * M + float(nnz) * M) / VALU_LANE_OPS_PER_S
     roof_valu = {"bound": "alu", "what": "VALU bit-op roof of the popcount formulation", "roof_us": t_valu * 1e6,
                  "achieved": ops / t_fwd / 1e12, "peak": ops / t_valu / 1e12, "unit": "TOP/s", "frac": t_valu / t_fwd}
+    # Layers of at most 128 rows run the step as ONE kernel (quantize into LDS + forward): it reads X and the
+    # layer and writes Y, nothing else, so its floor is those bytes at the HBM peak.
+    one_bytes = 4.0 * K * M + 4.0 * N * M + 4.0 * N * Kw + 12.0 * nnz
+    roof_one = {"kernel": "k_sparse_epilogue<.., float input> (quantize + forward in one kernel)", "bound": "hbm",
+                "achieved": one_bytes / (ms_one * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": None,
+                "algorithmic_bytes": one_bytes, "ms": ms_one}
+    roof_one["frac"] = roof_one["achieved"] / roof_one["peak"]
+    roof_two = roof_quant if ms_quant >= ms_fwd else roof_fwd
     res = {
         "workload": name, "N": N, "K": K, "M": M, "act_bits": bits, "nnz": int(nnz),
-        "ms_per_step": ms_step, "gops_step": ops / (ms_step * 1e-3) / 1e9,
+        "ms_per_step": ms_step, "gops_step": ops / (ms_step * 1e-3) / 1e9, "one_kernel_step": bool(one_kernel),
+        "ms_per_step_two_calls": ms_two,
         "ms_quantize": ms_quant, "ms_forward": ms_fwd, "ms_event_record_removed": ms_event_record,
         "gops_forward": ops / (ms_fwd * 1e-3) / 1e9,
-        "roofline": roof_quant if ms_quant >= ms_fwd else roof_fwd, "roofline_forward": roof_fwd,
+        "roofline": roof_one if one_kernel else roof_two, "roofline_forward": roof_fwd,
         "roofline_forward_valu_bitop": roof_valu,
         "roofline_quantize": roof_quant,
     }
@@ -640,7 +667,9 @@ def main():
         "dtype": "fp4 (exact 0/1 and 2-bit codes) on MFMA + f64 accumulate (f32 in/out)", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.note}", "N": cfg.N, "K": cfg.K, "M": cfg.M,
                    "act_bits": cfg.bits, "outlier_rate": cfg.rho, "nnz": res["nnz"],
-                   "step": "apb_quantize_acts + apb_forward, inputs resident in HBM"},
+                   "step": "apb_quantize_forward (= apb_quantize_acts + apb_forward; one kernel for layers of at most "
+                           "128 rows), inputs resident in HBM", "one_kernel_step": res["one_kernel_step"]},
+        "ms_per_step_two_calls": res["ms_per_step_two_calls"],
         "ms_quantize": res["ms_quantize"], "ms_forward": res["ms_forward"],
         "ms_event_record_removed": res["ms_event_record_removed"],
         "gops_forward_only": res["gops_forward"],
@@ -658,6 +687,7 @@ def main():
                 continue
             r, _ = run_workload(name, max(20, args.steps // 4), max(5, args.warmup // 4))
             others.append({k: r[k] for k in ("workload", "N", "K", "M", "act_bits", "nnz", "ms_per_step", "gops_step",
+                                             "one_kernel_step", "ms_per_step_two_calls",
                                              "ms_quantize", "ms_forward", "gops_forward")}
                           | {"forward_frac_of_valu_bitop_roof": r["roofline_forward_valu_bitop"]["frac"],
                              "forward_bound": r["roofline_forward"]["bound"],

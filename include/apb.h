@@ -115,6 +115,21 @@ int apb_quantize_acts(const float* X, int K, int M, int bits, float step, void* 
  * Asynchronous on `stream`. */
 int apb_forward(const apb_layer* layer, const void* packed, int M, int bits, float step, float* Y, void* stream);
 
+/* apb_quantize_acts followed by apb_forward as ONE call, with the same Y bit for bit.  For layers of at
+ * most 128 rows (one workgroup then holds every row, so no strip of X is quantized twice) whose K fits
+ * the on-chip memory, a single kernel reads X, keeps the packed codes of its 64 columns on chip and
+ * writes Y: the packed activations never travel to HBM and the memory-bound quantize phase of one
+ * workgroup overlaps the arithmetic of the others.  Other layers run the two kernels one after the
+ * other through `packed`.
+ *   X       DEVICE, K*M floats row-major, read-only.
+ *   packed  DEVICE, apb_acts_bytes(K, M, bits) bytes of scratch; contents unspecified afterwards.
+ *   Y       DEVICE, N*M floats, fully overwritten.
+ * Asynchronous on `stream`. */
+int apb_quantize_forward(const apb_layer* layer, const float* X, int M, int bits, float step, void* packed, float* Y,
+                         void* stream);
+/* 1 if apb_quantize_forward runs as the single kernel for this layer, M and bits, else 0 (also on bad arguments). */
+int apb_quantize_forward_is_one_kernel(const apb_layer* layer, int M, int bits);
+
 /* Two layers in a row without the float round trip: Eq. 13 of this layer followed directly by the
  * activation quantizer (Sec. IV) of the layer it feeds, whose K is this layer's N.  The result is
  * the packed buffer that apb_quantize_acts(Z, N, M, bits_out, step_out) would write for

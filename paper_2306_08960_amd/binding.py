@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libapb.so")
 
 EXPORTS = (
     "apb_compress", "apb_layer_info", "apb_layer_export", "apb_layer_free", "apb_acts_bytes",
-    "apb_quantize_acts", "apb_forward", "apb_forward_requant", "apb_forward_conv3x3", "apb_forward_conv3x3_requant",
+    "apb_quantize_acts", "apb_forward", "apb_quantize_forward", "apb_quantize_forward_is_one_kernel", "apb_forward_requant", "apb_forward_conv3x3", "apb_forward_conv3x3_requant",
     "apb_forward_int", "apb_forward_int_popcount", "apb_forward_popcount",
     "apb_w2_pack", "apb_w2_export", "apb_w2_free", "apb_gemm_2_2_int", "apb_gemm_2_2",
     "apb_strerror", "apb_last_hip_error",
@@ -63,6 +63,10 @@ def load() -> ctypes.CDLL:
     lib.apb_quantize_acts.restype = ci
     lib.apb_forward.argtypes = [vp, vp, ci, ci, cf, vp, vp]
     lib.apb_forward.restype = ci
+    lib.apb_quantize_forward.argtypes = [vp, vp, ci, ci, cf, vp, vp, vp]
+    lib.apb_quantize_forward.restype = ci
+    lib.apb_quantize_forward_is_one_kernel.argtypes = [vp, ci, ci]
+    lib.apb_quantize_forward_is_one_kernel.restype = ci
     lib.apb_forward_requant.argtypes = [vp, vp, ci, ci, cf, vp, vp, ci, cf, vp, vp]
     lib.apb_forward_requant.restype = ci
     lib.apb_forward_conv3x3.argtypes = [vp, vp, ci, ci, ci, ci, cf, vp, vp]
@@ -225,6 +229,31 @@ def apb_forward(layer: ApbLayer, packed: torch.Tensor, M: int, bits: int, step: 
     _check(load().apb_forward(layer.handle, _dev_ptr(packed, torch.int32, "packed"), int(M), int(bits),
                               float(step), _dev_ptr(Y, torch.float32, "Y"), _stream(stream)), "apb_forward")
     return Y
+
+
+def apb_quantize_forward(layer: ApbLayer, X: torch.Tensor, bits: int, step: float, packed: Optional[torch.Tensor] = None,
+                         Y: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """apb_quantize_acts + apb_forward in one call; `packed` is scratch."""
+    if X.dim() != 2:
+        raise TypeError("X must be 2-D [K, M]")
+    K, M = X.shape
+    if packed is None:
+        packed = alloc_packed(K, M, bits, X.device)
+    N, _ = _check_packed(layer, packed, M, bits)
+    if apb_layer_info(layer)["K"] != K:
+        raise ValueError("X must have the layer's K rows")
+    if Y is None:
+        Y = torch.empty((N, M), dtype=torch.float32, device=X.device)
+    elif tuple(Y.shape) != (N, M):
+        raise ValueError("Y must be [N, M]")
+    _check(load().apb_quantize_forward(layer.handle, _dev_ptr(X, torch.float32, "X"), int(M), int(bits), float(step),
+                                       _dev_ptr(packed, torch.int32, "packed"), _dev_ptr(Y, torch.float32, "Y"),
+                                       _stream(stream)), "apb_quantize_forward")
+    return Y
+
+
+def apb_quantize_forward_is_one_kernel(layer: ApbLayer, M: int, bits: int) -> bool:
+    return bool(load().apb_quantize_forward_is_one_kernel(layer.handle, int(M), int(bits)))
 
 
 def apb_forward_requant(layer: ApbLayer, packed: torch.Tensor, M: int, bits: int, step: float, bits_out: int,

@@ -353,6 +353,27 @@ int apb_forward_requant(const apb_layer* layer, const void* packed, int M, int b
     return launch_forward_requant(d, planes, colsum, M, bits, step, nullptr, scale, shift, bits_out, 1.0f / step_out, out, s);
 }
 
+int apb_quantize_forward_is_one_kernel(const apb_layer* layer, int M, int bits) {
+    if (!layer || M <= 0 || (bits != 1 && bits != 2)) return 0;
+    return forward_float_applies(layer->d, M, bits) ? 1 : 0;
+}
+
+int apb_quantize_forward(const apb_layer* layer, const float* X, int M, int bits, float step, void* packed, float* Y,
+                         void* stream) {
+    if (!layer || !X || !packed || !Y) return APB_ERR_NULL;
+    const LayerDev& d = layer->d;
+    if (bad_shape_acts(d.K, M) || (long long)d.N * M >= (1LL << 40)) return APB_ERR_SHAPE;
+    if (bits != 1 && bits != 2) return APB_ERR_BITS;
+    if (!std::isfinite(step) || !(step > 0.0f)) return APB_ERR_VALUE;
+    hipStream_t s = as_stream(stream);
+    if (forward_float_applies(d, M, bits)) return launch_forward_float(d, X, M, bits, step, Y, s);
+    const int rc = apb_quantize_acts(X, d.K, M, bits, step, packed, stream);
+    return rc != APB_OK ? rc : launch_forward(d, static_cast<const uint32_t*>(packed),
+                                              reinterpret_cast<const int32_t*>(static_cast<const uint32_t*>(packed) +
+                                                  (size_t)bits * d.Kw * ((size_t)kWave * (((size_t)M + kWave - 1) / kWave))),
+                                              M, bits, step, nullptr, Y, s);
+}
+
 // Shape checks shared by the two convolution entry points; fills `conv` and the pixel count.
 static int conv_shape(const LayerDev& d, int B, int H, int W, ConvShape& conv, int& P) {
     if (B <= 0 || H <= 0 || W <= 0 || d.K % 9 != 0 || (d.K / 9) % 64 != 0) return APB_ERR_SHAPE;

@@ -94,6 +94,10 @@ struct ConvShape {
 };
 int launch_forward(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                    const ConvShape* conv, float* Y, hipStream_t s);
+// quantize + forward in one kernel, from the float matrix X (K x M): same Y, bit for bit, as launch_quantize +
+// launch_forward; only where forward_float_applies says so (APB_ERR_SHAPE otherwise)
+bool forward_float_applies(const LayerDev& L, int M, int bits);
+int launch_forward_float(const LayerDev& L, const float* X, int M, int bits, float step, float* Y, hipStream_t s);
 // the same with the next layer's quantizer applied to scale[n] * Y + shift[n] (scale, shift nullable) and
 // the codes packed into `packed_out` (K = L.N, same M), fully overwritten
 int launch_forward_requant(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,

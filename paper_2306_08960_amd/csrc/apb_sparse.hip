@@ -56,6 +56,9 @@ struct SparseParams {
     // (dy, dx) = (tap / 3 - 1, tap % 3 - 1), or zero outside the image.
     int conv_Cw, conv_H, conv_W;
     float conv_inv_Cw;
+    // Float activations (FX kernels): K rows of X and 1 / step of the input quantizer.
+    int K;
+    float in_inv_step;
 };
 
 // Bit t of the result: tap t of pixel m lies inside the image (never for columns >= M).
@@ -187,11 +190,14 @@ __device__ __forceinline__ void batch(v16d& acc, v8d& pairs, const uint32_t* __r
 // CONV: the activation words come from a packed feature map through the implicit im2col (see
 // SparseParams); vm is the tap mask of this lane's column m_base + 32*tm + (lane & 31).  Cw is even, so
 // the two word rows of a step belong to the same tap.
-template <int BITS, bool CONV>
+// FX: the activation words of the workgroup's 64 columns sit in LDS (`lplanes`, [BITS][Kw rounded up to
+// even][64], written by quantize_strip).
+template <int BITS, bool CONV, bool FX = false>
 __device__ __forceinline__ void binary_tile_to_lds(const uint32_t* __restrict__ signT,
                                                    const uint32_t* __restrict__ planes, int Np, int Kw, int Mp,
                                                    int slot_base, int m_base, int tn, int tm, int s_begin, int s_end,
-                                                   int lane, int32_t* tile, const SparseParams& p, uint32_t vm) {
+                                                   int lane, int32_t* tile, const SparseParams& p, uint32_t vm,
+                                                   const uint32_t* lplanes = nullptr) {
     const int i = lane & 31, g = lane >> 5;
     const unsigned aoff = (unsigned)(g * Np + slot_base + 32 * tn + i);
     const unsigned boff = (unsigned)(g * Mp + m_base + 32 * tm + i);
@@ -211,7 +217,11 @@ __device__ __forceinline__ void binary_tile_to_lds(const uint32_t* __restrict__ 
     auto load_words = [&](int st, uint32_t (&a)[1][1], uint32_t (&b)[BITS][1]) {
         const int ss = min(st, steps - 1);                      // past the end: harmless re-read, never used
         a[0][0] = (signT + (size_t)(2 * ss) * Np)[aoff];
-        if (!CONV) {
+        if (FX) {
+            const int Kw2 = 2 * ((Kw + 1) / 2);
+#pragma unroll
+            for (int pl = 0; pl < BITS; ++pl) b[pl][0] = lplanes[(pl * Kw2 + 2 * ss + g) * kWave + 32 * tm + i];
+        } else if (!CONV) {
 #pragma unroll
             for (int pl = 0; pl < BITS; ++pl) b[pl][0] = (planes + pl * plane_stride + (size_t)(2 * ss) * Mp)[boff];
         } else {
@@ -385,9 +395,60 @@ __device__ __forceinline__ uint32_t load_act_word(const uint32_t* __restrict__ p
     return __builtin_amdgcn_raw_buffer_load_b32(rsrc, tap_offset(vm, tap, m_off >> 2, tap_shift(tap, p.conv_W)), 0, 0);
 }
 
+// FX kernels, phase 0: quantize the workgroup's strip of 64 columns of the float matrix X (K x M,
+// row-major) and leave its packed words in LDS -- lplanes[BITS][Kw2][64] (Kw2 = Kw rounded up to even,
+// the extra row zero) and the column sums lcol[64] -- instead of HBM.  The arithmetic is that of
+// apb_quantize_acts, bit for bit (same code2, same masks).  Waves take the words of K round-robin; a
+// wave's load of one row of X is one contiguous 256-byte segment, 16 of them in flight.
+template <int BITS>
+__device__ __forceinline__ void quantize_strip(const float* __restrict__ X, const SparseParams& p, int m, int wave,
+                                               int waves, int lane, uint32_t* lplanes, int32_t* lcol) {
+    const int Kw2 = 2 * ((p.Kw + 1) / 2);
+    if (wave == 0) lcol[lane] = 0;
+    __syncthreads();
+    const bool col_ok = m < p.M;
+    const unsigned mc = (unsigned)min(m, p.M - 1);
+    int sum = 0;
+    for (int j = wave; j < Kw2; j += waves) {
+        uint32_t w0 = 0, w1 = 0;
+        if (j < p.Kw) {
+            const int k0 = 32 * j;
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                float xv[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    xv[i] = __builtin_nontemporal_load((X + (size_t)min(k0 + 16 * half + i, p.K - 1) * p.M) + mc);
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int bit = 16 * half + i;
+                    if (BITS == 1) {
+                        w0 |= (xv[i] >= 0.0f ? 1u : 0u) << bit;
+                    } else {
+                        const uint32_t c = code2(xv[i], p.in_inv_step);
+                        w0 |= (c & 1u) << bit;
+                        w1 |= (c >> 1) << bit;
+                    }
+                }
+            }
+            const int valid = p.K - k0;
+            const uint32_t keep = !col_ok ? 0u : (valid >= 32 ? 0xffffffffu : ((1u << valid) - 1u));
+            w0 &= keep;
+            w1 &= keep;
+            sum += __builtin_popcount(w0) + 2 * __builtin_popcount(w1);
+        }
+        lplanes[j * kWave + lane] = w0;
+        if (BITS == 2) lplanes[(Kw2 + j) * kWave + lane] = w1;
+    }
+    if (sum) __hip_atomic_fetch_add(lcol + lane, sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    __syncthreads();
+}
+
 // WPW = words of a chunk each wave expands = 8 / waves per workgroup.
 // CONV: 3x3 convolution over a packed feature map (implicit im2col, see SparseParams).
-template <int BITS, int WPW, bool CONV>
+// FX: `planes` is the float matrix X itself; the workgroup quantizes its strip into LDS first (only for
+// layers whose rows all sit in one workgroup, so that no strip is quantized twice).
+template <int BITS, int WPW, bool CONV, bool FX = false>
 __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_waves_per_eu(WPW <= 2 ? 8 : 4, 8))) void k_sparse_epilogue(
     // Separate restrict-qualified arguments (not struct members) so that the compiler knows the
     // read-only arrays cannot alias Y and keeps the wave-uniform loads on the scalar path.
@@ -418,7 +479,11 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
     const int m_off = m * 4;                                    // the launcher keeps 4 * Mp below 2^31
 
     static_assert(TN == 16, "row field of an entry key addresses 16 register pairs");
+    static_assert(!(CONV && FX), "float input goes with the plain matrix form");
     const uint32_t vm = CONV ? tap_mask(m, p) : 0u;
+    uint32_t* lplanes = reinterpret_cast<uint32_t*>(lds + kBufs * kTableBytes);      // FX only
+    int32_t* lcol = reinterpret_cast<int32_t*>(lplanes + BITS * (2 * ((p.Kw + 1) / 2)) * kWave);
+    if (FX) quantize_strip<BITS>(reinterpret_cast<const float*>(planes), p, m, wave, waves, lane, lplanes, lcol);
     v16d acc;
     {
         // Binary part first; every lane then picks up the 16 products of its column and starts its
@@ -429,14 +494,14 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
         // (the binary tile's column of a lane is column 32 * (wave & 1) + (lane & 31) of the strip: its mask
         // is that lane's)
         const uint32_t vm_tile = CONV ? (uint32_t)__shfl((int)vm, 32 * (wave & 1) + (lane & 31)) : 0u;
-        binary_tile_to_lds<BITS, CONV>(signT, planes, p.Np, p.Kw, p.Mp, rg * waves * TN, strip * kWave, wave >> 1, wave & 1,
-                                       0, (p.Kw + 1) / 2, lane, tile_lds, p, vm_tile);
+        binary_tile_to_lds<BITS, CONV, FX>(signT, planes, p.Np, p.Kw, p.Mp, rg * waves * TN, strip * kWave, wave >> 1,
+                                           wave & 1, 0, (p.Kw + 1) / 2, lane, tile_lds, p, vm_tile, lplanes);
         __syncthreads();
         int P[TN];
 #pragma unroll
         for (int r = 0; r < TN; ++r) P[r] = tile_lds[(wave * TN + r) * kWave + lane];
         __syncthreads();
-        const int cs = column_code_sum<CONV>(colsum, m, vm, p);
+        const int cs = FX ? lcol[lane] : column_code_sum<CONV>(colsum, m, vm, p);
         const double a0 = p.alpha * (BITS == 1 ? 0.5 : 1.0) * (1.0 / kSumUnscale);
 #pragma unroll
         for (int r = 0; r < TN; ++r) {
@@ -462,7 +527,9 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
         for (int i = 0; i < WPW; ++i) {
             const int j = c * kChunkWords + wave + i * waves;
 #pragma unroll
-            for (int b = 0; b < BITS; ++b) xw[b][i] = load_act_word<CONV>(planes, plane_stride, b, j, m_off, vm, p);
+            for (int b = 0; b < BITS; ++b)
+                xw[b][i] = FX ? lplanes[(b * (2 * ((p.Kw + 1) / 2)) + min(j, p.Kw - 1)) * kWave + lane]
+                              : load_act_word<CONV>(planes, plane_stride, b, j, m_off, vm, p);
         }
     };
     fetch(0);
@@ -666,6 +733,31 @@ void launch_one(const LayerDev& L, const uint32_t* planes, const int32_t* colsum
                        L.slot_valsum, L.signT, o.scale, o.shift, o.out, p);
 }
 
+// LDS of a float-input launch: the code tables, then the strip's packed words and column sums.
+int float_input_lds_bytes(const LayerDev& L, int bits) {
+    const int wpw = kChunkWords / L.waves;
+    return table_buffers(wpw) * kTableBytes + bits * (2 * ((L.Kw + 1) / 2)) * kWave * 4 + kWave * 4;
+}
+
+template <int BITS, int WPW>
+void launch_one_float(const LayerDev& L, const float* X, const OutArgs& o, const SparseParams& p, hipStream_t s) {
+    hipLaunchKernelGGL((k_sparse_epilogue<BITS, WPW, false, true>), dim3((unsigned)p.blocks),
+                       dim3(kWave * kChunkWords / WPW), float_input_lds_bytes(L, BITS), s,
+                       reinterpret_cast<const uint32_t*>(X), static_cast<const int32_t*>(nullptr), L.rowsum, L.perm,
+                       L.seg_ptr, L.ent, L.slot_valsum, L.signT, o.scale, o.shift, o.out, p);
+}
+
+template <int BITS>
+int launch_bits_float(const LayerDev& L, const float* X, const OutArgs& o, const SparseParams& p, hipStream_t s) {
+    switch (L.waves) {
+        case 8: launch_one_float<BITS, 1>(L, X, o, p, s); break;
+        case 4: launch_one_float<BITS, 2>(L, X, o, p, s); break;
+        case 2: launch_one_float<BITS, 4>(L, X, o, p, s); break;
+        default: return APB_ERR_SHAPE;
+    }
+    return APB_OK;
+}
+
 template <int BITS, bool CONV>
 int launch_bits(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, const OutArgs& o, const SparseParams& p,
                 int ks, hipStream_t s) {
@@ -680,8 +772,21 @@ int launch_bits(const LayerDev& L, const uint32_t* planes, const int32_t* colsum
     return APB_OK;
 }
 
+// Launches of 8-wave workgroups that would put fewer than ~3000 waves on the chip split K two or four
+// ways inside the workgroup instead (see k_forward_ksplit).
+int ksplit_parts(const LayerDev& L, long long blocks) {
+    int ks = 1;
+    if (L.waves == 8) {
+        if (blocks * 8 < 3000 && L.nchunks >= 2) ks = 2;
+        if (blocks * 16 < 3000 && L.nchunks >= 4) ks = 4;
+    }
+    return ks;
+}
+
+// X != nullptr: float activations, quantized inside the kernel (see forward_float_applies).
 int launch_any(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
-               const ConvShape* conv, const OutArgs& o, int out_bits, float out_inv_step, hipStream_t s) {
+               const ConvShape* conv, const OutArgs& o, int out_bits, float out_inv_step, hipStream_t s,
+               const float* X = nullptr) {
     const int Mp = kWave * ((M + kWave - 1) / kWave);
     SparseParams p;
     p.alpha = (double)L.alpha;
@@ -699,17 +804,13 @@ int launch_any(const LayerDev& L, const uint32_t* planes, const int32_t* colsum,
     p.conv_H = conv ? conv->H : 0;
     p.conv_W = conv ? conv->W : 0;
     p.conv_inv_Cw = conv ? 1.0f / (float)(conv->C / 32) : 0.0f;
+    p.K = L.K;
+    p.in_inv_step = 1.0f / step;
     p.row_groups = L.Np / (TN * L.waves);
     const long long blocks = (long long)p.row_groups * (Mp / kWave);
     if (blocks > 0x7fffffffLL || (long long)Mp * 8 >= (1LL << 31)) return APB_ERR_SHAPE;
     p.blocks = (int)blocks;
-    // Launches of 8-wave workgroups that would put fewer than ~3000 waves on the chip split K two or
-    // four ways inside the workgroup instead (see k_forward_ksplit).
-    int ks = 1;
-    if (L.waves == 8) {
-        if (blocks * 8 < 3000 && L.nchunks >= 2) ks = 2;
-        if (blocks * 16 < 3000 && L.nchunks >= 4) ks = 4;
-    }
+    const int ks = X ? 1 : ksplit_parts(L, blocks);
     int rc;
     if (out_bits != 0) {
         // One workgroup holds every row of its columns: it stores whole words, nothing to clear.  Otherwise
@@ -721,7 +822,8 @@ int launch_any(const LayerDev& L, const uint32_t* planes, const int32_t* colsum,
             if (rc != APB_OK) return rc;
         }
     }
-    if (conv) rc = bits == 1 ? launch_bits<1, true>(L, planes, colsum, o, p, ks, s) : launch_bits<2, true>(L, planes, colsum, o, p, ks, s);
+    if (X) rc = bits == 1 ? launch_bits_float<1>(L, X, o, p, s) : launch_bits_float<2>(L, X, o, p, s);
+    else if (conv) rc = bits == 1 ? launch_bits<1, true>(L, planes, colsum, o, p, ks, s) : launch_bits<2, true>(L, planes, colsum, o, p, ks, s);
     else rc = bits == 1 ? launch_bits<1, false>(L, planes, colsum, o, p, ks, s) : launch_bits<2, false>(L, planes, colsum, o, p, ks, s);
     if (rc != APB_OK) return rc;
     APB_HIP(hipGetLastError());
@@ -735,6 +837,21 @@ int launch_any(const LayerDev& L, const uint32_t* planes, const int32_t* colsum,
 int launch_forward(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                    const ConvShape* conv, float* Y, hipStream_t s) {
     return launch_any(L, planes, colsum, M, bits, step, conv, OutArgs{nullptr, nullptr, Y}, 0, 0.0f, s);
+}
+
+// Quantize + forward in one kernel applies when one workgroup holds every row of the layer (so that no
+// strip of X is quantized twice), the launch fills the chip without splitting K, and the strip's packed
+// words fit the LDS a launch gets without asking.
+bool forward_float_applies(const LayerDev& L, int M, int bits) {
+    const long long Mp = (long long)kWave * ((M + kWave - 1) / kWave);
+    if (L.Np != TN * L.waves) return false;
+    if (ksplit_parts(L, Mp / kWave) != 1) return false;
+    return float_input_lds_bytes(L, bits) <= 64 * 1024;
+}
+
+int launch_forward_float(const LayerDev& L, const float* X, int M, int bits, float step, float* Y, hipStream_t s) {
+    if (!forward_float_applies(L, M, bits)) return APB_ERR_SHAPE;
+    return launch_any(L, nullptr, nullptr, M, bits, step, nullptr, OutArgs{nullptr, nullptr, Y}, 0, 0.0f, s, X);
 }
 
 // packed_out: the next layer's packed activation buffer (K = L.N), fully overwritten.
