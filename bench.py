@@ -30,7 +30,7 @@ VALU_LANE_OPS_PER_S = 256 * 64 * 2.4e9 # 39.3e12 32-bit vector lane-ops/s: the b
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # calibrated against a plain copy of known size (profiles/traffic_C2_pmc.txt says how).
-MEASURED_TRAFFIC_BYTES = {("C2", "k_quantize_pack"): 321.5e6}
+MEASURED_TRAFFIC_BYTES = {("C2", "k_quantize_pack"): 321.5e6, ("C2", "one_kernel_step"): 335.9e6}
 
 
 def parse_args():
@@ -178,7 +178,8 @@ def run_workload(name, steps, warmup, calibration_copy=False):
     # layer and writes Y, nothing else, so its floor is those bytes at the HBM peak.
     one_bytes = 4.0 * K * M + 4.0 * N * M + 4.0 * N * Kw + 12.0 * nnz
     roof_one = {"kernel": "k_sparse_epilogue<.., float input> (quantize + forward in one kernel)", "bound": "hbm",
-                "achieved": one_bytes / (ms_one * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": None,
+                "achieved": one_bytes / (ms_one * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "traffic": MEASURED_TRAFFIC_BYTES.get((name, "one_kernel_step")),
                 "algorithmic_bytes": one_bytes, "ms": ms_one}
     roof_one["frac"] = roof_one["achieved"] / roof_one["peak"]
     roof_two = roof_quant if ms_quant >= ms_fwd else roof_fwd
