@@ -399,7 +399,7 @@ __device__ __forceinline__ uint32_t load_act_word(const uint32_t* __restrict__ p
 // row-major) and leave its packed words in LDS -- lplanes[BITS][Kw2][64] (Kw2 = Kw rounded up to even,
 // the extra row zero) and the column sums lcol[64] -- instead of HBM.  The arithmetic is that of
 // apb_quantize_acts, bit for bit (same code2, same masks).  Waves take the words of K round-robin; a
-// wave's load of one row of X is one contiguous 256-byte segment, 16 of them in flight.
+// wave's load of one row of X is one contiguous 256-byte segment, 32 of them in flight.
 template <int BITS>
 __device__ __forceinline__ void quantize_strip(const float* __restrict__ X, const SparseParams& p, int m, int wave,
                                                int waves, int lane, uint32_t* lplanes, int32_t* lcol) {
@@ -413,22 +413,18 @@ __device__ __forceinline__ void quantize_strip(const float* __restrict__ X, cons
         uint32_t w0 = 0, w1 = 0;
         if (j < p.Kw) {
             const int k0 = 32 * j;
+            float xv[32];                                       // one word of K: 32 independent loads in flight
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                float xv[16];
+            for (int i = 0; i < 32; ++i)
+                xv[i] = __builtin_nontemporal_load((X + (size_t)min(k0 + i, p.K - 1) * p.M) + mc);
 #pragma unroll
-                for (int i = 0; i < 16; ++i)
-                    xv[i] = __builtin_nontemporal_load((X + (size_t)min(k0 + 16 * half + i, p.K - 1) * p.M) + mc);
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int bit = 16 * half + i;
-                    if (BITS == 1) {
-                        w0 |= (xv[i] >= 0.0f ? 1u : 0u) << bit;
-                    } else {
-                        const uint32_t c = code2(xv[i], p.in_inv_step);
-                        w0 |= (c & 1u) << bit;
-                        w1 |= (c >> 1) << bit;
-                    }
+            for (int i = 0; i < 32; ++i) {
+                if (BITS == 1) {
+                    w0 |= (xv[i] >= 0.0f ? 1u : 0u) << i;
+                } else {
+                    const uint32_t c = code2(xv[i], p.in_inv_step);
+                    w0 |= (c & 1u) << i;
+                    w1 |= (c >> 1) << i;
                 }
             }
             const int valid = p.K - k0;
