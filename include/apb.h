@@ -10,9 +10,12 @@
  * matrix of the residuals w - alpha*sign(w) of the few weights whose magnitude
  * lies outside the binarization interval (Eq. 3), and X^ are the activations
  * quantized to 1 bit (+-beta, Sec. IV "1/1") or 2 bits (p*s, p in 0..3,
- * Sec. IV "1/2").  The binary product runs on packed words with
- * logic + popcount (Eqs. 16, 18, 19); the sparse product reads the same packed
- * activations.
+ * Sec. IV "1/2").  Both operands of the binary product stay bit-packed in memory;
+ * it is computed exactly in integers, by default on the matrix cores (each lane
+ * spreads the bits it owns into 4-bit operand slots; the algebra is that of the
+ * paper's and/xor + popcount forms, Eqs. 16, 18, 19, which are kept as the
+ * *_popcount entry points for comparison).  The sparse product reads the same
+ * packed activations.
  *
  * Shapes and names: W is N x K row-major (N output channels, K = C_in*kh*kw),
  * X is K x M row-major (column m = one im2col patch), Y is N x M row-major.
@@ -28,6 +31,16 @@
  *    apb_quantize_acts, the apb_forward* family and apb_gemm_2_2* only enqueue work and return
  *    (none of them allocates, and none records a memset: a caller may capture them in a HIP
  *    graph); apb_compress, apb_layer_export and apb_w2_export synchronize the stream.
+ *  - A packed activation buffer is plain, untyped device memory: it carries no record of the
+ *    K, M and bits it was written with, and the entry points that read one cannot check them
+ *    (a check would need either a device-to-host read on the hot path or a host-side table of
+ *    pointers that a plain copy of the buffer would leave stale).  Passing K, M or bits other
+ *    than the writer's reads a different layout: unspecified numbers, never out of bounds as
+ *    long as the buffer has apb_acts_bytes(K, M, bits) bytes for the values passed.
+ *  - K limits: 3*K < 2^31 everywhere; the matrix-core entry points additionally need every
+ *    partial sum of the binary product exact in a float accumulator: K < 2^24 for 1-bit
+ *    activations, 3*K < 2^24 for 2-bit ones, 9*K < 2^24 for the 2/2 routine (APB_ERR_SHAPE
+ *    beyond; the *_popcount entry points have no such limit).
  *  - Non-finite values in W or X give unspecified numbers but never touch
  *    memory out of bounds (a NaN activation quantizes to code 0 / sign -).
  *  - Distinct layers and buffers may be used from distinct host threads.

@@ -104,6 +104,10 @@ int launch_forward_requant(const LayerDev& L, const uint32_t* planes, const int3
                            const ConvShape* conv, const float* scale, const float* shift, int bits_out,
                            float inv_step_out, uint32_t* packed_out, hipStream_t s);
 
+// true while K * max_weight * max_code < 2^24: the float accumulators of the matrix instruction then hold
+// every partial sum exactly (launchers return APB_ERR_SHAPE otherwise)
+bool mfma_sum_exact(int K, int max_weight, int max_code);
+
 // binary part alone on the matrix cores: the integer part D
 int launch_binary_mfma(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
                        int32_t* out, hipStream_t s);

@@ -21,6 +21,8 @@
 //      (see kCodeBytes), that is four instructions per residual and wave, and no branch.
 // Tiles are filled by dealing rows in order of residual count (see balanced_slots), so the skewed
 // rows of pruned layers are spread over the waves instead of serialising one of them.
+#include <atomic>
+
 #include "apb_fp4_expand.h"
 #include "apb_internal.h"
 
@@ -29,6 +31,7 @@ namespace apb {
 namespace {
 
 constexpr int TN = kRowTile;
+constexpr int kMaxDevices = 64;                                // devices of one process the launchers keep state for
 constexpr int kTablePitch = kChunkK + 4;                       // bytes per column row of the code table
 constexpr int kTableBytes = kWave * kTablePitch;               // one table (see table_buffers for how many a workgroup keeps)
 
@@ -122,6 +125,11 @@ typedef double v8d __attribute__((ext_vector_type(8)));
 // the multiply-adds sit inside the indexed region; the mode is off again when the statement ends.
 // The wait is for everything (lgkmcnt(0)): scalar loads in flight share the counter and may return
 // out of order, so no smaller count would prove that the table reads are back.
+// The index mode rewrites M0, so M0 is on the clobber list: the compiler then keeps no M0-dependent
+// sequence of its own alive across the statement (it warns that M0 is a reserved register, which is the
+// point).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void accumulate8(v16d& acc, v8d& pairs, const uint32_t* k, const double* v,
                                             uint32_t table_off) {
     uint32_t t0, t1;
@@ -157,9 +165,10 @@ __device__ __forceinline__ void accumulate8(v16d& acc, v8d& pairs, const uint32_
         : "s"(k[0]), "s"(k[1]), "s"(k[2]), "s"(k[3]), "s"(k[4]), "s"(k[5]), "s"(k[6]), "s"(k[7]),
           "s"(v[0]), "s"(v[1]), "s"(v[2]), "s"(v[3]), "s"(v[4]), "s"(v[5]), "s"(v[6]), "s"(v[7]),
           "v"(table_off)
-        : "memory");
+        : "memory", "m0");
 #undef APB_SDWA
 }
+#pragma clang diagnostic pop
 
 // NB (1 to 3) blocks of 8 entries starting at block b.  Keys and values of a block sit side by side,
 // so all the scalar loads of a batch leave together and cost one round trip.
@@ -712,9 +721,17 @@ int launch_ksplit(const LayerDev& L, const uint32_t* planes, const int32_t* cols
     const long long blocks = (long long)p.row_groups * (p.Mp / kWave);
     if (blocks > 0x7fffffffLL) return APB_ERR_SHAPE;
     p.blocks = (int)blocks;
-    if (kLds > 64 * 1024)                                       // more LDS than a launch gets without asking
-        APB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_forward_ksplit<BITS, KS, CONV>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
+    if (kLds > 64 * 1024) {                                     // more LDS than a launch gets without asking:
+        static std::atomic<bool> asked[kMaxDevices];            // asked for once per device, not per launch
+        int dev = 0;
+        APB_HIP(hipGetDevice(&dev));
+        if (dev < 0 || dev >= kMaxDevices) return APB_ERR_SHAPE;
+        if (!asked[dev].load(std::memory_order_acquire)) {
+            APB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_forward_ksplit<BITS, KS, CONV>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
+            asked[dev].store(true, std::memory_order_release);
+        }
+    }
     hipLaunchKernelGGL((k_forward_ksplit<BITS, KS, CONV>), dim3((unsigned)p.blocks), dim3(kWave * kChunkWords), kLds, s,
                        planes, colsum, L.rowsum, L.perm, L.seg_ptr, L.ent, L.slot_valsum, L.signT, o.scale, o.shift, o.out,
                        p);
@@ -783,6 +800,7 @@ int ksplit_parts(const LayerDev& L, long long blocks) {
 int launch_any(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                const ConvShape* conv, const OutArgs& o, int out_bits, float out_inv_step, hipStream_t s,
                const float* X = nullptr) {
+    if (!mfma_sum_exact(L.K, 1, bits == 1 ? 1 : 3)) return APB_ERR_SHAPE;
     const int Mp = kWave * ((M + kWave - 1) / kWave);
     SparseParams p;
     p.alpha = (double)L.alpha;
