@@ -62,7 +62,8 @@ typedef enum apb_status {
     APB_ERR_BITS = -3,     /* bits is not 1 or 2                                           */
     APB_ERR_VALUE = -4,    /* delta is NaN; alpha negative or infinite; step not finite or <= 0 */
     APB_ERR_NOMEM = -5,    /* host or device allocation failed                             */
-    APB_ERR_HIP = -6       /* a HIP call failed; see apb_last_hip_error()                  */
+    APB_ERR_HIP = -6,      /* a HIP call failed; see apb_last_hip_error()                  */
+    APB_ERR_SCRATCH = -7   /* apb_quantize_forward_static: sizes beyond the static scratch array */
 } apb_status;
 
 /* Opaque compressed layer.  Holds, in device memory: the sign words, the CSR of
@@ -142,6 +143,23 @@ int apb_quantize_forward(const apb_layer* layer, const float* X, int M, int bits
                          void* stream);
 /* 1 if apb_quantize_forward runs as the single kernel for this layer, M and bits, else 0 (also on bad arguments). */
 int apb_quantize_forward_is_one_kernel(const apb_layer* layer, int M, int bits);
+
+/* For callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and the same Y,
+ * bit for bit, as apb_quantize_forward, without its `packed` workspace: the packed activations
+ * pass through a static array in device memory that belongs to the library
+ * (APB_STATIC_SCRATCH_BYTES bytes on every GPU the library is used on, held until the process
+ * ends).  The call allocates nothing, frees nothing and records no memset.
+ *   - APB_ERR_SCRATCH, and nothing enqueued, if apb_acts_bytes(K, M, bits) exceeds
+ *     APB_STATIC_SCRATCH_BYTES (also for layers that would run as the single kernel).
+ *   - Every call on one GPU uses that GPU's one array: two calls whose work overlaps in time
+ *     on the same GPU (different streams, different host threads) race on it.  Calls on one stream
+ *     are ordered and safe; the array keeps the last call's contents, which the next call
+ *     overwrites or clears as far as it reads them.
+ * Asynchronous on `stream`. */
+#define APB_STATIC_SCRATCH_BYTES (32u << 20)
+int apb_quantize_forward_static(const apb_layer* layer, const float* X, int M, int bits, float step, float* Y,
+                                void* stream);
 
 /* Two layers in a row without the float round trip: Eq. 13 of this layer followed directly by the
  * activation quantizer (Sec. IV) of the layer it feeds, whose K is this layer's N.  The result is

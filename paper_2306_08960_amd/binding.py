@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libapb.so")
 
 EXPORTS = (
     "apb_compress", "apb_layer_info", "apb_layer_export", "apb_layer_free", "apb_acts_bytes",
-    "apb_quantize_acts", "apb_forward", "apb_quantize_forward", "apb_quantize_forward_is_one_kernel", "apb_forward_requant", "apb_forward_conv3x3", "apb_forward_conv3x3_requant",
+    "apb_quantize_acts", "apb_forward", "apb_quantize_forward", "apb_quantize_forward_static", "apb_quantize_forward_is_one_kernel", "apb_forward_requant", "apb_forward_conv3x3", "apb_forward_conv3x3_requant",
     "apb_forward_int", "apb_forward_int_popcount", "apb_forward_popcount",
     "apb_w2_pack", "apb_w2_export", "apb_w2_free", "apb_gemm_2_2_int", "apb_gemm_2_2",
     "apb_strerror", "apb_last_hip_error",
@@ -28,6 +28,8 @@ EXPORTS = (
 
 APB_OK = 0
 APB_ERR_NULL, APB_ERR_SHAPE, APB_ERR_BITS, APB_ERR_VALUE, APB_ERR_NOMEM, APB_ERR_HIP = -1, -2, -3, -4, -5, -6
+APB_ERR_SCRATCH = -7
+APB_STATIC_SCRATCH_BYTES = 32 << 20
 
 _lib: Optional[ctypes.CDLL] = None
 
@@ -65,6 +67,8 @@ def load() -> ctypes.CDLL:
     lib.apb_forward.restype = ci
     lib.apb_quantize_forward.argtypes = [vp, vp, ci, ci, cf, vp, vp, vp]
     lib.apb_quantize_forward.restype = ci
+    lib.apb_quantize_forward_static.argtypes = [vp, vp, ci, ci, cf, vp, vp]
+    lib.apb_quantize_forward_static.restype = ci
     lib.apb_quantize_forward_is_one_kernel.argtypes = [vp, ci, ci]
     lib.apb_quantize_forward_is_one_kernel.restype = ci
     lib.apb_forward_requant.argtypes = [vp, vp, ci, ci, cf, vp, vp, ci, cf, vp, vp]
@@ -249,6 +253,23 @@ def apb_quantize_forward(layer: ApbLayer, X: torch.Tensor, bits: int, step: floa
     _check(load().apb_quantize_forward(layer.handle, _dev_ptr(X, torch.float32, "X"), int(M), int(bits), float(step),
                                        _dev_ptr(packed, torch.int32, "packed"), _dev_ptr(Y, torch.float32, "Y"),
                                        _stream(stream)), "apb_quantize_forward")
+    return Y
+
+
+def apb_quantize_forward_static(layer: ApbLayer, X: torch.Tensor, bits: int, step: float, Y: torch.Tensor,
+                                stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """apb_quantize_forward through the library's static scratch array; allocates nothing (Y is the caller's)."""
+    if X.dim() != 2:
+        raise TypeError("X must be 2-D [K, M]")
+    K, M = X.shape
+    i = apb_layer_info(layer)
+    if i["K"] != K:
+        raise ValueError("X must have the layer's K rows")
+    if tuple(Y.shape) != (i["N"], M):
+        raise ValueError("Y must be [N, M]")
+    _check(load().apb_quantize_forward_static(layer.handle, _dev_ptr(X, torch.float32, "X"), int(M), int(bits),
+                                              float(step), _dev_ptr(Y, torch.float32, "Y"), _stream(stream)),
+           "apb_quantize_forward_static")
     return Y
 
 

@@ -218,13 +218,6 @@ int position_bits(long long n) {
     return b;
 }
 
-bool bad_shape_acts(int K, int M) {
-    if (K <= 0 || M <= 0) return true;
-    if ((long long)K * 3 >= (1LL << 31)) return true;
-    if ((long long)M + kWave >= (1LL << 31)) return true;
-    return false;
-}
-
 }  // namespace
 }  // namespace apb
 
@@ -505,6 +498,7 @@ const char* apb_strerror(int code) {
         case APB_ERR_VALUE: return "bad scalar (delta NaN, alpha negative/infinite, or step not finite and > 0)";
         case APB_ERR_NOMEM: return "out of memory";
         case APB_ERR_HIP: return "a HIP call failed (see apb_last_hip_error)";
+        case APB_ERR_SCRATCH: return "the packed activations of this K, M and bits do not fit the library's static scratch array";
         default: return "unknown apb status";
     }
 }

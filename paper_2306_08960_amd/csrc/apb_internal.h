@@ -47,6 +47,14 @@ struct LayerDev {
 
 void set_last_hip_error(hipError_t e);
 
+// Shapes of an activation matrix the entry points refuse (APB_ERR_SHAPE).
+inline bool bad_shape_acts(int K, int M) {
+    if (K <= 0 || M <= 0) return true;
+    if ((long long)K * 3 >= (1LL << 31)) return true;
+    if ((long long)M + kWave >= (1LL << 31)) return true;
+    return false;
+}
+
 // The 2-bit activation quantizer (Sec. IV "1/2"): p = clamp(rint(x / s), 0, 3) with one float
 // multiply by the precomputed 1/s, ties to even; NaN -> 0.
 __device__ __forceinline__ uint32_t code2(float x, float inv_step) {
