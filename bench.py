@@ -1,20 +1,30 @@
 #!/usr/bin/env python3
 """Benchmark of the APB layer forward pass on one MI355X.
 
-One "step" = the whole per-batch hot path on inputs already resident in HBM:
-apb_quantize_acts (quantize + bit-plane packing) followed by apb_forward (binary product on the
-matrix cores, then CSR part + epilogue).  apb_compress is per-layer offline work and is not timed.
+One "step" = the whole per-batch hot path on inputs already resident in HBM: quantize + bit-plane
+packing of the activations, then the forward (binary product on the matrix cores, residual part,
+epilogue), through the one entry point apb_quantize_forward.  apb_compress is per-layer offline work
+and is not timed.
 
-Prints ONE JSON line.  `value` is (2*N*K*M + 2*nnz*M) / step time, in GOPS, for the workload
-named in config.workload; `roofline` describes the kernel that dominates the step and
-`roofline_forward` the two forward kernels together; `cpu_baseline` is the CPU oracle timed on a bounded
-column sample of the same workload on this machine's host cores.
+Prints ONE JSON line.  `value` is (2*N*K*M + 2*nnz*M) / step time, in GOPS, for the workload named
+in config.workload (default: C5b, the largest layer of the benchmark); `roofline` describes the kernel
+that dominates that step; `others` holds the same measurements for every other benchmark layer;
+`cpu_baseline` is the CPU oracle timed on a bounded column sample of the headline workload on this
+box's host cores.
+
+How times are taken.  `ms_per_step` is the wall clock over the timed steps (launches from Python,
+synchronised on both sides).  Kernel-level figures (`ms_forward`, `ms_quantize`, `ms_step_graph`, every
+`roofline.ms`) are replays of a captured HIP graph that holds several launches, between two HIP events
+recorded on the stream the graph replays on: no host launch gaps, nothing subtracted, nothing
+estimated.  `roofline.traffic` is read from profiles/traffic_<workload>_pmc.txt when that file has a
+figure for the kernel, else null.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -28,9 +38,8 @@ MFMA_FP4_PEAK_TFLOPS = 10100.0         # dense FP4 MFMA, published
 FP64_VECTOR_PEAK_TFLOPS = 78.6         # 256 CUs x 64 lanes x 2.4 GHz x 2 (fused multiply-add)
 VALU_LANE_OPS_PER_S = 256 * 64 * 2.4e9 # 39.3e12 32-bit vector lane-ops/s: the bit-op roof of a popcount formulation
 
-# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# calibrated against a plain copy of known size (profiles/traffic_C2_pmc.txt says how).
-MEASURED_TRAFFIC_BYTES = {("C2", "k_quantize_pack"): 321.5e6, ("C2", "one_kernel_step"): 335.9e6}
+HEADLINE = "C5b"
+NO_GRAPH = False                       # --no-graph
 
 
 def parse_args():
@@ -38,44 +47,119 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="C2", help="name in paper_2306_08960_amd.synth.CONFIGS")
-    ap.add_argument("--all", action="store_true", help="also time every other benchmark layer (reported in 'others')")
+    ap.add_argument("--workload", default=HEADLINE, help="name in paper_2306_08960_amd.synth.CONFIGS")
+    ap.add_argument("--no-others", action="store_true", help="time the headline workload only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="time kernels with a short loop of plain launches between two events instead of graph replays "
+                         "(few dispatches: for rocprofv3 --pmc runs, which serialise every dispatch)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="before the steps, copy X into a buffer of the same size three times: a plain copy kernel of "
                          "known size, against which FETCH_SIZE / WRITE_SIZE of a rocprofv3 --pmc run are scaled")
     ap.add_argument("--sweep", action="store_true",
                     help="square-matrix sweep of the three bitwise products (1/1, 1/2, 2/2; Sec. V protocol): one JSON "
                          "line with the time of the product alone at each size")
-    ap.add_argument("--routine", default="apb", choices=["apb", "gemm_2_2", "chain", "conv_chain"],
-                    help="apb: the APB layer forward (the headline metric); gemm_2_2: the 2-bit x 2-bit "
-                         "product of Sec. IV on the same shapes (weights packed offline)")
+    ap.add_argument("--routine", default="apb",
+                    choices=["apb", "gemm_2_2", "chain", "conv_chain", "popcount_vs_mfma", "peaks", "resnet18",
+                             "rho_sweep", "train"],
+                    help="apb: the APB layer forward (the headline metric); gemm_2_2: the 2-bit x 2-bit product of "
+                         "Sec. IV on the same shapes; chain / conv_chain: a layer inside a network (packed in, packed "
+                         "out); popcount_vs_mfma: the binary part in its two formulations on the same inputs; peaks: "
+                         "register-only instruction-rate probes; resnet18: the 3x3 layers of an ImageNet ResNet-18 as "
+                         "im2col products (Sec. V-B protocol); rho_sweep: forward time against the outlier rate "
+                         "(Sec. V-C crossover); train: the training-side kernels (Sec. III Eqs. 3-9)")
     return ap.parse_args()
 
 
-def time_in_step(quant, fwd, iters, ms_step_plain):
-    """Per-launch times of the two entry points INSIDE the step loop (quantize, forward, quantize, ...),
-    from HIP events recorded on the stream the kernels run on.  Timed alone in a tight loop the quantize
-    kernel looks faster than it is in a pipeline, because part of X then survives in the memory-side
-    cache from one launch to the next.  Every event record costs the stream a couple of microseconds;
-    that cost (the slowdown of this instrumented pass against the plain timed pass, per record) is
-    taken off each interval, so the two figures add up to the plain step time less the launch gap."""
+def graph_ms(fn, reps=None, target_ms=30.0):
+    """Milliseconds per call of fn(): `reps` calls recorded into one HIP graph, which is then replayed between
+    two HIP events on the current stream.  Launches inside a graph follow one another without host gaps, so
+    a kernel of a few microseconds is timed as the GPU runs it; nothing is subtracted from the interval."""
     import torch
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(iters)]
+    for _ in range(3):
+        fn()                                   # first launches load code objects and set launch attributes
+    torch.cuda.synchronize()
+    a, c = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(5):
+        fn()
+    c.record()
+    c.synchronize()
+    rough = max(a.elapsed_time(c) / 5, 1e-3)   # upper estimate (host gaps included), only to size the graph
+    if NO_GRAPH:
+        return rough
+    if reps is None:
+        reps = int(min(50, max(4, 2.0 / rough)))
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(reps):
+            fn()
+    g.replay()
+    torch.cuda.synchronize()
+    replays = int(min(200, max(3, target_ms / (rough * reps))))
+    a.record()
+    for _ in range(replays):
+        g.replay()
+    c.record()
+    c.synchronize()
+    ms = a.elapsed_time(c) / (replays * reps)
+    del g
+    return ms
+
+
+def wall_ms(fn, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        fn()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for a, b_, c in ev:
-        a.record()
-        quant()
-        b_.record()
-        fwd()
-        c.record()
+    for _ in range(steps):
+        fn()
     torch.cuda.synchronize()
-    ms_step_events = (time.perf_counter() - t0) * 1e3 / iters
-    per_record = max(0.0, (ms_step_events - ms_step_plain) / 3.0)
-    tq = sum(a.elapsed_time(b_) for a, b_, c in ev) / iters - per_record
-    tf = sum(b_.elapsed_time(c) for a, b_, c in ev) / iters - per_record
-    return tq, tf, per_record          # ms
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def measured_traffic(workload, kernel_key):
+    """Bytes per launch from profiles/traffic_<workload>_pmc.txt: a line `traffic_bytes <kernel_key> <number>`
+    written from calibrated rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs.  None when there is no such line."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        m = re.match(r"\s*traffic_bytes\s+(\S+)\s+([0-9.eE+]+)", line)
+        if m and m.group(1) == kernel_key:
+            return float(m.group(2))
+    return None
+
+
+def forward_floors(N, K, M, bits, nnz):
+    """Seconds the forward kernel cannot go below: the bytes it must move (sign words, bit-planes, residual
+    entries, Y) at the HBM peak, the binary product at the FP4 matrix-core peak, the residual multiply-adds
+    at the float64 vector peak; and the yardstick the benchmark spec names, the vector-ALU bit-op time of
+    the popcount formulation (per weight word, plane and column one logic op + one accumulating popcount,
+    per residual and column one multiply-add)."""
+    Kw, Mp = (K + 31) // 32, 64 * ((M + 63) // 64)
+    fwd_bytes = 4.0 * N * Kw + 4.0 * bits * Kw * Mp + 4.0 * Mp + 12.0 * nnz + 4.0 * N * M
+    return {"hbm": fwd_bytes / (HBM_PEAK_GBS * 1e9), "mfma_fp4": 2.0 * N * K * M / (MFMA_FP4_PEAK_TFLOPS * 1e12),
+            "fp64_vector": 2.0 * nnz * M / (FP64_VECTOR_PEAK_TFLOPS * 1e12),
+            "valu_bitop_yardstick": (2.0 * bits * N * Kw * M + float(nnz) * M) / VALU_LANE_OPS_PER_S}, fwd_bytes
+
+
+def forward_roofline(N, K, M, bits, nnz, ms, kernel, traffic=None):
+    fl, fwd_bytes = forward_floors(N, K, M, bits, nnz)
+    t = ms * 1e-3
+    if fl["hbm"] >= max(fl["mfma_fp4"], fl["fp64_vector"]):
+        roof = {"bound": "hbm", "achieved": fwd_bytes / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    elif fl["mfma_fp4"] >= fl["fp64_vector"]:
+        roof = {"bound": "mfma", "achieved": 2.0 * N * K * M / t / 1e12, "peak": MFMA_FP4_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    else:
+        roof = {"bound": "alu", "achieved": 2.0 * nnz * M / t / 1e12, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    roof = {"kernel": kernel} | roof
+    roof |= {"frac": roof["achieved"] / roof["peak"], "traffic": traffic, "ms": ms,
+             "floor_us": {k: v * 1e6 for k, v in fl.items() if k != "valu_bitop_yardstick"},
+             "valu_bitop_yardstick_us": fl["valu_bitop_yardstick"] * 1e6,
+             "frac_of_valu_bitop_yardstick": fl["valu_bitop_yardstick"] / t}
+    return roof
 
 
 def run_workload(name, steps, warmup, calibration_copy=False):
@@ -106,92 +190,51 @@ def run_workload(name, steps, warmup, calibration_copy=False):
     def fwd():
         b.apb_forward(layer, packed, M, bits, s, Y=Y)
 
-    def two_calls():
-        quant()
-        fwd()
-
     def one_call():                          # the step: quantize + forward through the single entry point
         b.apb_quantize_forward(layer, Xd, bits, s, packed=packed, Y=Y)
 
-    def timed(fn):
-        for _ in range(warmup):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e3 / steps
-
     one_kernel = b.apb_quantize_forward_is_one_kernel(layer, M, bits)
-    ms_two = timed(two_calls)
-    ms_quant, ms_fwd, ms_event_record = time_in_step(quant, fwd, steps, ms_two)
-    ms_step = timed(one_call)
-    # the single call between events on its stream (same treatment of the record cost as in time_in_step)
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for a, c in ev:
-        a.record()
-        one_call()
-        c.record()
-    torch.cuda.synchronize()
-    per_record = max(0.0, ((time.perf_counter() - t0) * 1e3 / steps - ms_step) / 2.0)
-    ms_one = sum(a.elapsed_time(c) for a, c in ev) / steps - per_record
+    ms_step = wall_ms(one_call, steps, warmup)
+    ms_step_graph = graph_ms(one_call)
+    quant()
+    ms_fwd = graph_ms(fwd)
+    ms_quant = graph_ms(quant)
 
     ops = 2.0 * N * K * M + 2.0 * nnz * M
     Kw, Mp = (K + 31) // 32, 64 * ((M + 63) // 64)
     # quantize: reads X once, writes the bit-planes and the column sums
     quant_bytes = 4.0 * K * M + 4.0 * bits * Kw * Mp + 4.0 * Mp
     roof_quant = {"kernel": "k_quantize_pack", "bound": "hbm", "achieved": quant_bytes / (ms_quant * 1e-3) / 1e9,
-                  "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": MEASURED_TRAFFIC_BYTES.get((name, "k_quantize_pack")),
-                  "algorithmic_bytes": quant_bytes, "ms": ms_quant}
+                  "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": measured_traffic(name, "k_quantize_pack"),
+                  "algorithmic_bytes": quant_bytes, "ms": ms_quant,
+                  "note": "launched alone back to back: where X is smaller than the 256 MB memory-side cache part of "
+                          "it survives between launches; ms_quantize_in_step is the figure inside the step"}
     roof_quant["frac"] = roof_quant["achieved"] / roof_quant["peak"]
-    # forward = one kernel (binary tile on the matrix cores + residual part + epilogue).  Its floor is the
-    # largest of: the bytes it has to move
-    # (sign words, bit-planes, residual entries, Y), the FP4 matrix-core time of the binary product and
-    # the float64 vector time of the residual multiply-adds.
-    fwd_bytes = 4.0 * N * Kw + 4.0 * bits * Kw * Mp + 4.0 * Mp + 12.0 * nnz + 4.0 * N * M
-    t_hbm = fwd_bytes / (HBM_PEAK_GBS * 1e9)
-    t_mfma = 2.0 * N * K * M / (MFMA_FP4_PEAK_TFLOPS * 1e12)
-    t_f64 = 2.0 * nnz * M / (FP64_VECTOR_PEAK_TFLOPS * 1e12)
-    t_fwd = ms_fwd * 1e-3
-    if t_hbm >= max(t_mfma, t_f64):
-        roof_fwd = {"bound": "hbm", "achieved": fwd_bytes / t_fwd / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
-    elif t_mfma >= t_f64:
-        roof_fwd = {"bound": "mfma", "achieved": 2.0 * N * K * M / t_fwd / 1e12, "peak": MFMA_FP4_PEAK_TFLOPS,
-                    "unit": "TFLOP/s"}
-    else:
-        roof_fwd = {"bound": "alu", "achieved": 2.0 * nnz * M / t_fwd / 1e12, "peak": FP64_VECTOR_PEAK_TFLOPS,
-                    "unit": "TFLOP/s"}
-    roof_fwd = {"kernel": "k_sparse_epilogue or k_forward_ksplit (the forward kernel)"} | roof_fwd
-    roof_fwd |= {"frac": roof_fwd["achieved"] / roof_fwd["peak"], "traffic": None, "ms": ms_fwd,
-                 "floor_us": {"hbm": t_hbm * 1e6, "mfma_fp4": t_mfma * 1e6, "fp64_vector": t_f64 * 1e6}}
-    # The roof the benchmark spec names for the forward: the vector-ALU bit-op rate of the popcount
-    # formulation (per weight word, plane and column one logic op + one accumulating popcount; per residual
-    # and column one multiply-add).  The binary part runs on the matrix cores here, so this is a yardstick,
-    # not a bound: the fraction may exceed 1.
-    t_valu = (2.0 * bits * N * Kw * M + float(nnz) * M) / VALU_LANE_OPS_PER_S
-    roof_valu = {"bound": "alu", "what": "VALU bit-op roof of the popcount formulation", "roof_us": t_valu * 1e6,
-                 "achieved": ops / t_fwd / 1e12, "peak": ops / t_valu / 1e12, "unit": "TOP/s", "frac": t_valu / t_fwd}
+    roof_fwd = forward_roofline(N, K, M, bits, nnz, ms_fwd, b.apb_forward_kernel_name(layer, M, bits),
+                                measured_traffic(name, "forward"))
     # Layers of at most 128 rows run the step as ONE kernel (quantize into LDS + forward): it reads X and the
     # layer and writes Y, nothing else, so its floor is those bytes at the HBM peak.
     one_bytes = 4.0 * K * M + 4.0 * N * M + 4.0 * N * Kw + 12.0 * nnz
-    roof_one = {"kernel": "k_sparse_epilogue<.., float input> (quantize + forward in one kernel)", "bound": "hbm",
-                "achieved": one_bytes / (ms_one * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "traffic": MEASURED_TRAFFIC_BYTES.get((name, "one_kernel_step")),
-                "algorithmic_bytes": one_bytes, "ms": ms_one}
+    roof_one = {"kernel": b.apb_forward_kernel_name(layer, M, bits).replace("false>", "true>") +
+                          " (float input: quantize + forward in one kernel)", "bound": "hbm",
+                "achieved": one_bytes / (ms_step_graph * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "traffic": measured_traffic(name, "one_kernel_step"),
+                "algorithmic_bytes": one_bytes, "ms": ms_step_graph}
     roof_one["frac"] = roof_one["achieved"] / roof_one["peak"]
-    roof_two = roof_quant if ms_quant >= ms_fwd else roof_fwd
+    ms_quant_in_step = None if one_kernel else max(0.0, ms_step_graph - ms_fwd)
+    if one_kernel:
+        dominant = roof_one
+    else:                                    # the longer of the two kernels of the step, as timed inside the step
+        dominant = roof_fwd if ms_fwd >= ms_quant_in_step else roof_quant | {
+            "ms": ms_quant_in_step, "achieved": quant_bytes / (ms_quant_in_step * 1e-3) / 1e9,
+            "frac": quant_bytes / (ms_quant_in_step * 1e-3) / 1e9 / HBM_PEAK_GBS}
     res = {
         "workload": name, "N": N, "K": K, "M": M, "act_bits": bits, "nnz": int(nnz),
         "ms_per_step": ms_step, "gops_step": ops / (ms_step * 1e-3) / 1e9, "one_kernel_step": bool(one_kernel),
-        "ms_per_step_two_calls": ms_two,
-        "ms_quantize": ms_quant, "ms_forward": ms_fwd, "ms_event_record_removed": ms_event_record,
+        "ms_step_graph": ms_step_graph, "gops_step_graph": ops / (ms_step_graph * 1e-3) / 1e9,
+        "ms_quantize": ms_quant, "ms_quantize_in_step": ms_quant_in_step, "ms_forward": ms_fwd,
         "gops_forward": ops / (ms_fwd * 1e-3) / 1e9,
-        "roofline": roof_one if one_kernel else roof_two, "roofline_forward": roof_fwd,
-        "roofline_forward_valu_bitop": roof_valu,
-        "roofline_quantize": roof_quant,
+        "roofline": dominant, "roofline_forward": roof_fwd, "roofline_quantize": roof_quant,
     }
     layer.free()
     del Wd, Xd, packed, Y
@@ -221,17 +264,12 @@ def run_gemm_2_2(name, steps, warmup):
     def gemm():
         b.apb_gemm_2_2(w2, packed, M, s, Y=Y)
 
-    for _ in range(warmup):
+    def both():
         quant()
         gemm()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        quant()
-        gemm()
-    torch.cuda.synchronize()
-    ms_step = (time.perf_counter() - t0) * 1e3 / steps
-    ms_quant, ms_gemm, ms_event_record = time_in_step(quant, gemm, steps, ms_step)
+
+    ms_step = wall_ms(both, steps, warmup)
+    ms_quant, ms_gemm = graph_ms(quant), graph_ms(gemm)
     ops = 2.0 * N * K * M
     Kw, Mp = (K + 31) // 32, 64 * ((M + 63) // 64)
     gemm_bytes = 8.0 * N * Kw + 8.0 * Kw * Mp + 4.0 * Mp + 4.0 * N * M
@@ -247,7 +285,7 @@ def run_gemm_2_2(name, steps, warmup):
              "floor_us": {"hbm": t_hbm * 1e6, "mfma_fp4": t_mfma * 1e6}}
     w2.free()
     res = {"workload": name, "N": N, "K": K, "M": M, "ms_per_step": ms_step, "ms_quantize": ms_quant, "ms_gemm": ms_gemm,
-           "ms_event_record_removed": ms_event_record, "gops_step": ops / (ms_step * 1e-3) / 1e9,
+           "gops_step": ops / (ms_step * 1e-3) / 1e9,
            "gops_gemm": ops / t / 1e9, "roofline_gemm": roof}
     del Xd, packed, Y
     torch.cuda.empty_cache()
@@ -282,28 +320,8 @@ def run_chain(name, steps, warmup):
         b.apb_forward(layer, packed, M, bits, s, Y=Y)
         b.apb_quantize_acts(Y, bits_out, step_out, packed=out_b)
 
-    def timed(fn):
-        for _ in range(warmup):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e3 / steps
-
-    ms_chain, ms_two = timed(chained), timed(two_calls)
-    # the chained call alone between HIP events on its stream, the cost of the records taken off as in time_in_step
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for a, c in ev:
-        a.record()
-        chained()
-        c.record()
-    torch.cuda.synchronize()
-    per_record = max(0.0, ((time.perf_counter() - t0) * 1e3 / steps - ms_chain) / 2.0)
-    ms_call = sum(a.elapsed_time(c) for a, c in ev) / steps - per_record
+    ms_chain, ms_two = wall_ms(chained, steps, warmup), wall_ms(two_calls, steps, warmup)
+    ms_call = graph_ms(chained)              # the chained call alone, graph replay between HIP events
     same = bool(torch.equal(out_a, out_b))
     differing = int((out_a != out_b).sum().item())
     ops = 2.0 * N * K * M + 2.0 * nnz * M
@@ -381,30 +399,11 @@ def run_conv_chain(name, steps, warmup):
         b.apb_quantize_acts(X, bits, s, packed=packed)
         b.apb_forward(layer, packed, M, bits, s, Y=Y)
 
-    def timed(fn):
-        for _ in range(warmup):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e3 / steps
-
-    ms_chain, ms_float, ms_explicit = timed(chained), timed(conv_float), timed(explicit)
+    ms_chain, ms_float, ms_explicit = (wall_ms(f, steps, warmup) for f in (chained, conv_float, explicit))
     Y_conv = Y.clone()
     conv_float()
     same = bool(torch.equal(Y, Y_conv))                      # explicit and implicit routes, bit for bit
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for a, c in ev:
-        a.record()
-        chained()
-        c.record()
-    torch.cuda.synchronize()
-    per_record = max(0.0, ((time.perf_counter() - t0) * 1e3 / steps - ms_chain) / 2.0)
-    ms_call = sum(a.elapsed_time(c) for a, c in ev) / steps - per_record
+    ms_call = graph_ms(chained)
     ops = 2.0 * N * K * M + 2.0 * nnz * M
     Kw, Mp, Cw, Nw = (K + 31) // 32, 64 * ((M + 63) // 64), C // 32, (N + 31) // 32
     out_bytes = 4.0 * (bits_out * Nw + 1) * Mp
@@ -544,32 +543,71 @@ def cpu_baseline_2_2(cfg, W, step_w, X, step):
             "sample": f"first {m} of {cfg.M} columns of {cfg.name}, one pass (quantize both operands + product), {dt:.2f} s"}
 
 
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(cfg, W, delta, X, step):
-    """The CPU oracle (quantize, pack, popcount integer part, CSR part, epilogue) on the first
-    columns of the same workload, all host cores this process may use."""
+    """The CPU oracle as it stands, timed on this machine's host cores on the first columns of the workload:
+    the packed forward of the C oracle (popcount integer part over packed words, CSR part, float64 epilogue --
+    the activations are quantized and packed beforehand, outside the timed region, as they are resident
+    and packed for the GPU's forward kernel too) single-threaded and on all cores this process may use, and the
+    numpy quantize + pack step on its own.  The plain dense definition (brute force) is timed on C1."""
     from oracle import apb_oracle as o
     from oracle import capi
+    from paper_2306_08960_amd import synth
     cores = max(1, min(len(os.sched_getaffinity(0)), capi.max_threads()))
     L = o.compress(W, delta)
     nnz = int(L["row_ptr"][-1])
     per_col = 2.0 * cfg.N * cfg.K + 2.0 * nnz
-    target_ops = 60e9 * cores ** 0.5                 # sized for roughly 10-30 s of CPU work
-    m = int(max(64, min(cfg.M, target_ops / per_col)))
+    m = int(max(64, min(cfg.M, 12e9 / per_col)))        # a few seconds single-threaded
     Xs = np.ascontiguousarray(X[:, :m])
-    passes, dt = 0, 0.0
-    while passes == 0 or (dt < 1.0 and passes < 20):    # about 10-30 core-seconds in all
-        t0 = time.perf_counter()
-        c = o.quantize(Xs, cfg.bits, step)
-        packed = o.pack_acts(c, cfg.bits)
-        capi.forward(L, packed, c, cfg.bits, step, threads=cores)
-        dt += time.perf_counter() - t0
-        passes += 1
-    return {"value": per_col * m * passes / dt / 1e9, "unit": "GOPS", "cores": cores, "kind": "oracle",
-            "sample": f"first {m} of {cfg.M} columns of {cfg.name}, {passes} passes (quantize+pack+forward), {dt:.2f} s"}
+    t0 = time.perf_counter()
+    c = o.quantize(Xs, cfg.bits, step)
+    packed = o.pack_acts(c, cfg.bits)
+    dt_pack = time.perf_counter() - t0
+
+    def leg(threads, budget_s, max_passes):
+        passes, dt = 0, 0.0
+        while passes == 0 or (dt < budget_s and passes < max_passes):
+            t0 = time.perf_counter()
+            capi.forward(L, packed, c, cfg.bits, step, threads=threads)
+            dt += time.perf_counter() - t0
+            passes += 1
+        return per_col * m * passes / dt / 1e9, passes, dt
+
+    g1, p1, d1 = leg(1, 0.0, 1)                          # one repetition
+    gN, pN, dN = leg(cores, 3.0, 20)                     # at least three where they are short
+    # the plain definition on C1 (dense float64 product with the reconstructed weights)
+    c1 = synth.CONFIGS["C1"]
+    W1, delta1, X1, step1 = synth.make_layer(c1)
+    a1 = o.default_alpha(W1, delta1)
+    t0 = time.perf_counter()
+    reps = 20
+    for _ in range(reps):
+        o.brute_force(W1, delta1, a1, X1, c1.bits, step1)
+    dt_bf = (time.perf_counter() - t0) / reps
+    return {"value": gN, "unit": "GOPS", "cores": cores, "kind": "oracle", "cpu_model": cpu_model(),
+            "sample": f"first {m} of {cfg.M} columns of {cfg.name}: packed forward of the C oracle (integer part, CSR "
+                      f"part, epilogue), {pN} passes on {cores} threads in {dN:.2f} s",
+            "single_thread": {"value": g1, "unit": "GOPS", "cores": 1,
+                              "sample": f"same columns, {p1} pass in {d1:.2f} s"},
+            "quantize_and_pack_numpy": {"seconds": dt_pack, "sample": f"same columns, once, outside the timed forward"},
+            "brute_force_C1": {"value": 2.0 * c1.N * c1.K * c1.M / dt_bf / 1e9, "unit": "GOPS", "ms": dt_bf * 1e3,
+                               "sample": f"C1 ({c1.N}x{c1.K}, M={c1.M}): dense float64 product with the "
+                                         f"reconstructed weights, mean of {reps} passes (numpy matmul, library threads)"}}
 
 
 def main():
+    global NO_GRAPH
     args = parse_args()
+    NO_GRAPH = args.no_graph
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the layer shards over the columns of X with no "
               "exchange between GPUs, so one GPU shows the whole path). Run with --gpus 1.", file=sys.stderr)
@@ -607,7 +645,6 @@ def main():
             "config": {"workload": f"{cfg.name}: {cfg.note}", "N": cfg.N, "K": cfg.K, "M": cfg.M,
                        "step": "apb_quantize_acts (2 bits) + apb_gemm_2_2, inputs resident in HBM, weights packed offline"},
             "ms_quantize": res["ms_quantize"], "ms_gemm": res["ms_gemm"], "gops_gemm_only": res["gops_gemm"],
-            "ms_event_record_removed": res["ms_event_record_removed"],
             "roofline": roof_q if res["ms_quantize"] >= res["ms_gemm"] else res["roofline_gemm"],
             "roofline_gemm": res["roofline_gemm"], "roofline_quantize": roof_q,
         }
@@ -659,6 +696,10 @@ def main():
         print(json.dumps(out))
         return
 
+    if args.routine != "apb":
+        EXTRA_ROUTINES[args.routine](args)
+        return
+
     res, inputs = run_workload(args.workload, args.steps, args.warmup, args.calibration_copy)
     cfg = inputs[0]
     out = {
@@ -670,32 +711,196 @@ def main():
                    "act_bits": cfg.bits, "outlier_rate": cfg.rho, "nnz": res["nnz"],
                    "step": "apb_quantize_forward (= apb_quantize_acts + apb_forward; one kernel for layers of at most "
                            "128 rows), inputs resident in HBM", "one_kernel_step": res["one_kernel_step"]},
-        "ms_per_step_two_calls": res["ms_per_step_two_calls"],
-        "ms_quantize": res["ms_quantize"], "ms_forward": res["ms_forward"],
-        "ms_event_record_removed": res["ms_event_record_removed"],
-        "gops_forward_only": res["gops_forward"],
+        "ms_step_graph": res["ms_step_graph"], "gops_step_graph": res["gops_step_graph"],
+        "ms_quantize": res["ms_quantize"], "ms_quantize_in_step": res["ms_quantize_in_step"],
+        "ms_forward": res["ms_forward"], "gops_forward_only": res["gops_forward"],
         "roofline": res["roofline"], "roofline_forward": res["roofline_forward"],
-        "roofline_forward_valu_bitop": res["roofline_forward_valu_bitop"],
         "roofline_quantize": res["roofline_quantize"],
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(*inputs)
     del inputs
-    if args.all:
+    if not args.no_others:
         others = []
         for name in synth.CONFIGS:
             if name == args.workload:
                 continue
             r, _ = run_workload(name, max(20, args.steps // 4), max(5, args.warmup // 4))
+            rf = r["roofline_forward"]
             others.append({k: r[k] for k in ("workload", "N", "K", "M", "act_bits", "nnz", "ms_per_step", "gops_step",
-                                             "one_kernel_step", "ms_per_step_two_calls",
-                                             "ms_quantize", "ms_forward", "gops_forward")}
-                          | {"forward_frac_of_valu_bitop_roof": r["roofline_forward_valu_bitop"]["frac"],
-                             "forward_bound": r["roofline_forward"]["bound"],
-                             "forward_frac_of_roof": r["roofline_forward"]["frac"],
+                                             "one_kernel_step", "ms_step_graph", "gops_step_graph", "ms_quantize",
+                                             "ms_quantize_in_step", "ms_forward", "gops_forward")}
+                          | {"roofline": {k: r["roofline"][k] for k in ("kernel", "bound", "achieved", "peak", "unit",
+                                                                        "frac", "traffic", "ms")},
+                             "roofline_forward": {k: rf[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic",
+                                                                     "ms", "floor_us", "frac_of_valu_bitop_yardstick")},
                              "quantize_frac_of_hbm_roof": r["roofline_quantize"]["frac"]})
         out["others"] = others
     print(json.dumps(out))
+
+
+def routine_popcount_vs_mfma(args):
+    """The binary part in its two formulations on the same packed inputs: the paper's and/xor + popcount on the
+    vector ALU (apb_forward_int_popcount) against the FP4 matrix-core kernel (apb_forward_int), and the whole
+    forward built on each (apb_forward_popcount, apb_forward).  The two integer results must be equal."""
+    import torch
+    from paper_2306_08960_amd import binding as b
+    from paper_2306_08960_amd import synth
+    rows = []
+    for name in ("C2", "C3_r20_b1", "C3_r20_b2", "C4", "C5a", "C5b"):
+        cfg = synth.CONFIGS[name]
+        W, delta, X, step = synth.make_layer(cfg)
+        N, K, M, bits = cfg.N, cfg.K, cfg.M, cfg.bits
+        layer = b.apb_compress(torch.from_numpy(W).cuda(), float(delta))
+        nnz = layer.info()["nnz"]
+        packed = b.apb_quantize_acts(torch.from_numpy(X).cuda(), bits, float(step))
+        D1 = torch.empty((N, M), dtype=torch.int32, device="cuda")
+        D2 = torch.empty((N, M), dtype=torch.int32, device="cuda")
+        Y = torch.empty((N, M), dtype=torch.float32, device="cuda")
+        t_pop = graph_ms(lambda: b.apb_forward_int_popcount(layer, packed, M, bits, D=D1))
+        t_mfma = graph_ms(lambda: b.apb_forward_int(layer, packed, M, bits, D=D2))
+        t_fpop = graph_ms(lambda: b.apb_forward_popcount(layer, packed, M, bits, float(step), Y=Y))
+        t_fwd = graph_ms(lambda: b.apb_forward(layer, packed, M, bits, float(step), Y=Y))
+        Kw = (K + 31) // 32
+        t_valu_roof = 2.0 * bits * N * Kw * M / VALU_LANE_OPS_PER_S
+        rows.append({"workload": name, "N": N, "K": K, "M": M, "act_bits": bits, "nnz": int(nnz),
+                     "integer_results_equal": bool(torch.equal(D1, D2)),
+                     "us_int_popcount": t_pop * 1e3, "us_int_matrix_cores": t_mfma * 1e3,
+                     "us_forward_popcount": t_fpop * 1e3, "us_forward": t_fwd * 1e3,
+                     "popcount_frac_of_its_valu_bitop_roof": t_valu_roof / (t_pop * 1e-3),
+                     "matrix_cores_frac_of_fp4_peak": 2.0 * N * K * M / (t_mfma * 1e-3) / (MFMA_FP4_PEAK_TFLOPS * 1e12)})
+        layer.free()
+        del packed, D1, D2, Y
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "binary part of the APB forward: popcount on the vector ALU vs FP4 matrix cores",
+                      "unit": "us per launch (graph replay between HIP events)", "n_gpus": 1, "data": "synthetic",
+                      "rows": rows}))
+
+
+def routine_peaks(args):
+    """What the chip sustains for the instruction mixes of the forward kernels, register-only loops."""
+    import torch
+    from paper_2306_08960_amd import binding as b
+    out = torch.empty(b.apb_probe_out_bytes() // 8, dtype=torch.float64, device="cuda")
+    published = {"mfma_fp4": (MFMA_FP4_PEAK_TFLOPS * 1e12, "flop/s (2 per multiply-add), dense FP4"),
+                 "mfma_i8": (5.0e15, "op/s (2 per multiply-add), dense int8"),
+                 "and_bcnt": (VALU_LANE_OPS_PER_S, "32-bit vector lane-ops/s (256 CUs x 64 lanes x 2.4 GHz)"),
+                 "fma_f64": (VALU_LANE_OPS_PER_S, "float64 multiply-add lane-ops/s (78.6 TFLOP/s / 2)"),
+                 "lds_u8": (256 * 32 * 2.4e9, "LDS lane-reads/s at 32 banks per compute unit and cycle")}
+    rows = []
+    for name, kind in b.PROBES.items():
+        iters = 2048
+        work = b.apb_probe_rate(kind, iters, out)
+        torch.cuda.synchronize()
+        a, c = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(5):
+            b.apb_probe_rate(kind, iters, out)
+        c.record()
+        c.synchronize()
+        rate = work / (a.elapsed_time(c) / 5 * 1e-3)
+        rows.append({"probe": name, "measured_per_s": rate, "published_or_derived_per_s": published[name][0],
+                     "unit": published[name][1], "frac": rate / published[name][0],
+                     "ms_per_launch": a.elapsed_time(c) / 5})
+    print(json.dumps({"metric": "register-only instruction-rate probes", "n_gpus": 1, "rows": rows}))
+
+
+# The 3x3 convolutions of an ImageNet ResNet-18 as im2col products: (name, N = C_out, C_in, output H = W, stride).
+RESNET18_3X3 = [("layer1.x (64->64 @56)", 64, 64, 56, 1), ("layer2.0.conv1 (64->128 @28, stride 2)", 128, 64, 28, 2),
+                ("layer2.x (128->128 @28)", 128, 128, 28, 1), ("layer3.0.conv1 (128->256 @14, stride 2)", 256, 128, 14, 2),
+                ("layer3.x (256->256 @14)", 256, 256, 14, 1), ("layer4.0.conv1 (256->512 @7, stride 2)", 512, 256, 7, 2),
+                ("layer4.x (512->512 @7)", 512, 512, 7, 1)]
+
+
+def routine_resnet18(args):
+    """Sec. V-B protocol on the shapes Sec. V-C evaluates: every 3x3 layer of an ImageNet ResNet-18 as the
+    im2col product N x K x M (K = 9 C_in, M = batch * H_out * W_out; the first 7x7 layer, the 1x1 downsampling
+    layers and the classifier are left out as in the paper): the three bitwise products alone (operands
+    packed) and the APB layer forward (2-bit activations, 2 % of the weights outside the interval)."""
+    import torch
+    from paper_2306_08960_amd import binding as b
+    from paper_2306_08960_amd import synth
+    batch = 64
+    rows = []
+    for idx, (lname, N, Cin, Hout, stride) in enumerate(RESNET18_3X3):
+        K, M = 9 * Cin, batch * Hout * Hout
+        W, delta, X, step = synth.random_case(1800 + idx, N, K, M, 2, rho=0.02)
+        Wd, Xd = torch.from_numpy(W).cuda(), torch.from_numpy(X).cuda()
+        apb = b.apb_compress(Wd, float(delta))
+        binl = b.apb_compress(Wd, float("inf"), alpha=0.05)
+        w2 = b.apb_w2_pack(Wd, 0.05)
+        nnz = apb.info()["nnz"]
+        p1 = b.apb_quantize_acts(Xd - 0.5, 1, 1.0)
+        p2 = b.apb_quantize_acts(Xd, 2, float(step))
+        D = torch.empty((N, M), dtype=torch.int32, device="cuda")
+        Y = torch.empty((N, M), dtype=torch.float32, device="cuda")
+        t11 = graph_ms(lambda: b.apb_forward_int(binl, p1, M, 1, D=D))
+        t12 = graph_ms(lambda: b.apb_forward_int(binl, p2, M, 2, D=D))
+        t22 = graph_ms(lambda: b.apb_gemm_2_2_int(w2, p2, M, D=D))
+        tf = graph_ms(lambda: b.apb_forward(apb, p2, M, 2, float(step), Y=Y))
+        tq = graph_ms(lambda: b.apb_quantize_acts(Xd, 2, float(step), packed=p2))
+        ops = 2.0 * N * K * M
+        roof = forward_roofline(N, K, M, 2, nnz, tf, "the forward kernel")
+        rows.append({"layer": lname, "N": N, "K": K, "M": M, "nnz": int(nnz), "us_1_1": t11 * 1e3, "us_1_2": t12 * 1e3,
+                     "us_2_2": t22 * 1e3, "us_apb_forward": tf * 1e3, "us_quantize": tq * 1e3,
+                     "tops_1_1": ops / t11 / 1e9, "tops_1_2": ops / t12 / 1e9, "tops_2_2": ops / t22 / 1e9,
+                     "tops_apb_forward": (ops + 2.0 * nnz * M) / tf / 1e9,
+                     "cost_1_2_over_1_1": t12 / t11, "cost_2_2_over_1_1": t22 / t11, "cost_apb_over_1_2": tf / t12,
+                     "apb_forward_bound": roof["bound"], "apb_forward_frac_of_roof": roof["frac"],
+                     "apb_forward_frac_of_valu_bitop_yardstick": roof["frac_of_valu_bitop_yardstick"]})
+        for h in (apb, binl, w2):
+            h.free()
+        del Wd, Xd, p1, p2, D, Y
+        torch.cuda.empty_cache()
+    total = {k: sum(r[k] for r in rows) for k in ("us_1_1", "us_1_2", "us_2_2", "us_apb_forward")}
+    print(json.dumps({"metric": "3x3 layers of ResNet-18 (ImageNet shapes) as im2col products: bitwise products and APB forward",
+                      "unit": "us per launch (graph replay between HIP events); TOPS = 2*N*K*M (+ 2*nnz*M) / time",
+                      "n_gpus": 1, "data": "synthetic", "batch": batch,
+                      "note": "one row per distinct shape (layer1/2/3/4.x occur 4/3/3/3 times in the network)",
+                      "rows": rows, "sum_over_shapes_us": total}))
+
+
+def routine_rho_sweep(args):
+    """Sec. V-C crossover: the forward of the C3 layer (256 x 2304, M = 8192) against the fraction rho of
+    weights kept outside the binarization interval, for 1-bit and 2-bit activations.  The time of the residual
+    part is forward(rho) - forward(0); it equals the binary part's at the rate `crossover_rho` (interpolated)."""
+    import torch
+    from dataclasses import replace
+    from paper_2306_08960_amd import binding as b
+    from paper_2306_08960_amd import synth
+    rates = (0.0, 0.005, 0.01, 0.02, 0.03, 0.04, 0.05, 0.06, 0.08)
+    out = {}
+    for bits in (1, 2):
+        base = synth.CONFIGS[f"C3_r20_b{bits}"]
+        W, _ = synth.make_weights(base)
+        X = synth.make_acts(base)
+        Wd = torch.from_numpy(W).cuda()
+        packed = b.apb_quantize_acts(torch.from_numpy(X).cuda(), bits, float(base.step))
+        Y = torch.empty((base.N, base.M), dtype=torch.float32, device="cuda")
+        rows = []
+        for rho in rates:
+            delta = float("inf") if rho == 0.0 else float(synth._delta_for_rate(W, rho))
+            layer = b.apb_compress(Wd, delta)
+            nnz = layer.info()["nnz"]
+            t = graph_ms(lambda: b.apb_forward(layer, packed, base.M, bits, float(base.step), Y=Y))
+            rows.append({"rho": rho, "nnz": int(nnz), "us_forward": t * 1e3})
+            layer.free()
+        t0 = rows[0]["us_forward"]
+        cross = None
+        for r0, r1 in zip(rows, rows[1:]):
+            s0, s1 = r0["us_forward"] - t0, r1["us_forward"] - t0
+            r0["us_residual_part"], r1["us_residual_part"] = s0, s1
+            if cross is None and s0 < t0 <= s1:
+                cross = r0["rho"] + (r1["rho"] - r0["rho"]) * (t0 - s0) / (s1 - s0)
+        out[f"act_bits_{bits}"] = {"us_binary_part": t0, "rows": rows, "crossover_rho": cross,
+                                   "crossover_sparsity_percent": None if cross is None else 100.0 * (1.0 - cross)}
+    print(json.dumps({"metric": "APB forward time against the outlier rate (C3 shape, N=256 K=2304 M=8192)",
+                      "unit": "us per launch (graph replay between HIP events)", "n_gpus": 1, "data": "synthetic",
+                      "sweep": out}))
+
+
+EXTRA_ROUTINES = {"popcount_vs_mfma": routine_popcount_vs_mfma, "peaks": routine_peaks, "resnet18": routine_resnet18,
+                  "rho_sweep": routine_rho_sweep}
 
 
 if __name__ == "__main__":

@@ -129,6 +129,10 @@ int apb_quantize_acts(const float* X, int K, int M, int bits, float step, void* 
  * Asynchronous on `stream`. */
 int apb_forward(const apb_layer* layer, const void* packed, int M, int bits, float step, float* Y, void* stream);
 
+/* The kernel apb_forward launches for this layer, M and bits, by the name a profiler shows for it
+ * (a static string; "" on bad arguments).  For matching benchmark figures with profiler output. */
+const char* apb_forward_kernel_name(const apb_layer* layer, int M, int bits);
+
 /* apb_quantize_acts followed by apb_forward as ONE call, with the same Y bit for bit.  For layers of at
  * most 128 rows (one workgroup then holds every row, so no strip of X is quantized twice) whose K fits
  * the on-chip memory, a single kernel reads X, keeps the packed codes of its 64 columns on chip and
@@ -247,6 +251,30 @@ void apb_w2_free(apb_w2* w2);
  * Asynchronous on `stream`. */
 int apb_gemm_2_2_int(const apb_w2* w2, const void* packed, int M, int32_t* D, void* stream);
 int apb_gemm_2_2(const apb_w2* w2, const void* packed, int M, float step_a, float* Y, void* stream);
+
+/* ---- Measurement support: instruction-rate probes ---------------------------------------------
+ *
+ * The roofs this library's kernels are priced against (Sec. IV derives the paper's own "theoretical
+ * peak performance" from the instruction mix of its routines; this is the same exercise for this
+ * chip) come from the data sheet and, beside it, from what the chip sustains for each mix in a
+ * register-only loop.  apb_probe_rate launches one such loop: 2048 workgroups of 256 lanes, `iters`
+ * passes, no memory traffic but one word per lane at the end.
+ *   kind             which mix (below); APB_ERR_VALUE for another value.
+ *   iters            1 .. 2^20 loop passes per lane.
+ *   out              DEVICE, apb_probe_out_bytes() bytes of scratch, overwritten.
+ *   work_per_launch  HOST, receives the work of one launch in the unit of the mix: multiply-add
+ *                    flops (2 per product) for the two matrix probes, lane operations for the
+ *                    vector and LDS probes.
+ * Asynchronous on `stream`. */
+enum {
+    APB_PROBE_MFMA_FP4 = 0,   /* v_mfma_scale_f32_32x32x64_f8f6f4 with FP4 operands                    */
+    APB_PROBE_MFMA_I8 = 1,    /* v_mfma_i32_32x32x32_i8                                               */
+    APB_PROBE_AND_BCNT = 2,   /* v_and_b32 + v_bcnt_u32_b32: the popcount formulation's pair           */
+    APB_PROBE_FMA_F64 = 3,    /* v_fma_f64: the residual part's multiply-add                          */
+    APB_PROBE_LDS_U8 = 4      /* ds_read_u8 from a 260-byte-pitch table, one column for all lanes      */
+};
+size_t apb_probe_out_bytes(void);
+int apb_probe_rate(int kind, int iters, void* out, double* work_per_launch, void* stream);
 
 const char* apb_strerror(int code);
 int apb_last_hip_error(void);

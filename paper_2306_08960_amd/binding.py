@@ -20,9 +20,10 @@ LIB_PATH = os.path.join(_HERE, "libapb.so")
 
 EXPORTS = (
     "apb_compress", "apb_layer_info", "apb_layer_export", "apb_layer_free", "apb_acts_bytes",
-    "apb_quantize_acts", "apb_forward", "apb_quantize_forward", "apb_quantize_forward_static", "apb_quantize_forward_is_one_kernel", "apb_forward_requant", "apb_forward_conv3x3", "apb_forward_conv3x3_requant",
+    "apb_quantize_acts", "apb_forward", "apb_forward_kernel_name", "apb_quantize_forward", "apb_quantize_forward_static", "apb_quantize_forward_is_one_kernel", "apb_forward_requant", "apb_forward_conv3x3", "apb_forward_conv3x3_requant",
     "apb_forward_int", "apb_forward_int_popcount", "apb_forward_popcount",
     "apb_w2_pack", "apb_w2_export", "apb_w2_free", "apb_gemm_2_2_int", "apb_gemm_2_2",
+    "apb_probe_out_bytes", "apb_probe_rate",
     "apb_strerror", "apb_last_hip_error",
 )
 
@@ -67,6 +68,8 @@ def load() -> ctypes.CDLL:
     lib.apb_forward.restype = ci
     lib.apb_quantize_forward.argtypes = [vp, vp, ci, ci, cf, vp, vp, vp]
     lib.apb_quantize_forward.restype = ci
+    lib.apb_forward_kernel_name.argtypes = [vp, ci, ci]
+    lib.apb_forward_kernel_name.restype = ctypes.c_char_p
     lib.apb_quantize_forward_static.argtypes = [vp, vp, ci, ci, cf, vp, vp]
     lib.apb_quantize_forward_static.restype = ci
     lib.apb_quantize_forward_is_one_kernel.argtypes = [vp, ci, ci]
@@ -93,6 +96,10 @@ def load() -> ctypes.CDLL:
     lib.apb_gemm_2_2_int.restype = ci
     lib.apb_gemm_2_2.argtypes = [vp, vp, ci, cf, vp, vp]
     lib.apb_gemm_2_2.restype = ci
+    lib.apb_probe_out_bytes.argtypes = []
+    lib.apb_probe_out_bytes.restype = ctypes.c_size_t
+    lib.apb_probe_rate.argtypes = [ci, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
+    lib.apb_probe_rate.restype = ci
     lib.apb_strerror.argtypes = [ci]
     lib.apb_strerror.restype = ctypes.c_char_p
     lib.apb_last_hip_error.argtypes = []
@@ -254,6 +261,10 @@ def apb_quantize_forward(layer: ApbLayer, X: torch.Tensor, bits: int, step: floa
                                        _dev_ptr(packed, torch.int32, "packed"), _dev_ptr(Y, torch.float32, "Y"),
                                        _stream(stream)), "apb_quantize_forward")
     return Y
+
+
+def apb_forward_kernel_name(layer: ApbLayer, M: int, bits: int) -> str:
+    return load().apb_forward_kernel_name(layer.handle, int(M), int(bits)).decode()
 
 
 def apb_quantize_forward_static(layer: ApbLayer, X: torch.Tensor, bits: int, step: float, Y: torch.Tensor,
@@ -462,3 +473,22 @@ def apb_gemm_2_2(w2: ApbW2, packed: torch.Tensor, M: int, step_a: float, Y: Opti
     _check(load().apb_gemm_2_2(w2.handle, _dev_ptr(packed, torch.int32, "packed"), int(M), float(step_a),
                                _dev_ptr(Y, torch.float32, "Y"), _stream(stream)), "apb_gemm_2_2")
     return Y
+
+
+# ----------------------------------------------------------------------------- instruction-rate probes
+
+PROBES = {"mfma_fp4": 0, "mfma_i8": 1, "and_bcnt": 2, "fma_f64": 3, "lds_u8": 4}
+
+
+def apb_probe_out_bytes() -> int:
+    return int(load().apb_probe_out_bytes())
+
+
+def apb_probe_rate(kind: int, iters: int, out: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> float:
+    """Launch one probe; returns the work of the launch (flops or lane operations)."""
+    if out.numel() * out.element_size() < apb_probe_out_bytes():
+        raise ValueError("out smaller than apb_probe_out_bytes()")
+    work = ctypes.c_double()
+    _check(load().apb_probe_rate(int(kind), int(iters), out.data_ptr(), ctypes.byref(work), _stream(stream)),
+           "apb_probe_rate")
+    return work.value

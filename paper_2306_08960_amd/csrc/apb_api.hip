@@ -346,6 +346,11 @@ int apb_forward_requant(const apb_layer* layer, const void* packed, int M, int b
     return launch_forward_requant(d, planes, colsum, M, bits, step, nullptr, scale, shift, bits_out, 1.0f / step_out, out, s);
 }
 
+const char* apb_forward_kernel_name(const apb_layer* layer, int M, int bits) {
+    if (!layer || M <= 0 || (bits != 1 && bits != 2)) return "";
+    return forward_kernel_name(layer->d, M, bits);
+}
+
 int apb_quantize_forward_is_one_kernel(const apb_layer* layer, int M, int bits) {
     if (!layer || M <= 0 || (bits != 1 && bits != 2)) return 0;
     return forward_float_applies(layer->d, M, bits) ? 1 : 0;

@@ -102,6 +102,7 @@ struct ConvShape {
 };
 int launch_forward(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                    const ConvShape* conv, float* Y, hipStream_t s);
+const char* forward_kernel_name(const LayerDev& L, int M, int bits);
 // quantize + forward in one kernel, from the float matrix X (K x M): same Y, bit for bit, as launch_quantize +
 // launch_forward; only where forward_float_applies says so (APB_ERR_SHAPE otherwise)
 bool forward_float_applies(const LayerDev& L, int M, int bits);

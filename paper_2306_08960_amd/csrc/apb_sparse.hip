@@ -868,6 +868,20 @@ int launch_forward_float(const LayerDev& L, const float* X, int M, int bits, flo
     return launch_any(L, nullptr, nullptr, M, bits, step, nullptr, OutArgs{nullptr, nullptr, Y}, 0, 0.0f, s, X);
 }
 
+// Name of the kernel launch_forward picks for this layer, M and bits, as a profiler prints it (template
+// arguments: bits; words per wave or parts of K; implicit im2col; float input).
+const char* forward_kernel_name(const LayerDev& L, int M, int bits) {
+    const long long Mp = (long long)kWave * ((M + kWave - 1) / kWave);
+    const int ks = ksplit_parts(L, (long long)(L.Np / (TN * L.waves)) * (Mp / kWave));
+    if (ks == 4) return bits == 1 ? "k_forward_ksplit<1, 4, false>" : "k_forward_ksplit<2, 4, false>";
+    if (ks == 2) return bits == 1 ? "k_forward_ksplit<1, 2, false>" : "k_forward_ksplit<2, 2, false>";
+    switch (L.waves) {
+        case 8: return bits == 1 ? "k_sparse_epilogue<1, 1, false, false>" : "k_sparse_epilogue<2, 1, false, false>";
+        case 4: return bits == 1 ? "k_sparse_epilogue<1, 2, false, false>" : "k_sparse_epilogue<2, 2, false, false>";
+        default: return bits == 1 ? "k_sparse_epilogue<1, 4, false, false>" : "k_sparse_epilogue<2, 4, false, false>";
+    }
+}
+
 // packed_out: the next layer's packed activation buffer (K = L.N), fully overwritten.
 int launch_forward_requant(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                            const ConvShape* conv, const float* scale, const float* shift, int bits_out,
