@@ -899,8 +899,36 @@ def routine_rho_sweep(args):
                       "sweep": out}))
 
 
+def routine_train(args):
+    """The training-side operators (Sec. III Eqs. 3-9) on the latent weights of a layer the size of C5a's
+    (4096 x 4096) and of a whole ResNet-18's worth of 3x3 weights (11 M): HBM-bound, one pass each."""
+    import torch
+    from paper_2306_08960_amd import binding as b
+    rows = []
+    for label, n in (("C5a latent weights 4096x4096", 4096 * 4096), ("64 Mi weights", 1 << 26), ("256 Mi weights", 1 << 28)):
+        g = torch.Generator(device="cuda").manual_seed(230608960)
+        W = torch.randn(n, generator=g, device="cuda") * 0.05
+        G = torch.randn(n, generator=g, device="cuda")
+        out, gw = torch.empty_like(W), torch.empty_like(W)
+        sums = torch.empty(2, dtype=torch.float64, device="cuda")
+        cnt = torch.empty(1, dtype=torch.int64, device="cuda")
+        ws = torch.empty(b.apb_train_workspace_bytes() // 8, dtype=torch.float64, device="cuda")
+        tf = graph_ms(lambda: b.apb_train_forward(W, 0.04, 0.06, out=out))
+        tb = graph_ms(lambda: b.apb_train_backward(W, G, 0.04, 0.06, grad_w=gw, sums=sums, count=cnt, workspace=ws))
+        tb2 = graph_ms(lambda: b.apb_train_backward(W, G, 0.04, 0.06, want_grad_w=False, sums=sums, count=cnt, workspace=ws))
+        rows.append({"what": label, "n": n,
+                     "forward": {"ms": tf, "algorithmic_bytes": 8.0 * n, "GBps": 8.0 * n / tf / 1e6, "frac_of_hbm_peak": 8.0 * n / tf / 1e6 / HBM_PEAK_GBS},
+                     "backward": {"ms": tb, "algorithmic_bytes": 12.0 * n, "GBps": 12.0 * n / tb / 1e6, "frac_of_hbm_peak": 12.0 * n / tb / 1e6 / HBM_PEAK_GBS},
+                     "backward_reductions_only": {"ms": tb2, "algorithmic_bytes": 8.0 * n, "GBps": 8.0 * n / tb2 / 1e6, "frac_of_hbm_peak": 8.0 * n / tb2 / 1e6 / HBM_PEAK_GBS}})
+        del W, G, out, gw
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "APB training-side operators (Eq. 3 forward; straight-through gradient + dL/dalpha, dL/ddelta)",
+                      "unit": "ms per call (graph replay between HIP events); GB/s of algorithmic bytes against 8 TB/s",
+                      "n_gpus": 1, "data": "synthetic", "rows": rows}))
+
+
 EXTRA_ROUTINES = {"popcount_vs_mfma": routine_popcount_vs_mfma, "peaks": routine_peaks, "resnet18": routine_resnet18,
-                  "rho_sweep": routine_rho_sweep}
+                  "rho_sweep": routine_rho_sweep, "train": routine_train}
 
 
 if __name__ == "__main__":

@@ -252,6 +252,37 @@ void apb_w2_free(apb_w2* w2);
 int apb_gemm_2_2_int(const apb_w2* w2, const void* packed, int M, int32_t* D, void* stream);
 int apb_gemm_2_2(const apb_w2* w2, const void* packed, int M, float step_a, float* Y, void* stream);
 
+/* ---- Sec. III Eqs. 3-9: the training-side operators of one layer ---------------------------------
+ *
+ * During training the layer keeps full-precision latent weights and two learned scalars: alpha, the
+ * scale of the binarized weights, and delta, how far the binarization interval reaches beyond alpha
+ * (the interval is |w| <= alpha + delta; apb_compress takes that sum as its `delta` argument).
+ *
+ * apb_train_forward: Eq. 3 element-wise on the latent weights,
+ *      out[i] = sign(W[i]) * alpha  if |W[i]| <= alpha + delta (float compare against the float sum),
+ *               W[i]                otherwise;       sign(0) = + (Eq. 1).
+ * apb_train_backward: given the upstream gradient G (dL/dAPB(w), what backpropagation delivers),
+ *      grad_w[i]   = G[i]                                  Eq. 4 with the identity as surrogate: the
+ *                                                          straight-through gradient of the latent weight
+ *      dL/dw_hat_i = delta * sign(W[i]) * G[i]             Eq. 9 solved for dL/dw_hat
+ *      chi_B,i     = 1 if |W[i]| <= alpha + delta else 0   Eq. 6
+ *      grad_alpha  = -1 / (delta * n)   * sum_i dL/dw_hat_i * chi_B,i                    Eq. 8
+ *      grad_delta  =  1 / (delta^2 * n) * sum_i dL/dw_hat_i * (alpha - |W[i]|) * chi_B,i Eq. 7
+ *   with n the number of weights.  Terms and sums are float64; the sums are deterministic (fixed
+ *   partition, fixed order), so two calls on the same inputs give the same bits.
+ *   W, G              DEVICE, n floats each, read-only.      n in 1 .. 2^40 - 1.
+ *   alpha, delta      finite, alpha >= 0; delta >= 0 (forward), delta > 0 (backward).
+ *   out / grad_w      DEVICE, n floats, fully overwritten; grad_w may be NULL (the latent gradient is G
+ *                     itself) and may alias G.
+ *   grad_alpha_delta  DEVICE, 2 doubles: [0] = grad_alpha, [1] = grad_delta.
+ *   n_binarized       DEVICE, 1 int64 (the size of the binarized set), or NULL.
+ *   workspace         DEVICE, apb_train_workspace_bytes() bytes of scratch, 8-byte aligned.
+ * Asynchronous on `stream`; no allocation, no memset. */
+size_t apb_train_workspace_bytes(void);
+int apb_train_forward(const float* W, long long n, float alpha, float delta, float* out, void* stream);
+int apb_train_backward(const float* W, const float* G, long long n, float alpha, float delta, float* grad_w,
+                       double* grad_alpha_delta, long long* n_binarized, void* workspace, void* stream);
+
 /* ---- Measurement support: instruction-rate probes ---------------------------------------------
  *
  * The roofs this library's kernels are priced against (Sec. IV derives the paper's own "theoretical

@@ -23,6 +23,7 @@ EXPORTS = (
     "apb_quantize_acts", "apb_forward", "apb_forward_kernel_name", "apb_quantize_forward", "apb_quantize_forward_static", "apb_quantize_forward_is_one_kernel", "apb_forward_requant", "apb_forward_conv3x3", "apb_forward_conv3x3_requant",
     "apb_forward_int", "apb_forward_int_popcount", "apb_forward_popcount",
     "apb_w2_pack", "apb_w2_export", "apb_w2_free", "apb_gemm_2_2_int", "apb_gemm_2_2",
+    "apb_train_workspace_bytes", "apb_train_forward", "apb_train_backward",
     "apb_probe_out_bytes", "apb_probe_rate",
     "apb_strerror", "apb_last_hip_error",
 )
@@ -96,6 +97,12 @@ def load() -> ctypes.CDLL:
     lib.apb_gemm_2_2_int.restype = ci
     lib.apb_gemm_2_2.argtypes = [vp, vp, ci, cf, vp, vp]
     lib.apb_gemm_2_2.restype = ci
+    lib.apb_train_workspace_bytes.argtypes = []
+    lib.apb_train_workspace_bytes.restype = ctypes.c_size_t
+    lib.apb_train_forward.argtypes = [vp, ctypes.c_longlong, cf, cf, vp, vp]
+    lib.apb_train_forward.restype = ci
+    lib.apb_train_backward.argtypes = [vp, vp, ctypes.c_longlong, cf, cf, vp, vp, vp, vp, vp]
+    lib.apb_train_backward.restype = ci
     lib.apb_probe_out_bytes.argtypes = []
     lib.apb_probe_out_bytes.restype = ctypes.c_size_t
     lib.apb_probe_rate.argtypes = [ci, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
@@ -492,3 +499,47 @@ def apb_probe_rate(kind: int, iters: int, out: torch.Tensor, stream: Optional[to
     _check(load().apb_probe_rate(int(kind), int(iters), out.data_ptr(), ctypes.byref(work), _stream(stream)),
            "apb_probe_rate")
     return work.value
+
+
+# ----------------------------------------------------------------------------- training-side operators
+
+def apb_train_workspace_bytes() -> int:
+    return int(load().apb_train_workspace_bytes())
+
+
+def apb_train_forward(W: torch.Tensor, alpha: float, delta: float, out: Optional[torch.Tensor] = None,
+                      stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """APB(w) element-wise on the latent weights (any shape, contiguous float32)."""
+    ptr = _dev_ptr(W, torch.float32, "W")
+    if out is None:
+        out = torch.empty_like(W)
+    elif out.shape != W.shape:
+        raise ValueError("out must have W's shape")
+    _check(load().apb_train_forward(ptr, W.numel(), float(alpha), float(delta), _dev_ptr(out, torch.float32, "out"),
+                                    _stream(stream)), "apb_train_forward")
+    return out
+
+
+def apb_train_backward(W: torch.Tensor, G: torch.Tensor, alpha: float, delta: float, want_grad_w: bool = True,
+                       grad_w: Optional[torch.Tensor] = None, sums: Optional[torch.Tensor] = None,
+                       count: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                       stream: Optional[torch.cuda.Stream] = None):
+    """Returns (grad_w or None, sums [grad_alpha, grad_delta] float64 on the GPU, count int64 on the GPU)."""
+    if W.shape != G.shape:
+        raise ValueError("G must have W's shape")
+    if want_grad_w and grad_w is None:
+        grad_w = torch.empty_like(G)
+    if sums is None:
+        sums = torch.empty(2, dtype=torch.float64, device=W.device)
+    if count is None:
+        count = torch.empty(1, dtype=torch.int64, device=W.device)
+    if workspace is None:
+        workspace = torch.empty(apb_train_workspace_bytes() // 8, dtype=torch.float64, device=W.device)
+    elif workspace.numel() * workspace.element_size() < apb_train_workspace_bytes():
+        raise ValueError("workspace smaller than apb_train_workspace_bytes()")
+    _check(load().apb_train_backward(_dev_ptr(W, torch.float32, "W"), _dev_ptr(G, torch.float32, "G"), W.numel(),
+                                     float(alpha), float(delta),
+                                     None if grad_w is None else _dev_ptr(grad_w, torch.float32, "grad_w"),
+                                     sums.data_ptr(), count.data_ptr(), workspace.data_ptr(), _stream(stream)),
+           "apb_train_backward")
+    return grad_w, sums, count
