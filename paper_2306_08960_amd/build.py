@@ -18,7 +18,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libapb.so")
-SOURCES = ["apb_api.hip", "apb_compress.hip", "apb_quantize.hip", "apb_forward.hip", "apb_sparse.hip",
+SOURCES = ["apb_api.hip", "apb_compress.hip", "apb_quantize.hip", "apb_forward.hip", "apb_sparse.hip", "apb_rows.hip",
            "apb_binary_mfma.hip", "apb_binary_mfma_d1.hip", "apb_binary_mfma_d2.hip", "apb_binary_mfma_22i.hip",
            "apb_binary_mfma_22f.hip", "apb_noalloc.hip", "apb_probe.hip", "apb_train.hip"]
 

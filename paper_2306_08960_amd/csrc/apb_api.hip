@@ -19,7 +19,7 @@ hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 void free_layer_buffers(LayerDev& d) {
     void* ptrs[] = {d.sign, d.signT, d.perm, d.row_ptr, d.col_idx, d.val, d.rowsum, d.chunk_ptr, d.slot_valsum, d.vald, d.signC,
-                    d.seg_ptr, d.ent};
+                    d.seg_ptr, d.ent, d.rows_perm, d.rows_blk, d.rows_ek, d.rows_ev, d.rows_sign, d.rows_valsum};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     d = LayerDev{};
@@ -106,6 +106,44 @@ void build_tile_runs(const std::vector<int32_t>& perm, const std::vector<int32_t
             }
         }
         seg_ptr[(size_t)t * (nchunks + 1) + nchunks] = (int32_t)(ent.size() / kEntBlockWords);
+    }
+}
+
+// Row lists for the rows-in-lanes kernel (see LayerDev): rows in order of decreasing residual count, so
+// that the 64 rows of a block have nearly the same number of steps; a block takes as many steps as its
+// longest row, shorter rows are padded with (offset 0, value 0).
+void build_row_lists(const std::vector<int32_t>& row_ptr, const std::vector<int32_t>& col, const std::vector<float>& val,
+                     std::vector<int32_t>& perm, std::vector<int32_t>& blk, std::vector<uint32_t>& ek,
+                     std::vector<double>& ev, std::vector<double>& valsum) {
+    const int N = (int)row_ptr.size() - 1;
+    const int nb = (N + kWave - 1) / kWave, Nr = nb * kWave;
+    std::vector<int32_t> order(N);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
+        return row_ptr[a + 1] - row_ptr[a] > row_ptr[b + 1] - row_ptr[b];
+    });
+    perm.assign(Nr, -1);
+    std::copy(order.begin(), order.end(), perm.begin());
+    blk.assign(nb + 1, 0);
+    for (int b = 0; b < nb; ++b) {
+        const int n0 = perm[(size_t)b * kWave];                    // longest row of the block
+        blk[b + 1] = blk[b] + (row_ptr[n0 + 1] - row_ptr[n0]);
+    }
+    ek.assign((size_t)blk[nb] * kWave, 0u);
+    ev.assign((size_t)blk[nb] * kWave, 0.0);
+    valsum.assign(Nr, 0.0);
+    for (int i = 0; i < Nr; ++i) {
+        const int n = perm[i];
+        if (n < 0) continue;
+        const int b = i / kWave, lane = i % kWave;
+        double sum = 0.0;
+        for (int e = row_ptr[n]; e < row_ptr[n + 1]; ++e) {
+            const size_t at = ((size_t)blk[b] + (e - row_ptr[n])) * kWave + lane;
+            ek[at] = (uint32_t)col[e] * kRowsRowBytes;
+            ev[at] = std::ldexp((double)val[e], kEntValScaleLog2);
+            sum += (double)val[e];
+        }
+        valsum[i] = sum;
     }
 }
 
@@ -207,6 +245,33 @@ int compress_impl(const float* W, int N, int K, float delta, float alpha, hipStr
     APB_HIP(hipMemcpyAsync(d.seg_ptr, hseg.data(), hseg.size() * sizeof(int32_t), hipMemcpyHostToDevice, s));
     if (!hent.empty())
         APB_HIP(hipMemcpyAsync(d.ent, hent.data(), hent.size() * sizeof(uint32_t), hipMemcpyHostToDevice, s));
+    // Row lists for the rows-in-lanes kernel: only where K fits its on-chip code table and rows carry
+    // enough residuals for the padding of the lists (to the longest row of each block of 64) to stay small.
+    std::vector<int32_t> rperm, rblk;
+    std::vector<uint32_t> rek;
+    std::vector<double> rev, rvalsum;
+    if ((long long)32 * d.Kw * kRowsRowBytes <= kRowsMaxTableBytes && nnz >= (long long)4 * N) {
+        build_row_lists(hrow_ptr, hcol, hval, rperm, rblk, rek, rev, rvalsum);
+        const long long steps = rblk.back();
+        if (steps * kWave <= 2 * nnz) {                   // at most half of the list entries are padding
+            d.rows_Nr = (int)rperm.size();
+            d.rows_Kw4 = 4 * ((d.Kw + 3) / 4);
+            d.rows_steps = steps;
+            if ((rc = dev_alloc(&d.rows_perm, rperm.size())) != APB_OK) return rc;
+            if ((rc = dev_alloc(&d.rows_blk, rblk.size())) != APB_OK) return rc;
+            if ((rc = dev_alloc(&d.rows_ek, rek.size())) != APB_OK) return rc;
+            if ((rc = dev_alloc(&d.rows_ev, rev.size())) != APB_OK) return rc;
+            if ((rc = dev_alloc(&d.rows_valsum, rvalsum.size())) != APB_OK) return rc;
+            if ((rc = dev_alloc(&d.rows_sign, (size_t)d.rows_Kw4 * d.rows_Nr)) != APB_OK) return rc;
+            APB_HIP(hipMemcpyAsync(d.rows_perm, rperm.data(), rperm.size() * sizeof(int32_t), hipMemcpyHostToDevice, s));
+            APB_HIP(hipMemcpyAsync(d.rows_blk, rblk.data(), rblk.size() * sizeof(int32_t), hipMemcpyHostToDevice, s));
+            APB_HIP(hipMemcpyAsync(d.rows_ek, rek.data(), rek.size() * sizeof(uint32_t), hipMemcpyHostToDevice, s));
+            APB_HIP(hipMemcpyAsync(d.rows_ev, rev.data(), rev.size() * sizeof(double), hipMemcpyHostToDevice, s));
+            APB_HIP(hipMemcpyAsync(d.rows_valsum, rvalsum.data(), rvalsum.size() * sizeof(double), hipMemcpyHostToDevice, s));
+            if ((rc = launch_slot_major_signs(d.sign, d.rows_perm, d.rows_Nr, d.Kw, d.rows_Kw4, d.rows_sign, s)) != APB_OK)
+                return rc;
+        }
+    }
     APB_HIP(hipStreamSynchronize(s));                 // host staging vectors go out of scope after this
     return APB_OK;
 }
@@ -321,7 +386,7 @@ static int forward_common(const apb_layer* layer, const void* packed, int M, int
         return launch_binary_mfma(d, planes, colsum, M, bits, D, s);
     }
     if (kind == kFwdFull) {
-        return launch_forward(d, planes, colsum, M, bits, step, nullptr, Y, s);
+        return launch_forward_best(d, planes, colsum, M, bits, step, Y, s);
     }
     return launch_forward_popcount(d, planes, colsum, M, bits, step, Y, D, s);
 }
@@ -348,6 +413,7 @@ int apb_forward_requant(const apb_layer* layer, const void* packed, int M, int b
 
 const char* apb_forward_kernel_name(const apb_layer* layer, int M, int bits) {
     if (!layer || M <= 0 || (bits != 1 && bits != 2)) return "";
+    if (forward_rows_applies(layer->d, M, bits)) return bits == 1 ? "k_forward_rows<1>" : "k_forward_rows<2>";
     return forward_kernel_name(layer->d, M, bits);
 }
 
@@ -366,10 +432,10 @@ int apb_quantize_forward(const apb_layer* layer, const float* X, int M, int bits
     hipStream_t s = as_stream(stream);
     if (forward_float_applies(d, M, bits)) return launch_forward_float(d, X, M, bits, step, Y, s);
     const int rc = apb_quantize_acts(X, d.K, M, bits, step, packed, stream);
-    return rc != APB_OK ? rc : launch_forward(d, static_cast<const uint32_t*>(packed),
-                                              reinterpret_cast<const int32_t*>(static_cast<const uint32_t*>(packed) +
-                                                  (size_t)bits * d.Kw * ((size_t)kWave * (((size_t)M + kWave - 1) / kWave))),
-                                              M, bits, step, nullptr, Y, s);
+    return rc != APB_OK ? rc : launch_forward_best(d, static_cast<const uint32_t*>(packed),
+                                                   reinterpret_cast<const int32_t*>(static_cast<const uint32_t*>(packed) +
+                                                       (size_t)bits * d.Kw * ((size_t)kWave * (((size_t)M + kWave - 1) / kWave))),
+                                                   M, bits, step, Y, s);
 }
 
 // Shape checks shared by the two convolution entry points; fills `conv` and the pixel count.

@@ -43,7 +43,24 @@ struct LayerDev {
     int32_t* seg_ptr = nullptr;    // [Np/kRowTile][nchunks+1]  first block of (tile, chunk)
     uint32_t* ent = nullptr;       // [blocks][24]  8 keys: 2 * row_in_tile | (col - 256*chunk) << 8, then
                                    //               8 float64: residual * 2^kEntValScaleLog2 (0 for padding)
+    // Row lists for the rows-in-lanes forward kernel (apb_rows.hip), built for layers with many residuals
+    // per row whose K fits the on-chip code table; rows_steps == 0 when not built.  Rows are sorted by
+    // residual count and cut into blocks of 64 launch slots; block b walks steps rows_blk[b] .. rows_blk[b+1],
+    // and in a step lane l handles one residual of its row (or a padding entry: offset 0, value 0).
+    int rows_Nr = 0;               // 64 * blocks
+    int rows_Kw4 = 0;              // Kw rounded up to a multiple of 4 (one matrix step = 128 values of k)
+    long long rows_steps = 0;
+    int32_t* rows_perm = nullptr;  // [Nr]        row served by slot i, -1 for padding
+    int32_t* rows_blk = nullptr;   // [Nr/64 + 1]
+    uint32_t* rows_ek = nullptr;   // [steps][64] kRowsRowBytes * column: byte offset of the column's row in the code table
+    double* rows_ev = nullptr;     // [steps][64] residual * 2^kEntValScaleLog2
+    uint32_t* rows_sign = nullptr; // [Kw4][Nr]   sign words, slot-major in this order (pad rows and slots zero)
+    double* rows_valsum = nullptr; // [Nr]        sum of the residuals of the slot's row (float64, CSR order)
 };
+
+constexpr int kRowsCols = 16;            // output columns one workgroup of the rows-in-lanes kernel covers
+constexpr int kRowsRowBytes = 8;         // bytes of its code table per value of k (4 bits per column)
+constexpr int kRowsMaxTableBytes = 144 * 1024;   // the whole table (all of K) has to fit on chip
 
 void set_last_hip_error(hipError_t e);
 
@@ -116,6 +133,15 @@ int launch_forward_requant(const LayerDev& L, const uint32_t* planes, const int3
 // true while K * max_weight * max_code < 2^24: the float accumulators of the matrix instruction then hold
 // every partial sum exactly (launchers return APB_ERR_SHAPE otherwise)
 bool mfma_sum_exact(int K, int max_weight, int max_code);
+
+// the rows-in-lanes forward kernel (apb_rows.hip): same Y as launch_forward for a plain K x M matrix;
+// forward_rows_applies says whether the layer has row lists and the launch is worth it
+bool forward_rows_applies(const LayerDev& L, int M, int bits);
+int launch_forward_rows(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
+                        float* Y, hipStream_t s);
+// apb_forward's choice between the two forward kernels for a plain K x M matrix and a float output
+int launch_forward_best(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
+                        float* Y, hipStream_t s);
 
 // binary part alone on the matrix cores: the integer part D
 int launch_binary_mfma(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,

@@ -56,5 +56,5 @@ extern "C" int apb_quantize_forward_static(const apb_layer* layer, const float* 
     int32_t* colsum = reinterpret_cast<int32_t*>(planes + (size_t)bits * d.Kw * Mp);
     rc = launch_quantize(X, d.K, M, bits, 1.0f / step, planes, colsum, s);
     if (rc != APB_OK) return rc;
-    return launch_forward(d, planes, colsum, M, bits, step, nullptr, Y, s);
+    return launch_forward_best(d, planes, colsum, M, bits, step, Y, s);
 }

@@ -1,0 +1,400 @@
+// The forward kernel for layers with many residuals per row (Sec. III Eqs. 12-13):
+//     Y[n,m] = s * ( alpha * D[n,m] + sum_{j in row n} val_j * c[col_j, m] )
+// with the LANES ALONG THE ROWS n.  (The other forward kernel, apb_sparse.hip, runs its lanes along the
+// columns m; per residual and 64 outputs it needs one LDS read, and the LDS accepts one wave-wide read every
+// two cycles per compute unit -- measured, that read rate is what bounds it on layers like a 512 x 4608
+// convolution with 3 % residuals.)  Here a lane owns one row of the sparse matrix and kRowsCols = 16 output
+// columns:
+//   * a workgroup (up to 8 waves = 512 rows) takes one group of 16 columns and keeps the code table of those
+//     columns for ALL of K in LDS, one byte per activation, 16 bytes per value of k -- built once, shared by
+//     every row, no walk over chunks of K and no barrier inside the residual loop;
+//   * a step of the residual loop: the lane loads its next residual (table offset of its column, value) from
+//     the row lists laid out at compress time ([step][lane], so the loads are contiguous), reads the 16 codes
+//     of that column with ONE 8-byte LDS read and does 16 x (nibble mask + float64 multiply-add) into 16
+//     accumulators it keeps in registers.  Nothing is wave-uniform, so there is no scalar traffic, no index
+//     register and no out-of-order counter shared between entry loads and table reads: the entry loads are
+//     vector loads (in-order counter), fetched several steps ahead.
+// Per residual and output that is 2 vector-ALU instructions and 1/16 of an LDS read.
+// The binary part runs first on the matrix cores exactly as in the other kernels (apb_fp4_expand.h), here
+// with the 16x16x128 FP4 instruction: a wave computes its 64 rows x 16 columns as four tiles.
+// A table row is 8 bytes: the 16 codes of one k as nibbles.  A code becomes a float64 multiplicand by masking
+// its nibble in place inside the high half of a register pair (a subnormal number; see col_bit); the residuals
+// are stored times 2^895 so that the products are ordinary numbers, and all scales are powers of two.
+#include <algorithm>
+#include <atomic>
+
+#include "apb_fp4_expand.h"
+#include "apb_internal.h"
+
+namespace apb {
+
+namespace {
+
+constexpr int T = kRowsCols;
+constexpr int kMaxDevices = 64;
+constexpr int kBufferFlags = 0x00020000;                        // fourth word of a raw buffer descriptor: 32-bit data, no swizzle
+constexpr int kRowBytes = kRowsRowBytes;                        // table bytes per value of k: 16 columns x 4 bits
+
+// Column c of a table row sits in dword c / 8 as the nibble at bit 4 * (c % 8).  Its multiplicand is that
+// nibble left where it is in an otherwise zero high half of a float64 -- a subnormal number, code * 2^(P - 1042)
+// with P the bit position -- so no shift and no conversion is needed for the five nibbles that lie in the
+// mantissa field (bits 0..19); the other three are taken from the dword shifted right by 12.  Every column thus
+// carries its own power-of-two scale, which commutes with rounding and is taken out at the end.
+__host__ __device__ constexpr bool col_shifted(int c) { return (c & 7) >= 5; }
+__host__ __device__ constexpr int col_bit(int c) { return 4 * (c & 7) - (col_shifted(c) ? 12 : 0); }
+static_assert(kEntValScaleLog2 == 895, "col_unscale undoes 2^895 * 2^(P - 1042)");
+// 2^(147 - col_bit(c)) and its inverse, by position of the column in its dword (literals: nothing to evaluate
+// at run time, and no function call in device code).
+__device__ __forceinline__ double col_unscale(int c) {
+    constexpr double t[8] = {0x1p147, 0x1p143, 0x1p139, 0x1p135, 0x1p131, 0x1p139, 0x1p135, 0x1p131};
+    return t[c & 7];
+}
+__device__ __forceinline__ double col_scale(int c) {
+    constexpr double t[8] = {0x1p-147, 0x1p-143, 0x1p-139, 0x1p-135, 0x1p-131, 0x1p-139, 0x1p-135, 0x1p-131};
+    return t[c & 7];
+}
+static_assert(col_bit(0) == 0 && col_bit(4) == 16 && col_bit(5) == 8 && col_bit(7) == 16 && col_bit(13) == 8,
+              "the literals above are 2^(147 - col_bit)");
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+
+struct RowsParams {
+    double alpha, step;
+    int N, Nr, Kw, Kw4, Mp, M;
+    int nblocks;                                                 // row blocks of 64 slots
+    int row_groups;                                              // ceil(nblocks / waves per workgroup)
+    int tasks;                                                   // row_groups * column groups
+};
+
+__device__ __forceinline__ uint32_t spread4(uint32_t nib) { return (nib * 0x00204081u) & 0x01010101u; }
+
+// Codes of the 4 activations k = 32*j + 4*d + 0..3 of one column, one per byte, from the plane words of word row j.
+template <int BITS>
+__device__ __forceinline__ uint32_t codes4(uint32_t x0, uint32_t x1, int d) {
+    uint32_t t = spread4((x0 >> (4 * d)) & 0xFu);
+    if (BITS == 2) t |= spread4((x1 >> (4 * d)) & 0xFu) << 1;
+    return t;
+}
+
+__device__ __forceinline__ v4f mfma_fp4_16(const v8i& a, const v8i& b, const v4f& c) {
+    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 4, 4, 0, kScaleOne, 0, kScaleOne);
+}
+
+// acc[c] += v * code(column c of the table row q) * 2^(col_bit(c) - 1042), c = 0..15.  `m` is a register pair whose
+// low half stays zero: the masked nibble in its high half makes it the float64 multiplicand.
+__device__ __forceinline__ void accumulate16(double (&acc)[T], v2i& m, const v2u& q, double v) {
+    const uint32_t sh[2] = {q[0] >> 12, q[1] >> 12};
+#pragma unroll
+    for (int c = 0; c < T; ++c) {
+        const uint32_t src = col_shifted(c) ? sh[c >> 3] : q[c >> 3];
+        m.y = (int)(src & (0xFu << col_bit(c)));
+        acc[c] = fma(v, __builtin_bit_cast(double, m), acc[c]);
+    }
+}
+
+template <int BITS>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 4))) void k_forward_rows(
+    const uint32_t* __restrict__ planes, const int32_t* __restrict__ colsum, const int32_t* __restrict__ rowsum,
+    const int32_t* __restrict__ rperm, const int32_t* __restrict__ blk, const uint32_t* __restrict__ ek,
+    const double* __restrict__ ev, const uint32_t* __restrict__ signR, const double* __restrict__ valsumR,
+    float* __restrict__ Y, const RowsParams p) {
+    extern __shared__ __align__(16) uint8_t lds[];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int waves = blockDim.x / kWave;
+
+    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of tasks so that the
+    // row groups of one column group share an L2.
+    int task = blockIdx.x;
+    if ((p.tasks & 7) == 0) task = (blockIdx.x & 7) * (p.tasks >> 3) + (blockIdx.x >> 3);
+    const int rg = task % p.row_groups;
+    const int cg = task / p.row_groups;
+    const int b = rg * waves + wave;                             // this wave's block of 64 rows
+    const bool active = b < p.nblocks;                           // (the last row group may have idle waves)
+    const int m0 = cg * T;
+    const int slot = b * kWave + lane;
+
+    // ---- binary part: P = sum_k bit * code for 64 rows x 16 columns, four 16 x 16 tiles over K in steps of 128.
+    // Lane (i, g), i = lane & 15, g = lane >> 4, owns word 4*s + g of step s for row / column i of a tile.
+    // The activation operand is the same for every wave of the workgroup: it is expanded once, by all threads
+    // together, into LDS (16 bytes per step and lane -- as many bytes as the code table that later takes the
+    // same place) and the waves read it back with one 16-byte LDS read per step.
+    const int steps = p.Kw4 / 4;
+    {
+        const size_t plane_stride = (size_t)p.Kw * p.Mp;
+        v4u* stage = reinterpret_cast<v4u*>(lds);
+        for (int it = threadIdx.x; it < steps * kWave; it += blockDim.x) {
+            const int l = it & (kWave - 1), s = it >> 6;
+            // word rows past Kw: the sign words there are zero padding; the activation load re-reads the last
+            // row and is multiplied by those zeros
+            const uint32_t* brow = planes + (size_t)min(4 * s + (l >> 4), p.Kw - 1) * p.Mp + m0 + (l & 15);
+            v8i fb;
+            expand_words<BITS>(brow[0], BITS == 2 ? brow[plane_stride] : 0u, fb);
+            stage[it] = v4u{(uint32_t)fb[0], (uint32_t)fb[1], (uint32_t)fb[2], (uint32_t)fb[3]};
+        }
+    }
+    __syncthreads();
+    double acc[T];
+    {
+        const int i = lane & 15, g = lane >> 4;
+        v4f c[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) c[t][r] = 0.0f;
+        if (active) {
+            v8i fa, fb;
+#pragma unroll
+            for (int d = 4; d < 8; ++d) fa[d] = fb[d] = 0;
+            // Sign words are fetched kRing steps ahead (a ring of register sets indexed by step % kRing), so that
+            // the expansion and the matrix instructions of a step never wait for that step's own loads.
+            const uint32_t* arow = signR + (size_t)g * p.Nr + (size_t)b * kWave + i;
+            const v4u* stage = reinterpret_cast<const v4u*>(lds) + lane;
+            constexpr int kRing = 4;
+            uint32_t aw[kRing][4];
+            auto load_words = [&](int s, uint32_t (&a)[4]) {
+                const int ss = min(s, steps - 1);                // past the end: a harmless re-read, never used
+#pragma unroll
+                for (int t = 0; t < 4; ++t) a[t] = arow[(size_t)(4 * ss) * p.Nr + 16 * t];
+            };
+            auto one_step = [&](int s, int q) {
+                uint32_t a[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) a[t] = aw[q][t];
+                load_words(s + kRing, aw[q]);
+                const v4u bq = stage[(size_t)s * kWave];
+#pragma unroll
+                for (int d = 0; d < 4; ++d) fb[d] = (int)bq[d];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    expand_words<1>(a[t], 0u, fa);
+                    c[t] = mfma_fp4_16(fa, fb, c[t]);
+                }
+            };
+#pragma unroll
+            for (int q = 0; q < kRing; ++q) load_words(q, aw[q]);
+            int s0 = 0;
+            for (; s0 + kRing <= steps; s0 += kRing) {
+#pragma unroll
+                for (int q = 0; q < kRing; ++q) one_step(s0 + q, q);
+            }
+#pragma unroll
+            for (int q = 0; q < kRing - 1; ++q)
+                if (s0 + q < steps) one_step(s0 + q, q);
+        }
+        __syncthreads();                                         // every wave is done with the staged operands
+        // C layout of a 16 x 16 tile: lane (i, g), register r -> row 4*g + r, column i.  Through LDS, so that
+        // every lane gets the 16 products of ITS row.
+        int32_t* tile = reinterpret_cast<int32_t*>(lds) + wave * (kWave * T);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) tile[(16 * t + 4 * g + r) * T + i] = (int)(c[t][r] * 4.0f);
+        __syncthreads();
+        const int n = active ? rperm[slot] : -1;
+        const int rs = BITS == 1 && n >= 0 ? rowsum[n] : 0;
+        const double a0 = p.alpha * (BITS == 1 ? 0.5 : 1.0);
+#pragma unroll
+        for (int cc = 0; cc < T; ++cc) {
+            const int P = tile[lane * T + cc];
+            const int cs = colsum[m0 + cc];                      // m0 + 15 < Mp: Mp is a multiple of 64
+            const int d = BITS == 1 ? 4 * P - rs - 2 * cs : 2 * P - cs;
+            acc[cc] = a0 * (double)d * col_scale(cc);  // in the scaled domain of column cc's products
+        }
+        __syncthreads();                                         // the tiles are read; the table may overwrite them
+    }
+
+    // ---- code table of the 16 columns for all of K: table[k] = 8 bytes, byte u = code of column 2u in the low
+    // nibble, of column 2u + 1 in the high one.  Thread -> (word row j, quad d of its 32 values of k): it reads the
+    // 16 columns' words of row j (64 contiguous bytes per plane), takes nibble d of each and writes the four
+    // finished table rows k = 32*j + 4*d + 0..3 -- 32 contiguous bytes -- with two 16-byte stores.
+    {
+        const int items = p.Kw * 8;
+        const size_t plane_stride = (size_t)p.Kw * p.Mp;
+        for (int it = threadIdx.x; it < items; it += blockDim.x) {
+            const int d = it & 7, j = it >> 3;
+            const v4u* src0 = reinterpret_cast<const v4u*>(planes + (size_t)j * p.Mp + m0);
+            const v4u* src1 = reinterpret_cast<const v4u*>(planes + plane_stride + (size_t)j * p.Mp + m0);
+            uint32_t row[4][2];                                  // [q][half]: dword `half` of table row 4*d + q
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                // u[i], i = 0..3: bytes q = 0..3 of u[i] are byte (4*h + i) of the table rows q
+                uint32_t u[4];
+#pragma unroll
+                for (int v = 0; v < 2; ++v) {
+                    const v4u x0 = src0[2 * h + v];
+                    const v4u x1 = BITS == 2 ? src1[2 * h + v] : v4u{0, 0, 0, 0};
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+                        u[2 * v + i] = codes4<BITS>(x0[2 * i], x1[2 * i], d) | (codes4<BITS>(x0[2 * i + 1], x1[2 * i + 1], d) << 4);
+                }
+                // 4 x 4 byte transpose: row q, half h = { u[0].q, u[1].q, u[2].q, u[3].q }
+                const uint32_t a01 = __builtin_amdgcn_perm(u[1], u[0], 0x05010400u);   // u0.0 u1.0 u0.1 u1.1
+                const uint32_t b01 = __builtin_amdgcn_perm(u[1], u[0], 0x07030602u);   // u0.2 u1.2 u0.3 u1.3
+                const uint32_t a23 = __builtin_amdgcn_perm(u[3], u[2], 0x05010400u);
+                const uint32_t b23 = __builtin_amdgcn_perm(u[3], u[2], 0x07030602u);
+                row[0][h] = __builtin_amdgcn_perm(a23, a01, 0x05040100u);              // u0.0 u1.0 u2.0 u3.0
+                row[1][h] = __builtin_amdgcn_perm(a23, a01, 0x07060302u);
+                row[2][h] = __builtin_amdgcn_perm(b23, b01, 0x05040100u);
+                row[3][h] = __builtin_amdgcn_perm(b23, b01, 0x07060302u);
+            }
+            v4u* dst = reinterpret_cast<v4u*>(lds + (size_t)(32 * j + 4 * d) * kRowBytes);
+            dst[0] = v4u{row[0][0], row[0][1], row[1][0], row[1][1]};
+            dst[1] = v4u{row[2][0], row[2][1], row[3][0], row[3][1]};
+        }
+    }
+    __syncthreads();
+    if (!active) return;
+
+    // ---- residual part: steps e0 .. e1 of this block; entries fetched kAhead steps ahead, the table row of
+    // the next step read while the multiply-adds of this one issue.
+    {
+        const int e0 = blk[b], e1 = blk[b + 1];
+        const int n_steps = e1 - e0;
+        // Entry loads are buffer loads: descriptor = this block's part of the lists, the step in the scalar
+        // offset, the lane in a constant vector offset -- no address arithmetic on the vector ALU.
+        const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint32_t*>(ek + (size_t)e0 * kWave), 0, max(n_steps, 1) * kWave * 4, kBufferFlags);
+        const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<double*>(ev + (size_t)e0 * kWave), 0, max(n_steps, 1) * kWave * 8, kBufferFlags);
+        const int lane4 = lane * 4, lane8 = lane * 8;
+        auto load_k = [&](int jj) { return (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rk, lane4, jj * (kWave * 4), 0); };
+        auto load_v = [&](int jj) {
+            const v2u r = __builtin_amdgcn_raw_buffer_load_b64(rv, lane8, jj * (kWave * 8), 0);
+            return __builtin_bit_cast(double, r);
+        };
+        constexpr int kAhead = 4;
+        uint32_t kq[kAhead];
+        double vq[kAhead];
+#pragma unroll
+        for (int a = 0; a < kAhead; ++a) {
+            const int j = min(a, max(n_steps - 1, 0));
+            kq[a] = n_steps > 0 ? load_k(j) : 0u;
+            vq[a] = n_steps > 0 ? load_v(j) : 0.0;
+        }
+        v2i m = v2i{0, 0};
+        // kq[a], vq[a]: the entry of step j + a; q: the table row of the step about to be processed
+        v2u q = *reinterpret_cast<const v2u*>(lds + kq[0]);     // (offset 0 for an empty list: in bounds)
+        int j = 0;
+        for (; j + kAhead <= n_steps; j += kAhead) {
+#pragma unroll
+            for (int a = 0; a < kAhead; ++a) {
+                const v2u qc = q;
+                // the row of step j + a + 1 (slot 0 was refilled kAhead - 1 steps ago)
+                q = *reinterpret_cast<const v2u*>(lds + kq[(a + 1) % kAhead]);
+                // the slot is refilled before its old value is consumed (measured faster than after: the loads
+                // get a full kAhead steps of lead)
+                const double vcur = vq[a];
+                const int jn = min(j + a + kAhead, n_steps - 1); // past the end: the last entry again, never used
+                kq[a] = load_k(jn);
+                vq[a] = load_v(jn);
+                accumulate16(acc, m, qc, vcur);
+            }
+        }
+        for (int a = 0; j < n_steps; ++j, ++a) {                 // at most kAhead - 1 steps left, all in the queue
+            const v2u qc = a == 0 ? q : *reinterpret_cast<const v2u*>(lds + kq[a]);
+            accumulate16(acc, m, qc, vq[a]);
+        }
+    }
+
+    // ---- epilogue: 16 consecutive floats of row n.
+    const int n = rperm[slot];
+    if (n < 0) return;
+    const double vs = BITS == 1 ? valsumR[slot] : 0.0;
+    float y[T];
+#pragma unroll
+    for (int cc = 0; cc < T; ++cc) {
+        const double sum = acc[cc] * col_unscale(cc);
+        y[cc] = (float)((BITS == 1 ? 2.0 * sum - vs : sum) * p.step);
+    }
+    float* out = Y + (size_t)n * p.M + m0;
+    if (m0 + T <= p.M && (p.M & 3) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15u) == 0) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            reinterpret_cast<v4f*>(out)[u] = v4f{y[4 * u], y[4 * u + 1], y[4 * u + 2], y[4 * u + 3]};
+    } else {
+#pragma unroll
+        for (int cc = 0; cc < T; ++cc)
+            if (m0 + cc < p.M) out[cc] = y[cc];
+    }
+}
+
+int rows_waves(const LayerDev& L) {
+    const int nb = L.rows_Nr / kWave;
+    return nb >= 4 ? 4 : (nb >= 2 ? 2 : 1);
+}
+
+size_t rows_lds_bytes(const LayerDev& L, int waves) {
+    // the code table; before it, in the same place, the staged activation operands (16 bytes per step and lane)
+    // and the tiles of the binary product
+    const size_t table = (size_t)32 * L.Kw * kRowBytes, stage = (size_t)(L.rows_Kw4 / 4) * kWave * 16;
+    const size_t tiles = (size_t)waves * kWave * T * 4;
+    return std::max(table, std::max(stage, tiles));
+}
+
+template <int BITS>
+int launch_rows(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, float* Y, const RowsParams& p,
+                int waves, hipStream_t s) {
+    const size_t lds = rows_lds_bytes(L, waves);
+    if (lds > 64 * 1024) {                                      // more LDS than a launch gets without asking
+        static std::atomic<size_t> asked[kMaxDevices];          // largest size asked for, per device
+        int dev = 0;
+        APB_HIP(hipGetDevice(&dev));
+        if (dev < 0 || dev >= kMaxDevices) return APB_ERR_SHAPE;
+        if (asked[dev].load(std::memory_order_acquire) < lds) {
+            APB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_forward_rows<BITS>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, kRowsMaxTableBytes));
+            asked[dev].store((size_t)kRowsMaxTableBytes, std::memory_order_release);
+        }
+    }
+    hipLaunchKernelGGL((k_forward_rows<BITS>), dim3((unsigned)p.tasks), dim3(kWave * waves), lds, s, planes, colsum,
+                       L.rowsum, L.rows_perm, L.rows_blk, L.rows_ek, L.rows_ev, L.rows_sign, L.rows_valsum, Y, p);
+    APB_HIP(hipGetLastError());
+    return APB_OK;
+}
+
+}  // namespace
+
+// The rows-in-lanes kernel pays for a code table of all of K per 16 columns and for lists padded to the
+// longest row of each block; it wins where the residual multiply-adds dominate.
+bool forward_rows_applies(const LayerDev& L, int M, int bits) {
+    // Measured on the benchmark layers: ahead of the columns-in-lanes kernel from 0.5 % residuals upwards on
+    // layers of 256 rows and more; with fewer than four blocks of 64 rows a workgroup has too few waves.
+    return L.rows_steps > 0 && M > 0 && L.rows_Nr >= 4 * kWave;
+}
+
+int launch_forward_rows(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
+                        float* Y, hipStream_t s) {
+    if (L.rows_steps == 0 || (reinterpret_cast<uintptr_t>(planes) & 15u) != 0) return APB_ERR_SHAPE;
+    if (!mfma_sum_exact(L.K, 1, bits == 1 ? 1 : 3)) return APB_ERR_SHAPE;
+    const int Mp = kWave * ((M + kWave - 1) / kWave);
+    const int waves = rows_waves(L);
+    RowsParams p;
+    p.alpha = (double)L.alpha;
+    p.step = (double)step;
+    p.N = L.N;
+    p.Nr = L.rows_Nr;
+    p.Kw = L.Kw;
+    p.Kw4 = L.rows_Kw4;
+    p.Mp = Mp;
+    p.M = M;
+    p.nblocks = L.rows_Nr / kWave;
+    p.row_groups = (p.nblocks + waves - 1) / waves;
+    const long long tasks = (long long)p.row_groups * ((M + T - 1) / T);
+    if (tasks > 0x7fffffffLL || (long long)Mp * 8 >= (1LL << 31)) return APB_ERR_SHAPE;
+    p.tasks = (int)tasks;
+    return bits == 1 ? launch_rows<1>(L, planes, colsum, Y, p, waves, s) : launch_rows<2>(L, planes, colsum, Y, p, waves, s);
+}
+
+int launch_forward_best(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
+                        float* Y, hipStream_t s) {
+    // (the rows-in-lanes kernel reads the packed words 16 bytes at a time)
+    if (forward_rows_applies(L, M, bits) && (reinterpret_cast<uintptr_t>(planes) & 15u) == 0)
+        return launch_forward_rows(L, planes, colsum, M, bits, step, Y, s);
+    return launch_forward(L, planes, colsum, M, bits, step, nullptr, Y, s);
+}
+
+}  // namespace apb
