@@ -67,16 +67,21 @@ def test_special_values_and_degenerate_steps(b):
     check_2_2(b, W, np.float32(1e-6), X, np.float32(1e-3), tag="every weight and activation saturated")
 
 
-@pytest.mark.parametrize("name", ["C2", "C3_r05_b2", "C5a"])
+@pytest.mark.parametrize("name", ["C2", "C3_r05_b2", "C4", "C5a", "C5b"])
 def test_benchmark_shapes(b, name):
+    """Every benchmark shape at full size, every row and column against the oracle."""
     cfg = synth.CONFIGS[name]
     W, _, X, step = synth.make_layer(cfg)
     step_w = np.float32(np.std(W))
     check_2_2(b, W, step_w, X, step, tag=name)
 
 
-def test_largest_shape_on_sampled_rows(b):
-    cfg = synth.CONFIGS["C5b"]
-    W, _, X, step = synth.make_layer(cfg)
-    rows = np.random.default_rng(55).choice(cfg.N, size=24, replace=False)
-    check_2_2(b, W, np.float32(np.std(W)), X, step, rows=np.sort(rows), tag="C5b, 24 sampled rows")
+def test_k_beyond_the_exact_range_is_refused(b):
+    """9*K >= 2^24: the float accumulators of the matrix instruction could no longer hold every partial sum."""
+    K = (1 << 24) // 9 + 32
+    w2 = b.apb_w2_pack(torch.zeros((1, K), device="cuda"), 1.0)
+    packed = b.apb_quantize_acts(torch.zeros((K, 1), device="cuda"), 2, 1.0)
+    with pytest.raises(b.ApbError) as e:
+        b.apb_gemm_2_2_int(w2, packed, 1)
+    assert e.value.code == b.APB_ERR_SHAPE
+    w2.free()

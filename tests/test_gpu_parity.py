@@ -127,7 +127,8 @@ def test_signed_zeros_denormals_ties_and_boundaries(b):
     X[:, 6] = 2.625                             # 3.5 -> 4 -> clamp 3
     X[:, 7] = -3.0
     X[:, 8] = 1e30
-    X[:, 9:] = np.random.default_rng(5).standard_normal((70, 58)).astype(np.float32)
+    X[:, 66] = np.nan                           # quantizes to code 0 / sign -
+    X[:, 9:66] = np.random.default_rng(5).standard_normal((70, 57)).astype(np.float32)
     for bits, step in ((1, 1.0), (2, 0.75), (2, 0.1)):
         check_layer(b, W, np.float32(0.5), X, bits, np.float32(step), alpha=np.float32(0.25), tag="special values")
 

@@ -59,14 +59,21 @@ def test_against_the_oracle(b, bits):
     layer.free()
 
 
-@pytest.mark.parametrize("name", ["C1", "C2", "C4"])
+@pytest.mark.parametrize("name", ["C1", "C2", "C4", "C5b"])
 def test_benchmark_layers_at_full_size(b, name):
+    """The step as the benchmark launches it: bit-equal to the two calls, and every output within 1e-5 relative of
+    the oracle's directly."""
     cfg = synth.CONFIGS[name]
     W, delta, X, step = synth.make_layer(cfg)
+    L = o.compress(W, delta)
+    c = o.quantize(X, cfg.bits, step)
+    F = capi.forward(L, o.pack_acts(c, cfg.bits), c, cfg.bits, step, threads=THREADS)
     Xd = torch.from_numpy(X).cuda()
-    layer = b.apb_compress(torch.from_numpy(W).cuda(), float(delta))
+    layer = b.apb_compress(torch.from_numpy(W).cuda(), float(delta), alpha=float(L["alpha"]))
     packed = b.apb_quantize_acts(Xd, cfg.bits, float(step))
     Y2 = b.apb_forward(layer, packed, cfg.M, cfg.bits, float(step))
     Y1 = b.apb_quantize_forward(layer, Xd, cfg.bits, float(step), packed=packed)
     assert torch.equal(Y1, Y2)
+    ref = F["Y"].astype(np.float64)
+    assert np.all(np.abs(Y1.cpu().numpy().astype(np.float64) - ref) <= 1e-5 * np.abs(ref))
     layer.free()

@@ -131,11 +131,12 @@ def test_fc_chain_at_full_size_sampled_columns(b):
     c = o.quantize(X[:, cols], cfg.bits, step)
     F = capi.forward(L, o.pack_acts(c, cfg.bits), c, cfg.bits, step, threads=THREADS)
     ref1 = o.requant(L["alpha"], step, F["D"], F["R"], 2, step_out)
-    assert (code1[:, cols] != ref1["c"]).mean() < 1e-3
+    # equal codes, except within the float tolerance of a decision boundary, then off by one level and rare
+    compare_codes(code1[:, cols], ref1, L["alpha"], step, F["D"], F["R"], 2, step_out, None, None)
     c_mid = code1[:, cols].astype(np.int8)                   # second hop from the GPU's own codes
     F2 = capi.forward(L, o.pack_acts(c_mid, 2), c_mid, 2, step_out, threads=THREADS)
     ref2 = o.requant(L["alpha"], step_out, F2["D"], F2["R"], 2, step_out)
-    assert (code2[:, cols] != ref2["c"]).mean() < 1e-3
+    compare_codes(code2[:, cols], ref2, L["alpha"], step_out, F2["D"], F2["R"], 2, step_out, None, None)
     layer.free()
 
 
