@@ -125,6 +125,13 @@ typedef double v8d __attribute__((ext_vector_type(8)));
 // the multiply-adds sit inside the indexed region; the mode is off again when the statement ends.
 // The wait is for everything (lgkmcnt(0)): scalar loads in flight share the counter and may return
 // out of order, so no smaller count would prove that the table reads are back.
+// The statement names physical registers (v[0:31], v[32:47], v33 ... v47) under a budget of 64: that holds only
+// as long as the compiler keeps nothing else live there, which the parity tests establish for one compiler.
+// Validated with AMD clang 22.0 (ROCm 7.2); another major version has to re-run the GPU parity tests before
+// this check is moved.
+#if !defined(__clang_major__) || __clang_major__ != 22
+#error "accumulate8 pins vector registers by name and was validated with AMD clang 22 (ROCm 7.2) only: re-run the GPU parity tests with this compiler, then update this check"
+#endif
 // The index mode rewrites M0, so M0 is on the clobber list: the compiler then keeps no M0-dependent
 // sequence of its own alive across the statement (it warns that M0 is a reserved register, which is the
 // point).
