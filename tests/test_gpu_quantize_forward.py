@@ -26,7 +26,11 @@ def b():
 # N <= 128 with 2-, 4- and 8-wave workgroups, ragged K and M, K below one word, a K too long for the
 # on-chip strip (falls back to two kernels), N > 128 (falls back), few columns with 8 waves (falls back)
 SHAPES = [(1, 1, 1), (5, 33, 3), (16, 64, 64), (30, 100, 65), (33, 257, 130), (64, 300, 700), (64, 576, 5000),
-          (70, 520, 129), (128, 1152, 30000), (100, 200, 24001), (128, 9000, 300), (130, 200, 70), (40, 7000, 100)]
+          (70, 520, 129), (128, 1152, 30000), (100, 200, 24001), (128, 9000, 300), (130, 200, 70), (40, 7000, 100),
+          # more than 512 strips of columns (several rounds of workgroups on the chip): an odd number of strips,
+          # ragged M and K, 8-, 4- and 2-wave row groups, and values of K whose strip takes 15 to 39 KB of LDS
+          (128, 1152, 32900), (64, 300, 40000), (20, 97, 33333), (128, 1500, 32800), (64, 1800, 32770),
+          (128, 2400, 32800)]
 
 
 @pytest.mark.parametrize("bits", [1, 2])
