@@ -316,16 +316,29 @@ def forward_requant(layer: dict, c: np.ndarray, step, bits_out: int, step_out, s
     return requant(layer["alpha"], step, D, R, bits_out, step_out, scale, shift)
 
 
-def im2col_codes(c_map: np.ndarray, B: int, H: int, W: int, bits: int) -> np.ndarray:
-    """Patch matrix [9*C, B*H*W] of a 3x3 convolution (stride 1, padding 1) over the integer activation
-    values of a feature map [C, B*H*W] (column = (b*H + y)*W + x).  Row tap*C + ch with tap = 3*ky + kx;
-    column (b, y, x) holds the value at (b, y + ky - 1, x + kx - 1), and outside the image the value
-    whose stored code is 0: 0 for 2-bit activations (zero padding), -1 for 1-bit ones."""
+def conv_out_size(H: int, stride: int) -> int:
+    """Output rows (or columns) of a 3-wide window with padding 1 moved in steps of `stride` over H inputs."""
+    return (H - 1) // stride + 1
+
+
+def im2col_codes(c_map: np.ndarray, B: int, H: int, W: int, bits: int, stride: int = 1) -> np.ndarray:
+    """Patch matrix [9*C, B*Ho*Wo] of a 3x3 convolution (padding 1, the given stride; Ho, Wo = conv_out_size)
+    over the integer activation values of a feature map [C, B*H*W] (column = (b*H + y)*W + x).  Row tap*C + ch
+    with tap = 3*ky + kx; output column (b, yo, xo) holds the value at (b, stride*yo + ky - 1, stride*xo + kx - 1),
+    and outside the image the value whose stored code is 0: 0 for 2-bit activations (zero padding), -1 for
+    1-bit ones."""
     C, P = c_map.shape
-    assert P == B * H * W
+    assert P == B * H * W and stride >= 1
+    Ho, Wo = conv_out_size(H, stride), conv_out_size(W, stride)
     padded = np.full((C, B, H + 2, W + 2), 0 if bits == 2 else -1, dtype=c_map.dtype)
     padded[:, :, 1:H + 1, 1:W + 1] = c_map.reshape(C, B, H, W)
-    return np.concatenate([padded[:, :, ky:ky + H, kx:kx + W].reshape(C, P) for ky in range(3) for kx in range(3)], axis=0)
+    taps = []
+    for ky in range(3):
+        for kx in range(3):
+            view = padded[:, :, ky:ky + stride * (Ho - 1) + 1:stride, kx:kx + stride * (Wo - 1) + 1:stride]
+            assert view.shape == (C, B, Ho, Wo)
+            taps.append(view.reshape(C, B * Ho * Wo))
+    return np.concatenate(taps, axis=0)
 
 
 def brute_force(W: np.ndarray, delta, alpha, X: np.ndarray, bits: int, step) -> np.ndarray:

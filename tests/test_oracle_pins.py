@@ -507,3 +507,38 @@ def test_im2col_forward_is_the_direct_convolution(bits):
             want = sum(correlate2d(xhat[ch, b_], dense[n, :, :, ch], mode="same", boundary="fill", fillvalue=fill)
                        for ch in range(C))
             assert np.allclose(Y[n, b_], want, rtol=1e-6, atol=1e-9)
+
+
+@pytest.mark.parametrize("bits", [1, 2])
+@pytest.mark.parametrize("stride,H,W", [(2, 5, 6), (2, 6, 7), (2, 1, 1), (3, 7, 5)])
+def test_strided_im2col_is_the_subsampled_direct_convolution(bits, stride, H, W):
+    """With a stride the product on im2col_codes is the textbook cross-correlation (scipy, full resolution,
+    padded with the value of code 0) read at every stride-th row and column; its centre tap is the map
+    subsampled the same way, and stride 1 is the unstrided matrix."""
+    from scipy.signal import correlate2d
+    r = np.random.default_rng(57 + 10 * bits + stride + H)
+    N, C, B = 3, 4, 2
+    Wt = (r.standard_normal((N, 9 * C)) * 0.05).astype(np.float32)
+    delta = np.float32(0.08)
+    step = np.float32(0.75 if bits == 2 else 0.5)
+    Xmap = r.standard_normal((C, B * H * W)).astype(np.float32)
+    if bits == 2:
+        Xmap = np.maximum(Xmap, 0)
+    L = o.compress(Wt, delta)
+    c_map = o.quantize(Xmap, bits, step)
+    Ho, Wo = o.conv_out_size(H, stride), o.conv_out_size(W, stride)
+    assert (Ho, Wo) == (len(range(0, H, stride)), len(range(0, W, stride)))
+    patches = o.im2col_codes(c_map, B, H, W, bits, stride)
+    assert patches.shape == (9 * C, B * Ho * Wo)
+    assert np.array_equal(o.im2col_codes(c_map, B, H, W, bits, 1), o.im2col_codes(c_map, B, H, W, bits))
+    centre = c_map.reshape(C, B, H, W)[:, :, ::stride, ::stride].reshape(C, B * Ho * Wo)
+    assert np.array_equal(patches[4 * C:5 * C], centre)
+    Y = o.forward(L, patches, step)["Y"].reshape(N, B, Ho, Wo)
+    dense = o.apb_dense(Wt, delta, L["alpha"]).reshape(N, 3, 3, C)
+    xhat = o.dequantize(c_map, step).reshape(C, B, H, W)
+    fill = 0.0 if bits == 2 else -float(step)
+    for n in range(N):
+        for b_ in range(B):
+            full = sum(correlate2d(xhat[ch, b_], dense[n, :, :, ch], mode="same", boundary="fill", fillvalue=fill)
+                       for ch in range(C))
+            assert np.allclose(Y[n, b_], full[::stride, ::stride], rtol=1e-6, atol=1e-9)
