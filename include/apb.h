@@ -180,26 +180,29 @@ int apb_forward_requant(const apb_layer* layer, const void* packed, int M, int b
                         const float* scale, const float* shift, int bits_out, float step_out, void* packed_out,
                         void* stream);
 
-/* A 3 x 3 convolution (stride 1, padding 1) as Eq. 13 on the im2col matrix (Sec. III, footnote on
+/* A 3 x 3 convolution (padding 1, stride 1 or 2) as Eq. 13 on the im2col matrix (Sec. III, footnote on
  * convolutions), without building that matrix: the activations are a packed FEATURE MAP and the
  * kernel reads the nine shifted views of it.
  *   layer   compressed from W [N][K = 9*C]: N output channels, k = tap*C + c with tap = 3*ky + kx
- *           (ky, kx in 0..2) and c the input channel; C must be a multiple of 64.
+ *           (ky, kx in 0..2) and c the input channel; C must be a multiple of 32.
  *   fmap    DEVICE, the packed buffer of the C x P code matrix of the input map (row = channel,
  *           column p = (b*H + y)*W + x, P = B*H*W): exactly what apb_quantize_acts writes for a
  *           C x P float matrix, or apb_forward_requant / apb_forward_conv3x3_requant of the layer
  *           before; apb_acts_bytes(C, P, bits) bytes.
+ *   stride  1 or 2.  The output map has Ho = (H - 1) / stride + 1 rows and Wo = (W - 1) / stride + 1 columns;
+ *           output pixel (b, yo, xo) sees the inputs (b, stride*yo + ky - 1, stride*xo + kx - 1).
  *   padding pixels outside the image have code 0: the value 0 for 2-bit activations, -step for 1-bit.
- *   Y       DEVICE, N*P floats, channel-major like the input map, fully overwritten.
+ *   Y       DEVICE, N*Po floats (Po = B*Ho*Wo), channel-major like the input map, fully overwritten.
  * The _requant form ends with the next layer's quantizer as apb_forward_requant does and writes the
- * packed output map (apb_acts_bytes(N, P, bits_out) bytes), which a following 3 x 3 layer with C = N
- * takes as its fmap.  APB_ERR_SHAPE if K is not 9*C with C % 64 == 0 and C <= 16384, or B*H*W >= 2^28.
+ * packed output map (apb_acts_bytes(N, Po, bits_out) bytes), which a following 3 x 3 layer with C = N and
+ * images of Ho x Wo pixels takes as its fmap.  APB_ERR_SHAPE if K is not 9*C with C % 32 == 0 and C <= 16384,
+ * if stride is neither 1 nor 2, if B*H*W >= 2^28 or if one bit-plane of the map reaches 2^31 bytes.
  * Asynchronous on `stream`. */
-int apb_forward_conv3x3(const apb_layer* layer, const void* fmap, int B, int H, int W, int bits, float step, float* Y,
-                        void* stream);
-int apb_forward_conv3x3_requant(const apb_layer* layer, const void* fmap, int B, int H, int W, int bits, float step,
-                                const float* scale, const float* shift, int bits_out, float step_out, void* fmap_out,
-                                void* stream);
+int apb_forward_conv3x3(const apb_layer* layer, const void* fmap, int B, int H, int W, int stride, int bits, float step,
+                        float* Y, void* stream);
+int apb_forward_conv3x3_requant(const apb_layer* layer, const void* fmap, int B, int H, int W, int stride, int bits,
+                                float step, const float* scale, const float* shift, int bits_out, float step_out,
+                                void* fmap_out, void* stream);
 
 /* Test hook: the integer part D (N*M int32, row-major, DEVICE) alone, computed by the stand-alone
  * matrix-core kernel (the same bit expansion and matrix instruction as apb_forward's first

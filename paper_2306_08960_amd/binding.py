@@ -77,9 +77,9 @@ def load() -> ctypes.CDLL:
     lib.apb_quantize_forward_is_one_kernel.restype = ci
     lib.apb_forward_requant.argtypes = [vp, vp, ci, ci, cf, vp, vp, ci, cf, vp, vp]
     lib.apb_forward_requant.restype = ci
-    lib.apb_forward_conv3x3.argtypes = [vp, vp, ci, ci, ci, ci, cf, vp, vp]
+    lib.apb_forward_conv3x3.argtypes = [vp, vp, ci, ci, ci, ci, ci, cf, vp, vp]
     lib.apb_forward_conv3x3.restype = ci
-    lib.apb_forward_conv3x3_requant.argtypes = [vp, vp, ci, ci, ci, ci, cf, vp, vp, ci, cf, vp, vp]
+    lib.apb_forward_conv3x3_requant.argtypes = [vp, vp, ci, ci, ci, ci, ci, cf, vp, vp, ci, cf, vp, vp]
     lib.apb_forward_conv3x3_requant.restype = ci
     lib.apb_forward_int.argtypes = [vp, vp, ci, ci, vp, vp]
     lib.apb_forward_int.restype = ci
@@ -318,27 +318,31 @@ def apb_forward_requant(layer: ApbLayer, packed: torch.Tensor, M: int, bits: int
     return packed_out
 
 
-def _check_fmap(layer: ApbLayer, fmap: torch.Tensor, B: int, H: int, W: int, bits: int) -> Tuple[int, int]:
+def _check_fmap(layer: ApbLayer, fmap: torch.Tensor, B: int, H: int, W: int, bits: int, stride: int) -> Tuple[int, int]:
+    """(N, output pixels B*Ho*Wo) after checking the size of the input map's buffer."""
     i = apb_layer_info(layer)
     if i["K"] % 9:
         raise ValueError("the layer's K is not 9 * C")
+    if stride not in (1, 2):
+        raise ValueError("stride must be 1 or 2")
     P = int(B) * int(H) * int(W)
     need = apb_acts_bytes(i["K"] // 9, P, bits)
     if need and fmap.numel() * fmap.element_size() < need:
         raise ValueError("fmap smaller than apb_acts_bytes(C, B*H*W, bits)")
-    return i["N"], P
+    return i["N"], int(B) * ((int(H) - 1) // stride + 1) * ((int(W) - 1) // stride + 1)
 
 
 def apb_forward_conv3x3(layer: ApbLayer, fmap: torch.Tensor, B: int, H: int, W: int, bits: int, step: float,
-                        Y: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
-    """3x3 convolution over a packed feature map [C, B*H*W]; Y is [N, B*H*W]."""
-    N, P = _check_fmap(layer, fmap, B, H, W, bits)
+                        Y: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None,
+                        stride: int = 1) -> torch.Tensor:
+    """3x3 convolution (padding 1) over a packed feature map [C, B*H*W]; Y is [N, B*Ho*Wo]."""
+    N, P = _check_fmap(layer, fmap, B, H, W, bits, stride)
     if Y is None:
         Y = torch.empty((N, P), dtype=torch.float32, device=fmap.device)
     elif tuple(Y.shape) != (N, P):
-        raise ValueError("Y must be [N, B*H*W]")
-    _check(load().apb_forward_conv3x3(layer.handle, _dev_ptr(fmap, torch.int32, "fmap"), int(B), int(H), int(W), int(bits),
-                                      float(step), _dev_ptr(Y, torch.float32, "Y"), _stream(stream)),
+        raise ValueError("Y must be [N, B*Ho*Wo]")
+    _check(load().apb_forward_conv3x3(layer.handle, _dev_ptr(fmap, torch.int32, "fmap"), int(B), int(H), int(W), int(stride),
+                                      int(bits), float(step), _dev_ptr(Y, torch.float32, "Y"), _stream(stream)),
            "apb_forward_conv3x3")
     return Y
 
@@ -346,8 +350,8 @@ def apb_forward_conv3x3(layer: ApbLayer, fmap: torch.Tensor, B: int, H: int, W: 
 def apb_forward_conv3x3_requant(layer: ApbLayer, fmap: torch.Tensor, B: int, H: int, W: int, bits: int, step: float,
                                 bits_out: int, step_out: float, scale: Optional[torch.Tensor] = None,
                                 shift: Optional[torch.Tensor] = None, fmap_out: Optional[torch.Tensor] = None,
-                                stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
-    N, P = _check_fmap(layer, fmap, B, H, W, bits)
+                                stream: Optional[torch.cuda.Stream] = None, stride: int = 1) -> torch.Tensor:
+    N, P = _check_fmap(layer, fmap, B, H, W, bits, stride)
     if (scale is None) != (shift is None):
         raise ValueError("scale and shift go together")
     for name, t in (("scale", scale), ("shift", shift)):
@@ -356,9 +360,9 @@ def apb_forward_conv3x3_requant(layer: ApbLayer, fmap: torch.Tensor, B: int, H: 
     if fmap_out is None:
         fmap_out = alloc_packed(N, P, bits_out, fmap.device)
     elif fmap_out.numel() * fmap_out.element_size() < apb_acts_bytes(N, P, bits_out):
-        raise ValueError("fmap_out smaller than apb_acts_bytes(N, B*H*W, bits_out)")
+        raise ValueError("fmap_out smaller than apb_acts_bytes(N, B*Ho*Wo, bits_out)")
     _check(load().apb_forward_conv3x3_requant(
-        layer.handle, _dev_ptr(fmap, torch.int32, "fmap"), int(B), int(H), int(W), int(bits), float(step),
+        layer.handle, _dev_ptr(fmap, torch.int32, "fmap"), int(B), int(H), int(W), int(stride), int(bits), float(step),
         None if scale is None else _dev_ptr(scale, torch.float32, "scale"),
         None if shift is None else _dev_ptr(shift, torch.float32, "shift"), int(bits_out), float(step_out),
         _dev_ptr(fmap_out, torch.int32, "fmap_out"), _stream(stream)), "apb_forward_conv3x3_requant")

@@ -438,47 +438,52 @@ int apb_quantize_forward(const apb_layer* layer, const float* X, int M, int bits
                                                    M, bits, step, Y, s);
 }
 
-// Shape checks shared by the two convolution entry points; fills `conv` and the pixel count.
-static int conv_shape(const LayerDev& d, int B, int H, int W, ConvShape& conv, int& P) {
-    if (B <= 0 || H <= 0 || W <= 0 || d.K % 9 != 0 || (d.K / 9) % 64 != 0) return APB_ERR_SHAPE;
+// Shape checks shared by the two convolution entry points; fills `conv` and the output pixel count.
+static int conv_shape(const LayerDev& d, int B, int H, int W, int stride, ConvShape& conv, int& P_out) {
+    if (B <= 0 || H <= 0 || W <= 0 || (stride != 1 && stride != 2)) return APB_ERR_SHAPE;
+    if (d.K % 9 != 0 || (d.K / 9) % 32 != 0) return APB_ERR_SHAPE;
     if (d.K / 9 > 16384) return APB_ERR_SHAPE;                 // the kernels' row -> tap arithmetic is exact up to here
     const long long pixels = (long long)B * H * W;
-    if (pixels >= (1LL << 28) || (long long)d.N * pixels >= (1LL << 40)) return APB_ERR_SHAPE;
-    conv = ConvShape{d.K / 9, H, W};
-    P = (int)pixels;
+    if (pixels >= (1LL << 28)) return APB_ERR_SHAPE;
+    const long long Pp_in = kWave * ((pixels + kWave - 1) / kWave);
+    // a plane of the map is one buffer range of the kernels' loads: below 2^31 bytes
+    if ((long long)(d.K / 9 / 32) * Pp_in * 4 >= (1LL << 31)) return APB_ERR_SHAPE;
+    const int Ho = (H - 1) / stride + 1, Wo = (W - 1) / stride + 1;
+    const long long out_pixels = (long long)B * Ho * Wo;
+    if ((long long)d.N * out_pixels >= (1LL << 40)) return APB_ERR_SHAPE;
+    conv = ConvShape{d.K / 9, H, W, stride, Ho, Wo, (int)Pp_in};
+    P_out = (int)out_pixels;
     return APB_OK;
 }
 
-int apb_forward_conv3x3(const apb_layer* layer, const void* fmap, int B, int H, int W, int bits, float step, float* Y,
-                        void* stream) {
+int apb_forward_conv3x3(const apb_layer* layer, const void* fmap, int B, int H, int W, int stride, int bits, float step,
+                        float* Y, void* stream) {
     if (!layer || !fmap || !Y) return APB_ERR_NULL;
     const LayerDev& d = layer->d;
     ConvShape conv;
     int P;
-    const int rc = conv_shape(d, B, H, W, conv, P);
+    const int rc = conv_shape(d, B, H, W, stride, conv, P);
     if (rc != APB_OK) return rc;
     if (bits != 1 && bits != 2) return APB_ERR_BITS;
     if (!std::isfinite(step) || !(step > 0.0f)) return APB_ERR_VALUE;
-    const size_t Pp = (size_t)kWave * (((size_t)P + kWave - 1) / kWave);
     const uint32_t* planes = static_cast<const uint32_t*>(fmap);
-    const int32_t* pixsum = reinterpret_cast<const int32_t*>(planes + (size_t)bits * (conv.C / 32) * Pp);
+    const int32_t* pixsum = reinterpret_cast<const int32_t*>(planes + (size_t)bits * (conv.C / 32) * conv.Pp_in);
     return launch_forward(d, planes, pixsum, P, bits, step, &conv, Y, as_stream(stream));
 }
 
-int apb_forward_conv3x3_requant(const apb_layer* layer, const void* fmap, int B, int H, int W, int bits, float step,
-                                const float* scale, const float* shift, int bits_out, float step_out, void* fmap_out,
-                                void* stream) {
+int apb_forward_conv3x3_requant(const apb_layer* layer, const void* fmap, int B, int H, int W, int stride, int bits,
+                                float step, const float* scale, const float* shift, int bits_out, float step_out,
+                                void* fmap_out, void* stream) {
     if (!layer || !fmap || !fmap_out || (scale == nullptr) != (shift == nullptr)) return APB_ERR_NULL;
     const LayerDev& d = layer->d;
     ConvShape conv;
     int P;
-    int rc = conv_shape(d, B, H, W, conv, P);
+    int rc = conv_shape(d, B, H, W, stride, conv, P);
     if (rc != APB_OK) return rc;
     if ((bits != 1 && bits != 2) || (bits_out != 1 && bits_out != 2)) return APB_ERR_BITS;
     if (!std::isfinite(step) || !(step > 0.0f) || !std::isfinite(step_out) || !(step_out > 0.0f)) return APB_ERR_VALUE;
-    const size_t Pp = (size_t)kWave * (((size_t)P + kWave - 1) / kWave);
     const uint32_t* planes = static_cast<const uint32_t*>(fmap);
-    const int32_t* pixsum = reinterpret_cast<const int32_t*>(planes + (size_t)bits * (conv.C / 32) * Pp);
+    const int32_t* pixsum = reinterpret_cast<const int32_t*>(planes + (size_t)bits * (conv.C / 32) * conv.Pp_in);
     hipStream_t s = as_stream(stream);
     uint32_t* out = static_cast<uint32_t*>(fmap_out);
     return launch_forward_requant(d, planes, pixsum, P, bits, step, &conv, scale, shift, bits_out, 1.0f / step_out, out, s);

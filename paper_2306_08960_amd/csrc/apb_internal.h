@@ -112,10 +112,12 @@ int launch_forward_popcount(const LayerDev& L, const uint32_t* planes, const int
                             float step, float* Y, int32_t* D, hipStream_t s);
 // the forward kernel: binary part on the matrix cores, residual part and epilogue, one launch.
 // conv == nullptr: `planes` is the packed K x M matrix; otherwise a packed feature map of conv->C channels
-// (L.K = 9 * C, C a multiple of 64) with M = B * H * W pixels, read through an implicit im2col (3 x 3,
-// stride 1, padding 1).
+// (L.K = 9 * C, C a multiple of 32) of images of H x W pixels, read through an implicit im2col (3 x 3,
+// padding 1, the given stride), and M = B * Ho * Wo output pixels.
 struct ConvShape {
     int C, H, W;
+    int stride, Ho, Wo;            // Ho = (H - 1) / stride + 1, Wo likewise
+    int Pp_in;                     // B * H * W rounded up to a multiple of 64: columns of the packed input map
 };
 int launch_forward(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                    const ConvShape* conv, float* Y, hipStream_t s);

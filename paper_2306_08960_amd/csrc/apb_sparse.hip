@@ -53,20 +53,26 @@ struct SparseParams {
     int out_exclusive;                       // packed output: the workgroup holds ALL rows of its columns
     int out_Kw;                              // ceil(N / 32), words per column of a packed output plane
     float out_inv_step;                      // 1 / step of the 2-bit output quantizer
-    // Implicit im2col (CONV kernels): the activations are a packed feature map [bits][Cw][Mp] (+ per-pixel
-    // code sums), a column m is the pixel (b, y, x) = (m / (H*W), (m / W) % H, m % W), and word row
-    // j = tap * Cw + cw of the patch matrix is word row cw of the map at the pixel shifted by tap
+    // Implicit im2col (CONV kernels): the activations are a packed feature map [bits][Cw][conv_Mp] (+ per-pixel
+    // code sums) of B images of H x W pixels; a column m is the OUTPUT pixel (b, yo, xo) = (m / (Ho*Wo),
+    // (m / Wo) % Ho, m % Wo), its window is centred on the input pixel (b, stride*yo, stride*xo), and word row
+    // j = tap * Cw + cw of the patch matrix is word row cw of the map at that pixel shifted by tap
     // (dy, dx) = (tap / 3 - 1, tap % 3 - 1), or zero outside the image.
-    int conv_Cw, conv_H, conv_W;
+    int conv_Cw, conv_H, conv_W, conv_Ho, conv_Wo, conv_stride;
+    int conv_Mp;                             // columns of the input map, padded as its packed buffer is
     float conv_inv_Cw;
     // Float activations (FX kernels): K rows of X and 1 / step of the input quantizer.
     int K;
     float in_inv_step;
 };
 
-// Bit t of the result: tap t of pixel m lies inside the image (never for columns >= M).
-__device__ __forceinline__ uint32_t tap_mask(int m, const SparseParams& p) {
-    const int x = m % p.conv_W, y = (m / p.conv_W) % p.conv_H;
+// Output column m of a convolution: returns the tap mask (bit t: tap t of its window lies inside the image;
+// none for columns >= M) and sets `pin`, the column of the window's centre in the input map.
+__device__ __forceinline__ uint32_t conv_pixel(int m, const SparseParams& p, int& pin) {
+    const int xo = m % p.conv_Wo, rest = m / p.conv_Wo;
+    const int yo = rest % p.conv_Ho, img = rest / p.conv_Ho;
+    const int x = p.conv_stride * xo, y = p.conv_stride * yo;
+    pin = m < p.M ? (img * p.conv_H + y) * p.conv_W + x : 0;
     uint32_t vm = 0;
 #pragma unroll
     for (int t = 0; t < 9; ++t) {
@@ -83,10 +89,11 @@ __device__ __forceinline__ int tap_shift(int tap, int W) {
     return (t3 - 1) * W + (tap - 3 * t3 - 1);
 }
 
-// A lane's byte offset into a row of the map for tap `tap`: its shifted pixel, or an offset beyond any
-// buffer range (a buffer load out of range returns zero: that is the zero padding).
-__device__ __forceinline__ int tap_offset(uint32_t vm, int tap, int m, int shift) {
-    return ((vm >> tap) & 1u) ? (m + shift) * 4 : (int)0x80000000u;
+// A lane's byte offset into the map for tap `tap`: the word at `at` (row base + centre pixel) shifted by the
+// tap, or an offset beyond any buffer range (a buffer load out of range returns zero: that is the zero
+// padding).  Ranges stay below 2^31 bytes (checked by the entry points).
+__device__ __forceinline__ int tap_offset(uint32_t vm, int tap, int at, int shift) {
+    return ((vm >> tap) & 1u) ? (at + shift) * 4 : (int)0x80000000u;
 }
 
 // Spread the 4 low bits of `nib` to the least significant bits of the 4 bytes of a word.
@@ -204,21 +211,21 @@ __device__ __forceinline__ void batch(v16d& acc, v8d& pairs, const uint32_t* __r
 // reads one activation row past its plane -- still inside the packed buffer (the next plane, or the
 // column sums) and multiplied by zero weights.  Words are fetched four steps ahead.
 // CONV: the activation words come from a packed feature map through the implicit im2col (see
-// SparseParams); vm is the tap mask of this lane's column m_base + 32*tm + (lane & 31).  Cw is even, so
-// the two word rows of a step belong to the same tap.
+// SparseParams); vm and pin are the tap mask and the input-map column of this lane's column
+// m_base + 32*tm + (lane & 31).  The two word rows of a step may belong to different taps (odd Cw).
 // FX: the activation words of the workgroup's 64 columns sit in LDS (`lplanes`, [BITS][Kw rounded up to
 // even][64], written by quantize_strip).
 template <int BITS, bool CONV, bool FX = false>
 __device__ __forceinline__ void binary_tile_to_lds(const uint32_t* __restrict__ signT,
                                                    const uint32_t* __restrict__ planes, int Np, int Kw, int Mp,
                                                    int slot_base, int m_base, int tn, int tm, int s_begin, int s_end,
-                                                   int lane, int32_t* tile, const SparseParams& p, uint32_t vm,
+                                                   int lane, int32_t* tile, const SparseParams& p, uint32_t vm, int pin,
                                                    const uint32_t* lplanes = nullptr) {
     const int i = lane & 31, g = lane >> 5;
     const unsigned aoff = (unsigned)(g * Np + slot_base + 32 * tn + i);
     const unsigned boff = (unsigned)(g * Mp + m_base + 32 * tm + i);
-    const size_t plane_stride = (size_t)(CONV ? p.conv_Cw : Kw) * Mp;
-    // running (tap, word row of the map) of the next step to be loaded
+    const size_t plane_stride = CONV ? (size_t)p.conv_Cw * p.conv_Mp : (size_t)Kw * Mp;
+    // running (tap, word row of the map) of the first word row of the next step to be loaded
     int ld_tap = 0, ld_cw = 0;
     if (CONV) {
         ld_tap = tap_of_row(2 * s_begin, p);
@@ -241,19 +248,22 @@ __device__ __forceinline__ void binary_tile_to_lds(const uint32_t* __restrict__ 
 #pragma unroll
             for (int pl = 0; pl < BITS; ++pl) b[pl][0] = (planes + pl * plane_stride + (size_t)(2 * ss) * Mp)[boff];
         } else {
-            // rows ld_cw (lower lane half) and ld_cw + 1 of the map, shifted by the tap; past the last
-            // step the tap runs past 8, whose mask bits are clear: zeros, never used
-            const int off = tap_offset(vm, ld_tap, (int)boff, tap_shift(ld_tap, p.conv_W));
+            // word row ld_cw of the map under tap ld_tap (lower lane half) and the word row after it (upper half:
+            // the next tap's first row where ld_cw is the last of an odd Cw), each shifted by its tap; past the
+            // last step the tap runs past 8, whose mask bits are clear: zeros, never used
+            const bool wrap = ld_cw + 1 >= p.conv_Cw;
+            const int my_tap = g ? ld_tap + (wrap ? 1 : 0) : ld_tap;
+            const int my_cw = g ? (wrap ? 0 : ld_cw + 1) : ld_cw;
+            const int off = tap_offset(vm, my_tap, my_cw * p.conv_Mp + pin, tap_shift(my_tap, p.conv_W));
 #pragma unroll
             for (int pl = 0; pl < BITS; ++pl) {
-                const uint32_t* rows = planes + (pl * plane_stride + (size_t)ld_cw * Mp);
-                const __amdgpu_buffer_rsrc_t rsrc =
-                    __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(rows), 0, 2 * Mp * 4, kBufferFlags);
+                const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                    const_cast<uint32_t*>(planes + pl * plane_stride), 0, p.conv_Cw * p.conv_Mp * 4, kBufferFlags);
                 b[pl][0] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, off, 0, 0);
             }
             ld_cw += 2;
-            if (ld_cw >= p.conv_Cw) {
-                ld_cw = 0;
+            while (ld_cw >= p.conv_Cw) {                        // (twice for Cw = 1)
+                ld_cw -= p.conv_Cw;
                 ++ld_tap;
             }
         }
@@ -377,15 +387,15 @@ __device__ __forceinline__ void write_rows(const v16d& acc, int slot0, int m, co
 // Sum of the codes of column m: read as it stands, or (CONV) added up over the taps of the patch from
 // the per-pixel sums of the feature map.
 template <bool CONV>
-__device__ __forceinline__ int column_code_sum(const int32_t* __restrict__ colsum, int m, uint32_t vm,
+__device__ __forceinline__ int column_code_sum(const int32_t* __restrict__ colsum, int m, uint32_t vm, int pin,
                                                const SparseParams& p) {
     if (!CONV) return colsum[m];
     const __amdgpu_buffer_rsrc_t rsrc =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(colsum), 0, p.Mp * 4, kBufferFlags);
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(colsum), 0, p.conv_Mp * 4, kBufferFlags);
     int cs = 0;
 #pragma unroll
     for (int t = 0; t < 9; ++t)
-        cs += (int)__builtin_amdgcn_raw_buffer_load_b32(rsrc, tap_offset(vm, t, m, tap_shift(t, p.conv_W)), 0, 0);
+        cs += (int)__builtin_amdgcn_raw_buffer_load_b32(rsrc, tap_offset(vm, t, pin, tap_shift(t, p.conv_W)), 0, 0);
     return cs;
 }
 
@@ -396,7 +406,7 @@ __device__ __forceinline__ int column_code_sum(const int32_t* __restrict__ colsu
 // so that the wait for it can sit at the next chunk.
 template <bool CONV>
 __device__ __forceinline__ uint32_t load_act_word(const uint32_t* __restrict__ planes, size_t plane_stride, int b, int j,
-                                                  int m_off, uint32_t vm, const SparseParams& p) {
+                                                  int m_off, uint32_t vm, int pin, const SparseParams& p) {
     if (!CONV) {
         const uint32_t* row = planes + (b * plane_stride + (size_t)min(j, p.Kw - 1) * p.Mp);
         const __amdgpu_buffer_rsrc_t rsrc =
@@ -405,10 +415,10 @@ __device__ __forceinline__ uint32_t load_act_word(const uint32_t* __restrict__ p
     }
     const int tap = tap_of_row(j, p);
     const int cw = j - tap * p.conv_Cw;
-    const uint32_t* row = planes + (b * plane_stride + (size_t)cw * p.Mp);
+    const uint32_t* row = planes + (b * plane_stride + (size_t)cw * p.conv_Mp);
     const __amdgpu_buffer_rsrc_t rsrc =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(row), 0, p.Mp * 4, kBufferFlags);
-    return __builtin_amdgcn_raw_buffer_load_b32(rsrc, tap_offset(vm, tap, m_off >> 2, tap_shift(tap, p.conv_W)), 0, 0);
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(row), 0, p.conv_Mp * 4, kBufferFlags);
+    return __builtin_amdgcn_raw_buffer_load_b32(rsrc, tap_offset(vm, tap, pin, tap_shift(tap, p.conv_W)), 0, 0);
 }
 
 // FX kernels, phase 0: quantize the workgroup's strip of 64 columns of the float matrix X (K x M,
@@ -492,7 +502,8 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
 
     static_assert(TN == 16, "row field of an entry key addresses 16 register pairs");
     static_assert(!(CONV && FX), "float input goes with the plain matrix form");
-    const uint32_t vm = CONV ? tap_mask(m, p) : 0u;
+    int pin = 0;                                                // CONV: the lane's column in the input map
+    const uint32_t vm = CONV ? conv_pixel(m, p, pin) : 0u;
     uint32_t* lplanes = reinterpret_cast<uint32_t*>(lds + kBufs * kTableBytes);      // FX only
     int32_t* lcol = reinterpret_cast<int32_t*>(lplanes + BITS * (2 * ((p.Kw + 1) / 2)) * kWave);
     if (FX) quantize_strip<BITS>(reinterpret_cast<const float*>(planes), p, m, wave, waves, lane, lplanes, lcol);
@@ -506,14 +517,15 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
         // (the binary tile's column of a lane is column 32 * (wave & 1) + (lane & 31) of the strip: its mask
         // is that lane's)
         const uint32_t vm_tile = CONV ? (uint32_t)__shfl((int)vm, 32 * (wave & 1) + (lane & 31)) : 0u;
+        const int pin_tile = CONV ? __shfl(pin, 32 * (wave & 1) + (lane & 31)) : 0;
         binary_tile_to_lds<BITS, CONV, FX>(signT, planes, p.Np, p.Kw, p.Mp, rg * waves * TN, strip * kWave, wave >> 1,
-                                           wave & 1, 0, (p.Kw + 1) / 2, lane, tile_lds, p, vm_tile, lplanes);
+                                           wave & 1, 0, (p.Kw + 1) / 2, lane, tile_lds, p, vm_tile, pin_tile, lplanes);
         __syncthreads();
         int P[TN];
 #pragma unroll
         for (int r = 0; r < TN; ++r) P[r] = tile_lds[(wave * TN + r) * kWave + lane];
         __syncthreads();
-        const int cs = FX ? lcol[lane] : column_code_sum<CONV>(colsum, m, vm, p);
+        const int cs = FX ? lcol[lane] : column_code_sum<CONV>(colsum, m, vm, pin, p);
         const double a0 = p.alpha * (BITS == 1 ? 0.5 : 1.0) * (1.0 / kSumUnscale);
 #pragma unroll
         for (int r = 0; r < TN; ++r) {
@@ -526,7 +538,7 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
 #pragma unroll
     for (int r = 0; r < 8; ++r) pairs[r] = 0.0;
 
-    const size_t plane_stride = (size_t)(CONV ? p.conv_Cw : p.Kw) * p.Mp;
+    const size_t plane_stride = CONV ? (size_t)p.conv_Cw * p.conv_Mp : (size_t)p.Kw * p.Mp;
     uint8_t* my_row = lds + lane * kTablePitch;
     const uint32_t my_row_off = (uint32_t)(uintptr_t)(lds_u8*)my_row;   // the same row as an LDS byte address
     const int32_t* seg = seg_ptr + (size_t)tile * (p.nchunks + 1);
@@ -541,7 +553,7 @@ __global__ __launch_bounds__(kWave* kChunkWords / WPW) __attribute__((amdgpu_wav
 #pragma unroll
             for (int b = 0; b < BITS; ++b)
                 xw[b][i] = FX ? lplanes[(b * (2 * ((p.Kw + 1) / 2)) + min(j, p.Kw - 1)) * kWave + lane]
-                              : load_act_word<CONV>(planes, plane_stride, b, j, m_off, vm, p);
+                              : load_act_word<CONV>(planes, plane_stride, b, j, m_off, vm, pin, p);
         }
     };
     fetch(0);
@@ -608,7 +620,8 @@ __global__ __launch_bounds__(kWave* kChunkWords) __attribute__((amdgpu_waves_per
     const int m = strip * kWave + lane;
     const int m_off = m * 4;
     const int H = (p.nchunks + KS - 1) / KS;
-    const uint32_t vm = CONV ? tap_mask(m, p) : 0u;
+    int pin = 0;                                                // CONV: the lane's column in the input map
+    const uint32_t vm = CONV ? conv_pixel(m, p, pin) : 0u;
 
     // binary part: wave (tl, kp) computes 32 x 32 tile tl of the workgroup's 16*TW x 64 block over
     // its share of the K steps
@@ -618,8 +631,9 @@ __global__ __launch_bounds__(kWave* kChunkWords) __attribute__((amdgpu_waves_per
         const int SP = (steps + KS - 1) / KS;
         const int s_begin = min(steps, kp * SP), s_end = min(steps, s_begin + SP);
         const uint32_t vm_tile = CONV ? (uint32_t)__shfl((int)vm, 32 * (tl & 1) + (lane & 31)) : 0u;
+        const int pin_tile = CONV ? __shfl(pin, 32 * (tl & 1) + (lane & 31)) : 0;
         binary_tile_to_lds<BITS, CONV>(signT, planes, p.Np, p.Kw, p.Mp, rg * TW * TN, strip * kWave, tl >> 1, tl & 1,
-                                       s_begin, s_end, lane, part_lds + kp * (TN * TW * kWave), p, vm_tile);
+                                       s_begin, s_end, lane, part_lds + kp * (TN * TW * kWave), p, vm_tile, pin_tile);
     }
     __syncthreads();
     v16d acc;
@@ -631,7 +645,7 @@ __global__ __launch_bounds__(kWave* kChunkWords) __attribute__((amdgpu_waves_per
 #pragma unroll
             for (int q = 0; q < KS; ++q) P[r] += part_lds[q * (TN * TW * kWave) + (tl * TN + r) * kWave + lane];
         }
-        const int cs = column_code_sum<CONV>(colsum, m, vm, p);
+        const int cs = column_code_sum<CONV>(colsum, m, vm, pin, p);
         const double a0 = p.alpha * (BITS == 1 ? 0.5 : 1.0) * (1.0 / kSumUnscale);
 #pragma unroll
         for (int r = 0; r < TN; ++r) {
@@ -648,7 +662,7 @@ __global__ __launch_bounds__(kWave* kChunkWords) __attribute__((amdgpu_waves_per
     for (int r = 0; r < 8; ++r) pairs[r] = 0.0;
     __syncthreads();                                            // the partial products are read; tables may overwrite them
 
-    const size_t plane_stride = (size_t)(CONV ? p.conv_Cw : p.Kw) * p.Mp;
+    const size_t plane_stride = CONV ? (size_t)p.conv_Cw * p.conv_Mp : (size_t)p.Kw * p.Mp;
     uint8_t* my_row = lds + lane * kTablePitch;
     const uint32_t my_row_off = (uint32_t)(uintptr_t)(lds_u8*)my_row;
     const int32_t* seg = seg_ptr + (size_t)tile * (p.nchunks + 1);
@@ -660,7 +674,7 @@ __global__ __launch_bounds__(kWave* kChunkWords) __attribute__((amdgpu_waves_per
         for (int q = 0; q < KS; ++q) {
             const int j = (q * H + i) * kChunkWords + wave;
 #pragma unroll
-            for (int b = 0; b < BITS; ++b) xw[b][q] = load_act_word<CONV>(planes, plane_stride, b, j, m_off, vm, p);
+            for (int b = 0; b < BITS; ++b) xw[b][q] = load_act_word<CONV>(planes, plane_stride, b, j, m_off, vm, pin, p);
         }
     };
     fetch(0);
@@ -824,6 +838,10 @@ int launch_any(const LayerDev& L, const uint32_t* planes, const int32_t* colsum,
     p.conv_Cw = conv ? conv->C / 32 : 0;
     p.conv_H = conv ? conv->H : 0;
     p.conv_W = conv ? conv->W : 0;
+    p.conv_Ho = conv ? conv->Ho : 1;
+    p.conv_Wo = conv ? conv->Wo : 1;
+    p.conv_stride = conv ? conv->stride : 1;
+    p.conv_Mp = conv ? conv->Pp_in : 0;
     p.conv_inv_Cw = conv ? 1.0f / (float)(conv->C / 32) : 0.0f;
     p.K = L.K;
     p.in_inv_step = 1.0f / step;

@@ -39,34 +39,43 @@ def make_case(seed, N, C, B, H, W, bits, rho=0.03):
     return Wt, delta, Xmap, step
 
 
-def torch_im2col(Xmap_d, C, B, H, W, pad_value):
-    """Explicit float im2col [9*C, B*H*W] on the GPU (plain torch indexing; test-side only)."""
+def torch_im2col(Xmap_d, C, B, H, W, pad_value, stride=1):
+    """Explicit float im2col [9*C, B*Ho*Wo] on the GPU (plain torch indexing; test-side only)."""
     x = torch.full((C, B, H + 2, W + 2), pad_value, dtype=torch.float32, device=Xmap_d.device)
     x[:, :, 1:H + 1, 1:W + 1] = Xmap_d.view(C, B, H, W)
-    return torch.cat([x[:, :, ky:ky + H, kx:kx + W].reshape(C, B * H * W) for ky in range(3) for kx in range(3)], dim=0)
+    Ho, Wo = (H - 1) // stride + 1, (W - 1) // stride + 1
+    return torch.cat([x[:, :, ky:ky + stride * (Ho - 1) + 1:stride, kx:kx + stride * (Wo - 1) + 1:stride].reshape(C, B * Ho * Wo)
+                      for ky in range(3) for kx in range(3)], dim=0)
 
 
-SHAPES = [  # N, C, B, H, W
-    (20, 64, 2, 5, 7), (64, 64, 3, 8, 8), (130, 128, 1, 9, 13), (256, 64, 5, 8, 8), (40, 64, 1, 1, 1),
-    (33, 64, 1, 1, 70), (17, 64, 2, 66, 1), (512, 192, 1, 7, 7), (64, 64, 1, 32, 32),
+SHAPES = [  # N, C, B, H, W, stride
+    (20, 64, 2, 5, 7, 1), (64, 64, 3, 8, 8, 1), (130, 128, 1, 9, 13, 1), (256, 64, 5, 8, 8, 1), (40, 64, 1, 1, 1, 1),
+    (33, 64, 1, 1, 70, 1), (17, 64, 2, 66, 1, 1), (512, 192, 1, 7, 7, 1), (64, 64, 1, 32, 32, 1),
+    # channel counts that are odd multiples of 32 (a matrix step then straddles two taps), down to one word
+    (24, 32, 2, 6, 5, 1), (64, 96, 1, 9, 9, 1), (130, 160, 2, 7, 7, 1), (256, 32, 3, 8, 8, 1),
+    # stride 2: even and odd image sizes, one-pixel images, few output pixels (K split inside the workgroup)
+    (64, 64, 3, 8, 8, 2), (20, 64, 2, 5, 7, 2), (130, 128, 1, 9, 13, 2), (40, 64, 1, 1, 1, 2), (33, 32, 1, 2, 70, 2),
+    (128, 64, 2, 16, 16, 2), (256, 96, 5, 15, 14, 2), (512, 160, 1, 7, 7, 2), (64, 64, 1, 32, 31, 2),
 ]
 
 
 @pytest.mark.parametrize("bits", [2, 1])
-@pytest.mark.parametrize("N,C,B,H,W", SHAPES)
-def test_conv_matches_oracle(b, N, C, B, H, W, bits):
-    print(f"[case] conv N={N} C={C} B={B} H={H} W={W} bits={bits}", flush=True)
+@pytest.mark.parametrize("N,C,B,H,W,stride", SHAPES)
+def test_conv_matches_oracle(b, N, C, B, H, W, stride, bits):
+    print(f"[case] conv N={N} C={C} B={B} H={H} W={W} stride={stride} bits={bits}", flush=True)
     Wt, delta, Xmap, step = make_case(N + C + H * W, N, C, B, H, W, bits)
-    P = B * H * W
+    Ho, Wo = o.conv_out_size(H, stride), o.conv_out_size(W, stride)
+    P = B * Ho * Wo                                            # output pixels
     L = o.compress(Wt, delta)
     c_map = o.quantize(Xmap, bits, step)
-    patches = o.im2col_codes(c_map, B, H, W, bits)
+    patches = o.im2col_codes(c_map, B, H, W, bits, stride)
     F = capi.forward(L, o.pack_acts(patches, bits), patches, bits, step, threads=THREADS)
 
     layer = b.apb_compress(torch.from_numpy(Wt).cuda(), float(delta), alpha=float(L["alpha"]))
     fmap = b.apb_quantize_acts(torch.from_numpy(Xmap).cuda(), bits, float(step))
     assert np.array_equal(fmap.cpu().numpy().view(np.uint32), o.pack_acts(c_map, bits))
-    Y = b.apb_forward_conv3x3(layer, fmap, B, H, W, bits, float(step)).cpu().numpy()
+    Y = b.apb_forward_conv3x3(layer, fmap, B, H, W, bits, float(step), stride=stride).cpu().numpy()
+    assert Y.shape == (N, P)
     ref = F["Y"].astype(np.float64)
     assert np.all(np.abs(Y.astype(np.float64) - ref) <= REL_TOL * np.abs(ref))
 
@@ -81,19 +90,20 @@ def test_conv_matches_oracle(b, N, C, B, H, W, bits):
         out.fill_(-1)
         b.apb_forward_conv3x3_requant(layer, fmap, B, H, W, bits, float(step), 2, float(step_out),
                                       None if sc is None else torch.from_numpy(sc).cuda(),
-                                      None if sh is None else torch.from_numpy(sh).cuda(), fmap_out=out)
+                                      None if sh is None else torch.from_numpy(sh).cuda(), fmap_out=out, stride=stride)
         torch.cuda.synchronize()
         code, pixsum = unpack(out.cpu().numpy().view(np.uint32), N, P, 2)
         assert np.array_equal(pixsum[:P], code.sum(axis=0))
         compare_codes(code, want, L["alpha"], step, F["D"], F["R"], 2, step_out, sc, sh)
-    if N % 64 == 0:
+    if N % 32 == 0:
+        # (the output map is B images of Ho x Wo pixels; the second layer runs on it with stride 1)
         W2, delta2, _, _ = synth.random_case(N + 1, 24, 9 * N, 1, 2, rho=0.02)
         L2 = o.compress(W2, delta2)
         c2 = code.astype(np.int8)
-        patches2 = o.im2col_codes(c2, B, H, W, 2)
+        patches2 = o.im2col_codes(c2, B, Ho, Wo, 2)
         F2 = capi.forward(L2, o.pack_acts(patches2, 2), patches2, 2, step_out, threads=THREADS)
         layer2 = b.apb_compress(torch.from_numpy(W2).cuda(), float(delta2), alpha=float(L2["alpha"]))
-        Y2 = b.apb_forward_conv3x3(layer2, out, B, H, W, 2, float(step_out)).cpu().numpy()
+        Y2 = b.apb_forward_conv3x3(layer2, out, B, Ho, Wo, 2, float(step_out)).cpu().numpy()
         ref2 = F2["Y"].astype(np.float64)
         assert np.all(np.abs(Y2.astype(np.float64) - ref2) <= REL_TOL * np.abs(ref2))
         layer2.free()
@@ -101,12 +111,21 @@ def test_conv_matches_oracle(b, N, C, B, H, W, bits):
 
 
 def test_shape_errors(b):
-    Wt, delta, _, _ = synth.random_case(3, 8, 9 * 32, 1, 2)              # C = 32: not a multiple of 64
+    Wt, delta, _, _ = synth.random_case(3, 8, 9 * 16, 1, 2)              # C = 16: not a multiple of 32
     layer = b.apb_compress(torch.from_numpy(Wt).cuda(), float(delta))
-    fmap = b.alloc_packed(32, 16, 2)
+    fmap = b.alloc_packed(16, 16, 2)
     with pytest.raises(b.ApbError) as e:
         b.apb_forward_conv3x3(layer, fmap, 1, 4, 4, 2, 0.75)
     assert e.value.code == b.APB_ERR_SHAPE
+    layer.free()
+    Wt, delta, _, _ = synth.random_case(4, 8, 9 * 32, 1, 2)
+    layer = b.apb_compress(torch.from_numpy(Wt).cuda(), float(delta))
+    fmap = b.alloc_packed(32, 16, 2)
+    Y = torch.empty((8, 16), device="cuda")
+    lib = b.load()
+    for stride in (0, 3, -1):                                           # only strides 1 and 2
+        rc = lib.apb_forward_conv3x3(layer.handle, fmap.data_ptr(), 1, 4, 4, stride, 2, 0.75, Y.data_ptr(), None)
+        assert rc == b.APB_ERR_SHAPE
     layer.free()
 
 
@@ -145,6 +164,42 @@ def test_full_size_conv_layers_equal_the_explicit_route(b, name, B, H, W):
     cm = np.full((C, B, H + 2, W + 2), pad, dtype=np.int8)
     cm[:, :, 1:H + 1, 1:W + 1] = c_map.reshape(C, B, H, W)
     bb, yy, xx = pix // (H * W), (pix // W) % H, pix % W
+    patches = np.concatenate([cm[:, bb, yy + ky, xx + kx] for ky in range(3) for kx in range(3)], axis=0)
+    F = capi.forward(L, o.pack_acts(patches, bits), patches, bits, step, threads=THREADS)
+    got = Y[:, torch.from_numpy(pix).cuda()].cpu().numpy().astype(np.float64)
+    ref = F["Y"].astype(np.float64)
+    assert np.all(np.abs(got - ref) <= REL_TOL * np.abs(ref))
+    layer.free()
+
+
+@pytest.mark.parametrize("N,C,B,H,W,bits", [(128, 64, 64, 56, 56, 2), (256, 128, 64, 28, 28, 2), (512, 256, 128, 14, 14, 1),
+                                            (96, 96, 32, 35, 35, 2)])
+def test_full_size_stride_2_layers_equal_the_explicit_route(b, N, C, B, H, W, bits):
+    """The first convolution of a ResNet stage (stride 2, channels doubled) at the size of the benchmark layers,
+    and one with an odd multiple of 32 channels and odd image sizes: the implicit route against apb_quantize_acts
+    on the explicit strided float im2col matrix + apb_forward (bit for bit, float and packed outputs), and sampled
+    output pixels against the oracle (image corners and edges included)."""
+    print(f"[case] stride-2 conv N={N} C={C} B={B} H={H} W={W} bits={bits}", flush=True)
+    Wt, delta, Xmap, step = make_case(N + C + H, N, C, B, H, W, bits)
+    Ho, Wo = o.conv_out_size(H, 2), o.conv_out_size(W, 2)
+    P = B * Ho * Wo
+    Xd = torch.from_numpy(Xmap).cuda()
+    layer = b.apb_compress(torch.from_numpy(Wt).cuda(), float(delta))
+    fmap = b.apb_quantize_acts(Xd, bits, float(step))
+    Y = b.apb_forward_conv3x3(layer, fmap, B, H, W, bits, float(step), stride=2)
+    explicit = torch_im2col(Xd, C, B, H, W, 0.0 if bits == 2 else -1.0, stride=2)
+    packed = b.apb_quantize_acts(explicit, bits, float(step))
+    del explicit
+    assert torch.equal(Y, b.apb_forward(layer, packed, P, bits, float(step)))
+    out = b.apb_forward_conv3x3_requant(layer, fmap, B, H, W, bits, float(step), 2, 1.0, stride=2)
+    assert torch.equal(out, b.apb_forward_requant(layer, packed, P, bits, float(step), 2, 1.0))
+    L = o.compress(Wt, delta, alpha=np.float32(layer.info()["alpha"]))
+    pix = np.unique(np.concatenate([[0, Wo - 1, (Ho - 1) * Wo, Ho * Wo - 1, P - 1, P - Wo],
+                                    np.random.default_rng(7).choice(P, 40, replace=False)]))
+    c_map = o.quantize(Xmap, bits, step)
+    cm = np.full((C, B, H + 2, W + 2), 0 if bits == 2 else -1, dtype=np.int8)
+    cm[:, :, 1:H + 1, 1:W + 1] = c_map.reshape(C, B, H, W)
+    bb, yy, xx = pix // (Ho * Wo), 2 * ((pix // Wo) % Ho), 2 * (pix % Wo)
     patches = np.concatenate([cm[:, bb, yy + ky, xx + kx] for ky in range(3) for kx in range(3)], axis=0)
     F = capi.forward(L, o.pack_acts(patches, bits), patches, bits, step, threads=THREADS)
     got = Y[:, torch.from_numpy(pix).cuda()].cpu().numpy().astype(np.float64)
