@@ -486,7 +486,7 @@ def cpu_baseline_chain(cfg, W, delta, X, step, bits_out, step_out):
             "sample": f"first {m} of {cfg.M} columns of {cfg.name}, {passes} passes (forward+requantize+pack), {dt:.2f} s"}
 
 
-def run_square_sweep(sizes=(512, 1024, 2048, 4096, 8192), iters=30):
+def run_square_sweep(sizes=(512, 1024, 2048, 4096, 8192)):
     """The paper's efficiency protocol (square matrices, the product alone, operands already packed) for
     its three bitwise routines: 1/1 and 1/2 are a binary layer without residuals (integer part D through
     apb_forward_int), 2/2 is apb_gemm_2_2_int.  Seeded normal weights, ReLU-normal activations."""
@@ -503,17 +503,7 @@ def run_square_sweep(sizes=(512, 1024, 2048, 4096, 8192), iters=30):
         p2 = b.apb_quantize_acts(X, 2, 0.75)
         D = torch.empty((n, n), dtype=torch.int32, device="cuda")
 
-        def timed(fn):
-            for _ in range(3):
-                fn()
-            a, c = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            torch.cuda.synchronize()
-            a.record()
-            for _ in range(iters):
-                fn()
-            c.record()
-            c.synchronize()
-            return a.elapsed_time(c) / iters
+        timed = graph_ms                       # (launches back to back in a replayed graph: no host gaps at small n)
 
         t11 = timed(lambda: b.apb_forward_int(layer, p1, n, 1, D=D))
         t12 = timed(lambda: b.apb_forward_int(layer, p2, n, 2, D=D))
