@@ -431,11 +431,9 @@ int apb_quantize_forward(const apb_layer* layer, const float* X, int M, int bits
     if (!std::isfinite(step) || !(step > 0.0f)) return APB_ERR_VALUE;
     hipStream_t s = as_stream(stream);
     if (forward_float_applies(d, M, bits)) return launch_forward_float(d, X, M, bits, step, Y, s);
-    const int rc = apb_quantize_acts(X, d.K, M, bits, step, packed, stream);
-    return rc != APB_OK ? rc : launch_forward_best(d, static_cast<const uint32_t*>(packed),
-                                                   reinterpret_cast<const int32_t*>(static_cast<const uint32_t*>(packed) +
-                                                       (size_t)bits * d.Kw * ((size_t)kWave * (((size_t)M + kWave - 1) / kWave))),
-                                                   M, bits, step, Y, s);
+    uint32_t* planes = static_cast<uint32_t*>(packed);
+    int32_t* colsum = reinterpret_cast<int32_t*>(planes + (size_t)bits * d.Kw * ((size_t)kWave * (((size_t)M + kWave - 1) / kWave)));
+    return launch_quantize_then_forward(d, X, M, bits, step, planes, colsum, Y, s);
 }
 
 // Shape checks shared by the two convolution entry points; fills `conv` and the output pixel count.

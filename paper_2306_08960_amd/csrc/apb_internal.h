@@ -101,7 +101,7 @@ int launch_slot_major_signs(const uint32_t* sign, const int32_t* perm, int Np, i
 int launch_slot_tables(const int32_t* perm, const int32_t* row_ptr, const int32_t* col_idx, const float* val, int Np,
                        int nchunks, int32_t* chunk_ptr, double* slot_valsum, hipStream_t s);
 
-// activations
+// activations.  colsum == nullptr: the planes only (for a consumer that adds the code sums up from the words itself)
 int launch_quantize(const float* X, int K, int M, int bits, float inv_step, uint32_t* planes, int32_t* colsum,
                     hipStream_t s);
 int launch_zero_words(uint32_t* p, size_t count, hipStream_t s);
@@ -139,8 +139,13 @@ bool mfma_sum_exact(int K, int max_weight, int max_code);
 // the rows-in-lanes forward kernel (apb_rows.hip): same Y as launch_forward for a plain K x M matrix;
 // forward_rows_applies says whether the layer has row lists and the launch is worth it
 bool forward_rows_applies(const LayerDev& L, int M, int bits);
+// colsum == nullptr: the kernel adds the code sums of its columns up from the packed words
 int launch_forward_rows(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                         float* Y, hipStream_t s);
+// launch_quantize + launch_forward_best through the scratch buffer planes / colsum (the step of layers that do
+// not run as one kernel); what `colsum` holds afterwards is unspecified
+int launch_quantize_then_forward(const LayerDev& L, const float* X, int M, int bits, float step, uint32_t* planes,
+                                 int32_t* colsum, float* Y, hipStream_t s);
 // apb_forward's choice between the two forward kernels for a plain K x M matrix and a float output
 int launch_forward_best(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                         float* Y, hipStream_t s);

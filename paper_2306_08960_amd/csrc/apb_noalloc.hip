@@ -50,11 +50,10 @@ extern "C" int apb_quantize_forward_static(const apb_layer* layer, const float* 
     void* base = nullptr;
     int rc = scratch_of_current_device(&base);
     if (rc != APB_OK) return rc;
-    // The quantize kernel overwrites every plane word and every column sum of this K x M (it clears the
-    // sums first, with a fill kernel, where it adds to them), so nothing of an earlier call is read.
+    // The quantize kernel overwrites every plane word of this K x M, and every column sum the forward kernel
+    // reads (it clears the sums first, with a fill kernel, where it adds to them), so nothing of an earlier
+    // call is read.
     uint32_t* planes = static_cast<uint32_t*>(base);
     int32_t* colsum = reinterpret_cast<int32_t*>(planes + (size_t)bits * d.Kw * Mp);
-    rc = launch_quantize(X, d.K, M, bits, 1.0f / step, planes, colsum, s);
-    if (rc != APB_OK) return rc;
-    return launch_forward_best(d, planes, colsum, M, bits, step, Y, s);
+    return launch_quantize_then_forward(d, X, M, bits, step, planes, colsum, Y, s);
 }

@@ -19,6 +19,10 @@ namespace apb {
 namespace {
 
 constexpr int kMaxWaves = 16;
+#ifndef APB_NOSUM_GROUPS
+#define APB_NOSUM_GROUPS 192
+#endif
+constexpr int kNoSumGroups = APB_NOSUM_GROUPS;
 
 __global__ __launch_bounds__(256) void k_zero_words(uint32_t* __restrict__ p, size_t count) {
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (size_t)gridDim.x * 256) p[i] = 0u;
@@ -114,6 +118,7 @@ __global__ __launch_bounds__(kWave* kMaxWaves) void k_quantize_pack(const float*
             if (BITS == 2) *reinterpret_cast<UV*>(planes + ((size_t)Kw + j) * Mp + m0) = o1;
         }
     }
+    if (colsum == nullptr) return;                                  // the caller takes the code sums from the words
 #pragma unroll
     for (int q = 0; q < CPL; ++q) s_sum[wave * kStrip + lane * CPL + q] = sum[q];
     __syncthreads();
@@ -161,9 +166,11 @@ int launch_quantize(const float* X, int K, int M, int bits, float inv_step, uint
     const int strips = (Mp + strip - 1) / strip;
     // Few strips: split K into slabs as well, until three quarters of the 256 compute units have a workgroup
     // (and there are 1024 waves) or a slab is down to 4 words.  (Measured: 128 strips -> 2 slabs gains a fifth;
-    // splitting 196 strips further loses to the extra fill launch and the atomics.)
+    // splitting 196 strips further loses to the extra fill launch and the atomics.)  Without column sums
+    // (colsum == nullptr) a split costs neither: then until every compute unit has kNoSumGroups workgroups.
+    const long long min_groups = colsum ? 192 : kNoSumGroups;
     int slabs = 1;
-    while (((long long)strips * slabs < 192 || (long long)strips * kMaxWaves * slabs < 1024) &&
+    while (((long long)strips * slabs < min_groups || (long long)strips * kMaxWaves * slabs < 1024) &&
            (Kw + 2 * slabs - 1) / (2 * slabs) >= 4)
         slabs *= 2;
     const int words_per_slab = (Kw + slabs - 1) / slabs;
@@ -181,7 +188,7 @@ int launch_quantize(const float* X, int K, int M, int bits, float inv_step, uint
             waves = w;
         }
     }
-    if (slabs > 1) {
+    if (slabs > 1 && colsum) {
         const int rc = launch_zero_words(reinterpret_cast<uint32_t*>(colsum), (size_t)Mp, s);
         if (rc != APB_OK) return rc;
     }

@@ -67,6 +67,7 @@ struct RowsParams {
     int nblocks;                                                 // row blocks of 64 slots
     int row_groups;                                              // ceil(nblocks / waves per workgroup)
     int tasks;                                                   // row_groups * column groups
+    int lds_main_bytes;                                          // LDS up to the waves' partial column sums
 };
 
 __device__ __forceinline__ uint32_t spread4(uint32_t nib) { return (nib * 0x00204081u) & 0x01010101u; }
@@ -123,17 +124,30 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 4))) voi
     // together, into LDS (16 bytes per step and lane -- as many bytes as the code table that later takes the
     // same place) and the waves read it back with one 16-byte LDS read per step.
     const int steps = p.Kw4 / 4;
+    // Without a colsum array the code sums of the 16 columns are added up here, from the same words: a thread
+    // stages words of one column only (lane & 15: the workgroup size is a multiple of 64), the four lanes of a
+    // wave that share a column add theirs up, and the waves' partial sums wait in LDS behind the table.
+    int32_t* cs_part = reinterpret_cast<int32_t*>(lds + p.lds_main_bytes);        // [waves][16]
     {
         const size_t plane_stride = (size_t)p.Kw * p.Mp;
         v4u* stage = reinterpret_cast<v4u*>(lds);
+        int my_cs = 0;
         for (int it = threadIdx.x; it < steps * kWave; it += blockDim.x) {
             const int l = it & (kWave - 1), s = it >> 6;
             // word rows past Kw: the sign words there are zero padding; the activation load re-reads the last
             // row and is multiplied by those zeros
-            const uint32_t* brow = planes + (size_t)min(4 * s + (l >> 4), p.Kw - 1) * p.Mp + m0 + (l & 15);
+            const int row = 4 * s + (l >> 4);
+            const uint32_t* brow = planes + (size_t)min(row, p.Kw - 1) * p.Mp + m0 + (l & 15);
+            const uint32_t w0 = brow[0], w1 = BITS == 2 ? brow[plane_stride] : 0u;
+            if (row < p.Kw) my_cs += __builtin_popcount(w0) + 2 * __builtin_popcount(w1);
             v8i fb;
-            expand_words<BITS>(brow[0], BITS == 2 ? brow[plane_stride] : 0u, fb);
+            expand_words<BITS>(w0, w1, fb);
             stage[it] = v4u{(uint32_t)fb[0], (uint32_t)fb[1], (uint32_t)fb[2], (uint32_t)fb[3]};
+        }
+        if (colsum == nullptr) {
+            my_cs += __shfl_xor(my_cs, 16);
+            my_cs += __shfl_xor(my_cs, 32);
+            if (lane < T) cs_part[wave * T + lane] = my_cs;
         }
     }
     __syncthreads();
@@ -200,7 +214,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 4))) voi
 #pragma unroll
         for (int cc = 0; cc < T; ++cc) {
             const int P = tile[lane * T + cc];
-            const int cs = colsum[m0 + cc];                      // m0 + 15 < Mp: Mp is a multiple of 64
+            int cs = 0;
+            if (colsum) {
+                cs = colsum[m0 + cc];                            // m0 + 15 < Mp: Mp is a multiple of 64
+            } else {
+                for (int w = 0; w < waves; ++w) cs += cs_part[w * T + cc];
+            }
             const int d = BITS == 1 ? 4 * P - rs - 2 * cs : 2 * P - cs;
             acc[cc] = a0 * (double)d * col_scale(cc);  // in the scaled domain of column cc's products
         }
@@ -327,18 +346,23 @@ int rows_waves(const LayerDev& L) {
     return nb >= 4 ? 4 : (nb >= 2 ? 2 : 1);
 }
 
+constexpr size_t kColsumBytes = 8 * T * sizeof(int32_t);      // partial column sums of up to 8 waves
+// the largest table, the staged operands of a K rounded up to whole steps, the partial sums
+constexpr int kMaxLdsBytes = kRowsMaxTableBytes + 1024 + (int)kColsumBytes;
+static_assert(kMaxLdsBytes <= 160 * 1024, "LDS of one compute unit");
+
 size_t rows_lds_bytes(const LayerDev& L, int waves) {
     // the code table; before it, in the same place, the staged activation operands (16 bytes per step and lane)
     // and the tiles of the binary product
     const size_t table = (size_t)32 * L.Kw * kRowBytes, stage = (size_t)(L.rows_Kw4 / 4) * kWave * 16;
     const size_t tiles = (size_t)waves * kWave * T * 4;
-    return std::max(table, std::max(stage, tiles));
+    return (std::max(table, std::max(stage, tiles)) + 15) & ~(size_t)15;
 }
 
 template <int BITS>
 int launch_rows(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, float* Y, const RowsParams& p,
                 int waves, hipStream_t s) {
-    const size_t lds = rows_lds_bytes(L, waves);
+    const size_t lds = rows_lds_bytes(L, waves) + kColsumBytes;
     if (lds > 64 * 1024) {                                      // more LDS than a launch gets without asking
         static std::atomic<size_t> asked[kMaxDevices];          // largest size asked for, per device
         int dev = 0;
@@ -346,8 +370,8 @@ int launch_rows(const LayerDev& L, const uint32_t* planes, const int32_t* colsum
         if (dev < 0 || dev >= kMaxDevices) return APB_ERR_SHAPE;
         if (asked[dev].load(std::memory_order_acquire) < lds) {
             APB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_forward_rows<BITS>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, kRowsMaxTableBytes));
-            asked[dev].store((size_t)kRowsMaxTableBytes, std::memory_order_release);
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
+            asked[dev].store((size_t)kMaxLdsBytes, std::memory_order_release);
         }
     }
     hipLaunchKernelGGL((k_forward_rows<BITS>), dim3((unsigned)p.tasks), dim3(kWave * waves), lds, s, planes, colsum,
@@ -386,6 +410,7 @@ int launch_forward_rows(const LayerDev& L, const uint32_t* planes, const int32_t
     const long long tasks = (long long)p.row_groups * ((M + T - 1) / T);
     if (tasks > 0x7fffffffLL || (long long)Mp * 8 >= (1LL << 31)) return APB_ERR_SHAPE;
     p.tasks = (int)tasks;
+    p.lds_main_bytes = (int)rows_lds_bytes(L, waves);
     return bits == 1 ? launch_rows<1>(L, planes, colsum, Y, p, waves, s) : launch_rows<2>(L, planes, colsum, Y, p, waves, s);
 }
 
@@ -394,6 +419,18 @@ int launch_forward_best(const LayerDev& L, const uint32_t* planes, const int32_t
     // (the rows-in-lanes kernel reads the packed words 16 bytes at a time)
     if (forward_rows_applies(L, M, bits) && (reinterpret_cast<uintptr_t>(planes) & 15u) == 0)
         return launch_forward_rows(L, planes, colsum, M, bits, step, Y, s);
+    return launch_forward(L, planes, colsum, M, bits, step, nullptr, Y, s);
+}
+
+int launch_quantize_then_forward(const LayerDev& L, const float* X, int M, int bits, float step, uint32_t* planes,
+                                 int32_t* colsum, float* Y, hipStream_t s) {
+    // The rows-in-lanes kernel reads every word of its columns anyway and adds their code sums up itself: the
+    // quantize kernel then writes the planes only -- no sums in LDS, and where it splits K no fill launch and
+    // no atomics.
+    const bool rows = forward_rows_applies(L, M, bits) && (reinterpret_cast<uintptr_t>(planes) & 15u) == 0;
+    const int rc = launch_quantize(X, L.K, M, bits, 1.0f / step, planes, rows ? nullptr : colsum, s);
+    if (rc != APB_OK) return rc;
+    if (rows) return launch_forward_rows(L, planes, nullptr, M, bits, step, Y, s);
     return launch_forward(L, planes, colsum, M, bits, step, nullptr, Y, s);
 }
 
