@@ -170,6 +170,169 @@ __global__ __launch_bounds__(256) void k_binary_mfma(const MfmaParams p) {
     }
 }
 
+
+// The same product with the activation operand SHARED by the four waves of a workgroup through LDS.
+// The waves are stacked along n (wave w: rows [32*RN*w, 32*RN*(w+1)) of the workgroup's 128*RN rows) and
+// all multiply by the same 128 columns.  Wave w fetches and expands the activation words of columns
+// [32*w, 32*w + 32) only and leaves the operand (16 bytes per lane) in LDS; after a barrier every wave
+// reads the four operands back.  Against k_binary_mfma with the same wave tile that is a quarter of the
+// activation words through L2 and a quarter of their expansion work per wave (the weight operands stay in
+// registers: nothing to share along n).  Three LDS buffers rotate, one barrier per K step (see the pipeline
+// in the kernel).
+// No wave leaves early (the barriers, and its share of the activation operand): rows and columns outside
+// the matrices are clamped for the loads and skipped by the stores.
+template <int WBITS, int BITS, int RN, int EPI>
+__global__ __launch_bounds__(256) void k_binary_mfma_shared(const MfmaParams p) {
+    constexpr int RM = 4;
+    typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+    __shared__ v4u bstage[3][RM][64];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int i = lane & 31, g = lane >> 5;
+    const int tile_m = blockIdx.x % p.tiles_m;
+    const int tile_n = blockIdx.x / p.tiles_m;
+    const int slot_base = (tile_n * 4 + wave) * (32 * RN);
+    const int m_base = tile_m * (32 * RM);
+
+    unsigned aoff[RN];
+#pragma unroll
+    for (int t = 0; t < RN; ++t) aoff[t] = (unsigned)(g * p.Np + min(slot_base + 32 * t + i, p.Np - 1));
+    const unsigned boff = (unsigned)(g * p.Mp + min(m_base + 32 * wave + i, p.Mp - 1));   // this wave's share
+    const size_t plane_stride = (size_t)p.Kw * p.Mp;
+    const int steps = (p.Kw + 1) / 2;
+
+    v16f acc[RN][RM];
+#pragma unroll
+    for (int t = 0; t < RN; ++t)
+#pragma unroll
+        for (int u = 0; u < RM; ++u)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][u][r] = 0.0f;
+
+    auto load_words = [&](int s, uint32_t (&a)[WBITS][RN], uint32_t (&b)[BITS][1]) {
+        const int ss = min(s, steps - 1);                     // past the end: harmless re-read, never used
+#pragma unroll
+        for (int pl = 0; pl < WBITS; ++pl) {
+            const uint32_t* arow = p.signT + pl * p.wplane_stride + (size_t)(2 * ss) * p.Np;
+#pragma unroll
+            for (int t = 0; t < RN; ++t) a[pl][t] = arow[aoff[t]];
+        }
+#pragma unroll
+        for (int pl = 0; pl < BITS; ++pl) b[pl][0] = (p.planes + pl * plane_stride + (size_t)(2 * ss) * p.Mp)[boff];
+    };
+
+    // Pipeline over the K steps (s % kRing, s % 3 and s % 2 are compile-time constants inside the unrolled loop):
+    //   words:    fetched kRing steps ahead into a ring of register sets;
+    //   step s:   reads the shared operands of step s+1 from LDS buffer (s+1) % 3 (written during step s-1, visible
+    //             since the barrier that ended it), expands its weight words of step s+1 into the other register set
+    //             and its share of the activation words of step s+2 into buffer (s+2) % 3 (last read during step
+    //             s-2, whose data every wave has waited for before the barrier of step s-1), and runs the matrix
+    //             instructions of step s on operands it read one step earlier -- no LDS latency in front of them.
+    constexpr int kRing = 6;                                  // (12 measured the same)
+    static_assert(kRing % 6 == 0, "s % 3 and s % 2 from s % kRing");
+    uint32_t aw[kRing][WBITS][RN], bw[kRing][BITS][1];
+    v8i fa[2][RN], fb[2][RM];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+        for (int t = 0; t < RN; ++t)
+#pragma unroll
+            for (int d = 4; d < 8; ++d) fa[h][t][d] = 0;
+#pragma unroll
+        for (int u = 0; u < RM; ++u)
+#pragma unroll
+            for (int d = 4; d < 8; ++d) fb[h][u][d] = 0;
+    }
+    auto expand_a = [&](const uint32_t (&a)[WBITS][RN], int set) {
+#pragma unroll
+        for (int t = 0; t < RN; ++t) expand_words<WBITS>(a[0][t], a[WBITS - 1][t], fa[set][t]);
+    };
+    auto expand_b = [&](const uint32_t (&b)[BITS][1], int buf) {
+        v8i f;
+        expand_words<BITS>(b[0][0], b[BITS - 1][0], f);
+        bstage[buf][wave][lane] = v4u{(uint32_t)f[0], (uint32_t)f[1], (uint32_t)f[2], (uint32_t)f[3]};
+    };
+    auto read_b = [&](int buf, int set) {
+#pragma unroll
+        for (int u = 0; u < RM; ++u) {
+            const v4u b = bstage[buf][u][lane];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) fb[set][u][d] = (int)b[d];
+        }
+    };
+#pragma unroll
+    for (int q = 0; q < kRing; ++q) load_words(q, aw[q], bw[q]);
+    expand_a(aw[0], 0);
+    expand_b(bw[0], 0);
+    expand_b(bw[1], 1);
+    __syncthreads();
+    read_b(0, 0);
+
+    constexpr int kValuPerMfma = ((WBITS == 2 ? 15 : 7) * RN + (BITS == 2 ? 15 : 7) + RN * RM - 1) / (RN * RM);
+    auto one_step = [&](int s, int q) {
+        read_b((q + 1) % 3, (q + 1) & 1);                                         // operands of step s+1
+        // (the words of steps s+1 and s+2 are taken out of the ring before slot q is refilled below; past the
+        //  last step they are clamped re-reads, expanded and never used)
+        expand_a(aw[(q + 1) % kRing], (q + 1) & 1);
+        expand_b(bw[(q + 2) % kRing], (q + 2) % 3);
+        load_words(s + kRing, aw[q], bw[q]);
+#pragma unroll
+        for (int t = 0; t < RN; ++t)
+#pragma unroll
+            for (int u = 0; u < RM; ++u) acc[t][u] = mfma_fp4(fa[q & 1][t], fb[q & 1][u], acc[t][u]);
+        // Ask the scheduler to alternate: one matrix instruction, then a slice of the expansion work, which
+        // issues in its shadow.  (Pinning the whole step -- LDS reads first, nothing across the barrier --
+        // measured 5 % slower than what the scheduler makes of it.)
+#pragma unroll
+        for (int e = 0; e < RN * RM; ++e) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                     // 1 MFMA
+            __builtin_amdgcn_sched_group_barrier(0x002, kValuPerMfma, 0);          // VALU
+        }
+        __syncthreads();
+    };
+    int s0 = 0;
+    for (; s0 + kRing <= steps; s0 += kRing) {
+#pragma unroll
+        for (int q = 0; q < kRing; ++q) one_step(s0 + q, q);
+    }
+#pragma unroll
+    for (int q = 0; q < kRing - 1; ++q)
+        if (s0 + q < steps) one_step(s0 + q, q);              // (steps is the same for every wave: so are the barriers)
+
+    if (slot_base >= p.Np) return;
+    const size_t out0 = (size_t)(slot_base + 4 * g) * p.M + m_base + i;
+    int cs[RM];
+#pragma unroll
+    for (int u = 0; u < RM; ++u) cs[u] = p.colsum[min(m_base + 32 * u + i, p.Mp - 1)];
+#pragma unroll
+    for (int t = 0; t < RN; ++t) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = 32 * t + 8 * (r / 4) + (r % 4);          // + slot_base + 4*g
+            if (slot_base + 4 * g + row >= p.Np) continue;
+#pragma unroll
+            for (int u = 0; u < RM; ++u) {
+                if (m_base + 32 * u + i >= p.M) continue;
+                const size_t at = out0 + (size_t)row * p.M + 32 * u;
+                const int P = (int)(acc[t][u][r] * 4.0f);
+                if (EPI == kIntD)
+                    static_cast<int32_t*>(p.out)[at] =
+                        BITS == 2 ? 2 * P - cs[u] : 4 * P - p.rowsum[slot_base + 4 * g + row] - 2 * cs[u];
+                else if (EPI == kInt22) static_cast<int32_t*>(p.out)[at] = 2 * P - 3 * cs[u];
+                else static_cast<float*>(p.out)[at] = (float)(p.scale * (double)(2 * P - 3 * cs[u]));
+            }
+        }
+    }
+}
+
+template <int WBITS, int BITS, int RN, int EPI>
+void launch_shared(MfmaParams p, hipStream_t s) {
+    p.waves_m = 1;
+    p.tiles_m = (p.Mp + 127) / 128;
+    const int tiles_n = (p.Np + 128 * RN - 1) / (128 * RN);
+    hipLaunchKernelGGL((k_binary_mfma_shared<WBITS, BITS, RN, EPI>), dim3((unsigned)(p.tiles_m * tiles_n)), dim3(256), 0, s, p);
+}
+
 template <int WBITS, int BITS, int RN, int RM, int EPI>
 void launch_shape(MfmaParams p, int waves_m, hipStream_t s) {
     const int waves_n = 4 / waves_m;
@@ -188,6 +351,15 @@ void launch_shape(MfmaParams p, int waves_m, hipStream_t s) {
 template <int WBITS, int BITS, int EPI>
 int launch_best_tile(MfmaParams p, int N, hipStream_t s) {
     if ((long long)2 * N >= (1LL << 30) || (long long)2 * p.Mp >= (1LL << 30)) return APB_ERR_SHAPE;
+    // Enough workgroups of 128 rows x 128 columns for one and a half per compute unit: the kernel that shares the
+    // activation operand through LDS (measured ahead of the one below from there on: 2/2 on 512 x 4608 x 12544
+    // 36 -> 30 us, squares of 4096 and 8192 a quarter faster; behind it on shapes with fewer workgroups, where
+    // the small wave tiles of the menu put more waves on the chip).
+    if (N >= 128 && (long long)((N + 127) / 128) * ((p.Mp + 127) / 128) >= 384) {
+        launch_shared<WBITS, BITS, 1, EPI>(p, s);
+        APB_HIP(hipGetLastError());
+        return APB_OK;
+    }
     static const int menu[5][2] = {{1, 1}, {2, 1}, {2, 2}, {2, 4}, {4, 2}};    // smallest first
     constexpr double kL2Budget = 200e6;
     const double steps = (p.Kw + 1) / 2;

@@ -55,6 +55,29 @@ def test_edge_shapes(b, N, K, M):
     check_2_2(b, W, np.float32(0.04), X, step, tag="edge")
 
 
+# Shapes with 384 or more tiles of 128 x 128: the kernel whose waves share the activation operand through LDS --
+# ragged N, K (one step, an odd number of words, a tail past the pipeline's ring of six) and M
+SHARED_SHAPES = [(130, 200, 24593), (300, 33, 16500), (128, 64, 49100), (257, 1000, 16400), (513, 832, 9900)]
+
+
+@pytest.mark.parametrize("N,K,M", SHARED_SHAPES)
+def test_shapes_on_the_shared_operand_kernel(b, N, K, M):
+    assert ((N + 127) // 128) * ((M + 63) // 64 * 64 + 127) // 128 >= 384
+    W, _, X, step = synth.random_case(4100 + N + K + M, N, K, M, 2, rho=0.05)
+    check_2_2(b, W, np.float32(0.04), X, step, tag="shared operand")
+    # the same kernel computes the integer part D of a binary layer (1- and 2-bit activations)
+    for bits in (1, 2):
+        Wb, delta, Xb, stepb = synth.random_case(4200 + N + K + M + bits, N, K, M, bits, rho=0.02)
+        c = o.quantize(Xb, bits, stepb)
+        rows = np.unique(np.concatenate([[0, N - 1], np.random.default_rng(N).choice(N, 24, replace=False)]))
+        want = o.int_part_unpacked(o.sign_bits(Wb)[rows], c)
+        layer = b.apb_compress(torch.from_numpy(Wb).cuda(), float(delta))
+        packed = b.apb_quantize_acts(torch.from_numpy(Xb).cuda(), bits, float(stepb))
+        D = b.apb_forward_int(layer, packed, M, bits).cpu().numpy()
+        assert np.array_equal(D[rows], want)
+        layer.free()
+
+
 def test_special_values_and_degenerate_steps(b):
     W = np.zeros((4, 70), dtype=np.float32)
     W[0] = [0.0, -0.0, 0.49, 0.5, 0.99, 1.0, 7.0, -1e-30, -0.5, -0.51, -1.0, -1.01, -9.0, np.inf] * 5
