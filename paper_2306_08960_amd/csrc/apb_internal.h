@@ -142,6 +142,11 @@ bool forward_rows_applies(const LayerDev& L, int M, int bits);
 // colsum == nullptr: the kernel adds the code sums of its columns up from the packed words
 int launch_forward_rows(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                         float* Y, hipStream_t s);
+// the rows-in-lanes kernel ending in the next layer's quantizer (what launch_forward_requant does on a plain matrix)
+bool forward_rows_requant_applies(const LayerDev& L, const uint32_t* planes, int M, int bits);
+int launch_forward_rows_requant(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
+                                float step, const float* scale, const float* shift, int bits_out, float inv_step_out,
+                                uint32_t* packed_out, hipStream_t s);
 // launch_quantize + launch_forward_best through the scratch buffer planes / colsum (the step of layers that do
 // not run as one kernel); what `colsum` holds afterwards is unspecified
 int launch_quantize_then_forward(const LayerDev& L, const float* X, int M, int bits, float step, uint32_t* planes,

@@ -68,6 +68,9 @@ struct RowsParams {
     int row_groups;                                              // ceil(nblocks / waves per workgroup)
     int tasks;                                                   // row_groups * column groups
     int lds_main_bytes;                                          // LDS up to the waves' partial column sums
+    // REQ kernels: the output is the packed activation buffer of the next layer (its K = this layer's N)
+    int out_bits, out_Kw;                                        // 1 or 2; ceil(N / 32)
+    float out_inv_step;
 };
 
 __device__ __forceinline__ uint32_t spread4(uint32_t nib) { return (nib * 0x00204081u) & 0x01010101u; }
@@ -96,12 +99,14 @@ __device__ __forceinline__ void accumulate16(double (&acc)[T], v2i& m, const v2u
     }
 }
 
-template <int BITS>
+// REQ: instead of Y the kernel writes the packed codes of the next layer's quantizer applied to
+// scale[n] * Y + shift[n] (see the epilogue); Y then points to that buffer, zero-filled before the launch.
+template <int BITS, bool REQ>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 4))) void k_forward_rows(
     const uint32_t* __restrict__ planes, const int32_t* __restrict__ colsum, const int32_t* __restrict__ rowsum,
     const int32_t* __restrict__ rperm, const int32_t* __restrict__ blk, const uint32_t* __restrict__ ek,
     const double* __restrict__ ev, const uint32_t* __restrict__ signR, const double* __restrict__ valsumR,
-    float* __restrict__ Y, const RowsParams p) {
+    const float* __restrict__ scale, const float* __restrict__ shift, float* __restrict__ Y, const RowsParams p) {
     extern __shared__ __align__(16) uint8_t lds[];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -266,11 +271,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 4))) voi
         }
     }
     __syncthreads();
-    if (!active) return;
+    if (!REQ && !active) return;                                 // (REQ: every wave meets again in the epilogue)
 
     // ---- residual part: steps e0 .. e1 of this block; entries fetched kAhead steps ahead, the table row of
     // the next step read while the multiply-adds of this one issue.
-    {
+    if (active) {
         const int e0 = blk[b], e1 = blk[b + 1];
         const int n_steps = e1 - e0;
         // Entry loads are buffer loads: descriptor = this block's part of the lists, the step in the scalar
@@ -319,7 +324,56 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 4))) voi
         }
     }
 
-    // ---- epilogue: 16 consecutive floats of row n.
+    // ---- epilogue.  REQ: z = scale[n] * y + shift[n] (float64, rounded once to float; z = y without scale) is
+    // quantized exactly as apb_quantize_acts does and its code bits go into word n / 32 of column m of the next
+    // layer's buffer (planes [out_bits][out_Kw][Mp], then the column sums [Mp]).  The rows of a workgroup are
+    // scattered over all of N (the lists are sorted by length), so its bits first meet in LDS -- where the table
+    // was: [out_bits][out_Kw][16] words and 16 partial column sums -- and then leave as one atomic OR per
+    // non-zero word and one atomic add per column; integer OR and add commute, so the order between
+    // workgroups does not matter.
+    if (REQ) {
+        uint32_t* merged = reinterpret_cast<uint32_t*>(lds);
+        const int nwords = p.out_bits * p.out_Kw * T;
+        __syncthreads();                                         // every wave is done with the table
+        for (int i = threadIdx.x; i < nwords + T; i += blockDim.x) merged[i] = 0u;
+        __syncthreads();
+        const int n = active ? rperm[slot] : -1;
+        const double vs = BITS == 1 && n >= 0 ? valsumR[slot] : 0.0;
+        const double sc = scale && n >= 0 ? (double)scale[n] : 1.0, sh = scale && n >= 0 ? (double)shift[n] : 0.0;
+        const uint32_t bit = 1u << (n & 31);
+        uint32_t* w0_at = merged + (size_t)(max(n, 0) >> 5) * T;
+        uint32_t* w1_at = w0_at + (size_t)p.out_Kw * T;
+#pragma unroll
+        for (int cc = 0; cc < T; ++cc) {
+            const double sum = acc[cc] * col_unscale(cc);
+            double z = (BITS == 1 ? 2.0 * sum - vs : sum) * p.step;
+            if (scale) z = fma(sc, z, sh);
+            const float zf = (float)z;
+            uint32_t code = p.out_bits == 1 ? (zf >= 0.0f ? 1u : 0u) : code2(zf, p.out_inv_step);
+            if (n < 0 || m0 + cc >= p.M) code = 0;
+            if (code & 1u) __hip_atomic_fetch_or(w0_at + cc, bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (code >> 1) __hip_atomic_fetch_or(w1_at + cc, bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            // the wave's share of the column sum: two ballots instead of 64 additions to one address
+            const int tot = __builtin_popcountll(__ballot((code & 1u) != 0)) + 2 * __builtin_popcountll(__ballot((code >> 1) != 0));
+            if (lane == 0 && tot)
+                __hip_atomic_fetch_add(merged + nwords + cc, (uint32_t)tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+        __syncthreads();
+        uint32_t* words = reinterpret_cast<uint32_t*>(Y);
+        for (int i = threadIdx.x; i < nwords; i += blockDim.x) {
+            const uint32_t w = merged[i];
+            // merged row i / 16 = word row of the packed output (planes one after the other), column i % 16
+            if (w) __hip_atomic_fetch_or(words + (size_t)(i / T) * p.Mp + m0 + (i % T), w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (threadIdx.x < T) {
+            const uint32_t tot = merged[nwords + threadIdx.x];
+            if (tot)
+                __hip_atomic_fetch_add(words + (size_t)p.out_bits * p.out_Kw * p.Mp + m0 + threadIdx.x, tot, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+        }
+        return;
+    }
+    // 16 consecutive floats of row n.
     const int n = rperm[slot];
     if (n < 0) return;
     const double vs = BITS == 1 ? valsumR[slot] : 0.0;
@@ -359,24 +413,56 @@ size_t rows_lds_bytes(const LayerDev& L, int waves) {
     return (std::max(table, std::max(stage, tiles)) + 15) & ~(size_t)15;
 }
 
-template <int BITS>
-int launch_rows(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, float* Y, const RowsParams& p,
-                int waves, hipStream_t s) {
-    const size_t lds = rows_lds_bytes(L, waves) + kColsumBytes;
+// bytes of LDS the packed-output epilogue needs for a layer of N rows (both planes) -- it reuses the table's place
+size_t rows_merge_bytes(int N) { return ((size_t)2 * ((N + 31) / 32) * T + T) * sizeof(uint32_t); }
+
+template <int BITS, bool REQ>
+int launch_rows(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, const float* scale, const float* shift,
+                float* Y, const RowsParams& p, int waves, hipStream_t s) {
+    size_t lds = rows_lds_bytes(L, waves) + kColsumBytes;
+    if (REQ) lds = std::max(lds, rows_merge_bytes(L.N));
+    if (lds > (size_t)kMaxLdsBytes) return APB_ERR_SHAPE;
     if (lds > 64 * 1024) {                                      // more LDS than a launch gets without asking
-        static std::atomic<size_t> asked[kMaxDevices];          // largest size asked for, per device
+        static std::atomic<size_t> asked[kMaxDevices];          // largest size asked for, per device and kernel
         int dev = 0;
         APB_HIP(hipGetDevice(&dev));
         if (dev < 0 || dev >= kMaxDevices) return APB_ERR_SHAPE;
         if (asked[dev].load(std::memory_order_acquire) < lds) {
-            APB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_forward_rows<BITS>),
+            APB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_forward_rows<BITS, REQ>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
             asked[dev].store((size_t)kMaxLdsBytes, std::memory_order_release);
         }
     }
-    hipLaunchKernelGGL((k_forward_rows<BITS>), dim3((unsigned)p.tasks), dim3(kWave * waves), lds, s, planes, colsum,
-                       L.rowsum, L.rows_perm, L.rows_blk, L.rows_ek, L.rows_ev, L.rows_sign, L.rows_valsum, Y, p);
+    hipLaunchKernelGGL((k_forward_rows<BITS, REQ>), dim3((unsigned)p.tasks), dim3(kWave * waves), lds, s, planes, colsum,
+                       L.rowsum, L.rows_perm, L.rows_blk, L.rows_ek, L.rows_ev, L.rows_sign, L.rows_valsum, scale, shift, Y,
+                       p);
     APB_HIP(hipGetLastError());
+    return APB_OK;
+}
+
+// Fills the launch parameters; APB_ERR_SHAPE where the kernel does not apply.
+int rows_params(const LayerDev& L, const uint32_t* planes, int M, int bits, float step, RowsParams& p, int& waves) {
+    if (L.rows_steps == 0 || (reinterpret_cast<uintptr_t>(planes) & 15u) != 0) return APB_ERR_SHAPE;
+    if (!mfma_sum_exact(L.K, 1, bits == 1 ? 1 : 3)) return APB_ERR_SHAPE;
+    const int Mp = kWave * ((M + kWave - 1) / kWave);
+    waves = rows_waves(L);
+    p.alpha = (double)L.alpha;
+    p.step = (double)step;
+    p.N = L.N;
+    p.Nr = L.rows_Nr;
+    p.Kw = L.Kw;
+    p.Kw4 = L.rows_Kw4;
+    p.Mp = Mp;
+    p.M = M;
+    p.nblocks = L.rows_Nr / kWave;
+    p.row_groups = (p.nblocks + waves - 1) / waves;
+    const long long tasks = (long long)p.row_groups * ((M + T - 1) / T);
+    if (tasks > 0x7fffffffLL || (long long)Mp * 8 >= (1LL << 31)) return APB_ERR_SHAPE;
+    p.tasks = (int)tasks;
+    p.lds_main_bytes = (int)rows_lds_bytes(L, waves);
+    p.out_bits = 0;
+    p.out_Kw = 0;
+    p.out_inv_step = 0.0f;
     return APB_OK;
 }
 
@@ -392,26 +478,38 @@ bool forward_rows_applies(const LayerDev& L, int M, int bits) {
 
 int launch_forward_rows(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                         float* Y, hipStream_t s) {
-    if (L.rows_steps == 0 || (reinterpret_cast<uintptr_t>(planes) & 15u) != 0) return APB_ERR_SHAPE;
-    if (!mfma_sum_exact(L.K, 1, bits == 1 ? 1 : 3)) return APB_ERR_SHAPE;
-    const int Mp = kWave * ((M + kWave - 1) / kWave);
-    const int waves = rows_waves(L);
     RowsParams p;
-    p.alpha = (double)L.alpha;
-    p.step = (double)step;
-    p.N = L.N;
-    p.Nr = L.rows_Nr;
-    p.Kw = L.Kw;
-    p.Kw4 = L.rows_Kw4;
-    p.Mp = Mp;
-    p.M = M;
-    p.nblocks = L.rows_Nr / kWave;
-    p.row_groups = (p.nblocks + waves - 1) / waves;
-    const long long tasks = (long long)p.row_groups * ((M + T - 1) / T);
-    if (tasks > 0x7fffffffLL || (long long)Mp * 8 >= (1LL << 31)) return APB_ERR_SHAPE;
-    p.tasks = (int)tasks;
-    p.lds_main_bytes = (int)rows_lds_bytes(L, waves);
-    return bits == 1 ? launch_rows<1>(L, planes, colsum, Y, p, waves, s) : launch_rows<2>(L, planes, colsum, Y, p, waves, s);
+    int waves;
+    const int rc = rows_params(L, planes, M, bits, step, p, waves);
+    if (rc != APB_OK) return rc;
+    return bits == 1 ? launch_rows<1, false>(L, planes, colsum, nullptr, nullptr, Y, p, waves, s)
+                     : launch_rows<2, false>(L, planes, colsum, nullptr, nullptr, Y, p, waves, s);
+}
+
+// The same kernel ending in the next layer's quantizer (packed output): where the float-output form applies and
+// the bits of all N rows of 16 columns fit the LDS of a workgroup.
+bool forward_rows_requant_applies(const LayerDev& L, const uint32_t* planes, int M, int bits) {
+    return forward_rows_applies(L, M, bits) && (reinterpret_cast<uintptr_t>(planes) & 15u) == 0 &&
+           rows_merge_bytes(L.N) <= (size_t)kMaxLdsBytes;
+}
+
+int launch_forward_rows_requant(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
+                                float step, const float* scale, const float* shift, int bits_out, float inv_step_out,
+                                uint32_t* packed_out, hipStream_t s) {
+    RowsParams p;
+    int waves;
+    int rc = rows_params(L, planes, M, bits, step, p, waves);
+    if (rc != APB_OK) return rc;
+    p.out_bits = bits_out;
+    p.out_Kw = (L.N + 31) / 32;
+    p.out_inv_step = inv_step_out;
+    // the workgroups OR their bits into the buffer: cleared here (a fill kernel, not a memset node: the call may
+    // be recorded into a graph)
+    rc = launch_zero_words(packed_out, ((size_t)bits_out * p.out_Kw + 1) * p.Mp, s);
+    if (rc != APB_OK) return rc;
+    float* out = reinterpret_cast<float*>(packed_out);
+    return bits == 1 ? launch_rows<1, true>(L, planes, colsum, scale, shift, out, p, waves, s)
+                     : launch_rows<2, true>(L, planes, colsum, scale, shift, out, p, waves, s);
 }
 
 int launch_forward_best(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,

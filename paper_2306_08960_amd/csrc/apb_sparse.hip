@@ -911,6 +911,9 @@ const char* forward_kernel_name(const LayerDev& L, int M, int bits) {
 int launch_forward_requant(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                            const ConvShape* conv, const float* scale, const float* shift, int bits_out,
                            float inv_step_out, uint32_t* packed_out, hipStream_t s) {
+    if (!conv && forward_rows_requant_applies(L, planes, M, bits))
+        return launch_forward_rows_requant(L, planes, colsum, M, bits, step, scale, shift, bits_out, inv_step_out, packed_out,
+                                           s);
     return launch_any(L, planes, colsum, M, bits, step, conv, OutArgs{scale, shift, reinterpret_cast<float*>(packed_out)},
                       bits_out, inv_step_out, s);
 }

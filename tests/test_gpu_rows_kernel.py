@@ -4,7 +4,8 @@ entry point, every output of Y within 1e-5 relative, no floor.  Each case first 
 library reports, that it is this kernel that runs.  Shapes: rows not a multiple of 64 (padding slots), K not a
 multiple of 128 or of 32 (padded matrix steps, partial last word), column groups with fewer than 16 valid columns,
 one column, empty rows and rows of very different lengths (padding entries in the lists), the largest K whose code
-table fits on chip, both activation widths."""
+table fits on chip, both activation widths.  Every case that runs on this kernel also runs its packed-output
+form (apb_forward_requant) and compares the codes and column sums with the oracle's."""
 import os
 
 import numpy as np
@@ -14,6 +15,7 @@ import torch
 from oracle import apb_oracle as o
 from oracle import capi
 from paper_2306_08960_amd import synth
+from requant_checks import compare_codes, unpack
 
 pytestmark = pytest.mark.gpu
 THREADS = max(1, min(16, len(os.sched_getaffinity(0))))
@@ -44,6 +46,25 @@ def check(b, W, delta, X, bits, step, tag, expect_rows=True):
     ref = F["Y"].astype(np.float64)
     bad = ~(np.abs(Y - ref) <= 1e-5 * np.abs(ref))             # (a NaN left in Y counts as bad)
     assert not bad.any(), f"{int(bad.sum())} of {bad.size} outputs off; first at {np.argwhere(bad)[0]}"
+    if expect_rows:
+        # the same kernel ending in the next layer's quantizer (apb_forward_requant): both output widths, with and
+        # without the per-row affine map, into a buffer full of ones
+        r = np.random.default_rng(N + K)
+        for bits_out in (2, 1):
+            step_out = np.float32(np.std(ref) * 0.7 + 1e-3)
+            scale = r.uniform(0.5, 1.5, N).astype(np.float32)
+            shift = (r.standard_normal(N) * float(step_out)).astype(np.float32)
+            for sc, sh in ((None, None), (scale, shift)):
+                want = o.requant(L["alpha"], step, F["D"], F["R"], bits_out, step_out, sc, sh)
+                out = b.alloc_packed(N, M, bits_out)
+                out.fill_(-1)
+                b.apb_forward_requant(layer, packed, M, bits, float(step), bits_out, float(step_out),
+                                      None if sc is None else torch.from_numpy(sc).cuda(),
+                                      None if sh is None else torch.from_numpy(sh).cuda(), packed_out=out)
+                torch.cuda.synchronize()
+                code, colsum = unpack(out.cpu().numpy().view(np.uint32), N, M, bits_out)
+                assert np.array_equal(colsum[:M], code.sum(axis=0))
+                compare_codes(code, want, L["alpha"], step, F["D"], F["R"], bits_out, step_out, sc, sh)
     layer.free()
 
 
