@@ -389,11 +389,20 @@ def run_conv_chain(name, steps, warmup):
     del pad
     packed = b.alloc_packed(K, M, bits)
 
+    # the step is called with a workspace of apb_acts_bytes(K, M, bits): layers with many residuals per row write
+    # the packed patch matrix there and multiply it as a plain matrix, the others gather inside the kernel
+    workspace = b.alloc_packed(K, M, bits)
+    takes_patch_route = b.apb_forward_kernel_name(layer, M, bits).startswith("k_forward_rows")
+
     def chained():
+        b.apb_forward_conv3x3_requant(layer, fmap, B, H, W_, bits, s, bits_out, step_out, fmap_out=fmap_out,
+                                      workspace=workspace)
+
+    def chained_gather():
         b.apb_forward_conv3x3_requant(layer, fmap, B, H, W_, bits, s, bits_out, step_out, fmap_out=fmap_out)
 
     def conv_float():
-        b.apb_forward_conv3x3(layer, fmap, B, H, W_, bits, s, Y=Y)
+        b.apb_forward_conv3x3(layer, fmap, B, H, W_, bits, s, Y=Y, workspace=workspace)
 
     def explicit():
         b.apb_quantize_acts(X, bits, s, packed=packed)
@@ -404,6 +413,7 @@ def run_conv_chain(name, steps, warmup):
     conv_float()
     same = bool(torch.equal(Y, Y_conv))                      # explicit and implicit routes, bit for bit
     ms_call = graph_ms(chained)
+    ms_call_gather = graph_ms(chained_gather) if takes_patch_route else ms_call
     ops = 2.0 * N * K * M + 2.0 * nnz * M
     Kw, Mp, Cw, Nw = (K + 31) // 32, 64 * ((M + 63) // 64), C // 32, (N + 31) // 32
     out_bytes = 4.0 * (bits_out * Nw + 1) * Mp
@@ -420,12 +430,15 @@ def run_conv_chain(name, steps, warmup):
         roof = {"bound": "mfma", "achieved": 2.0 * N * K * M / t / 1e12, "peak": MFMA_FP4_PEAK_TFLOPS, "unit": "TFLOP/s"}
     else:
         roof = {"bound": "alu", "achieved": 2.0 * nnz * M / t / 1e12, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s"}
-    roof = {"kernel": "forward kernel, implicit im2col + packed-output epilogue (+ zero fill)"} | roof
+    roof = {"kernel": ("packed patch matrix + rows-in-lanes forward kernel with the packed-output epilogue (+ zero fill)"
+                       if takes_patch_route else
+                       "forward kernel, implicit im2col + packed-output epilogue (+ zero fill)")} | roof
     roof |= {"frac": roof["achieved"] / roof["peak"], "traffic": None, "ms": ms_call,
              "floor_us": {"hbm": t_hbm * 1e6, "mfma_fp4": t_mfma * 1e6, "fp64_vector": t_f64 * 1e6}}
     t_valu = (2.0 * bits * N * Kw * M + float(nnz) * M) / VALU_LANE_OPS_PER_S
     res = {"workload": name, "N": N, "C": C, "B": B, "H": H, "W": W_, "act_bits": bits, "nnz": int(nnz),
            "ms_per_step": ms_chain, "gops_step": ops / (ms_chain * 1e-3) / 1e9,
+           "packed_patch_route": takes_patch_route, "ms_step_graph": ms_call, "ms_step_graph_gather_in_kernel": ms_call_gather,
            "ms_conv_float_output": ms_float, "ms_explicit_im2col_quantize_plus_forward": ms_explicit,
            "implicit_equals_explicit_bitwise": same, "roofline": roof, "bits_out": bits_out, "step_out": step_out,
            "frac_of_valu_bitop_roof": t_valu / t}
@@ -658,7 +671,9 @@ def main():
             "config": {"workload": f"{cfg.name}: {cfg.note}", "N": res["N"], "C": res["C"], "B": res["B"], "H": res["H"],
                        "W": res["W"], "act_bits": cfg.bits, "outlier_rate": cfg.rho, "nnz": res["nnz"],
                        "bits_out": res["bits_out"], "step_out": res["step_out"],
-                       "step": "apb_forward_conv3x3_requant, packed input map resident in HBM"},
+                       "step": "apb_forward_conv3x3_requant with a workspace, packed input map resident in HBM",
+                       "packed_patch_route": res["packed_patch_route"]},
+            "ms_step_graph": res["ms_step_graph"], "ms_step_graph_gather_in_kernel": res["ms_step_graph_gather_in_kernel"],
             "ms_conv_float_output": res["ms_conv_float_output"],
             "ms_explicit_im2col_quantize_plus_forward": res["ms_explicit_im2col_quantize_plus_forward"],
             "implicit_equals_explicit_bitwise": res["implicit_equals_explicit_bitwise"],

@@ -192,6 +192,12 @@ int apb_forward_requant(const apb_layer* layer, const void* packed, int M, int b
  *   stride  1 or 2.  The output map has Ho = (H - 1) / stride + 1 rows and Wo = (W - 1) / stride + 1 columns;
  *           output pixel (b, yo, xo) sees the inputs (b, stride*yo + ky - 1, stride*xo + kx - 1).
  *   padding pixels outside the image have code 0: the value 0 for 2-bit activations, -step for 1-bit.
+ *   workspace, workspace_bytes  optional DEVICE scratch (NULL, 0: none), 16-byte aligned.  With at least
+ *           apb_acts_bytes(9*C, Po, bits) bytes, layers with many residuals per row (those apb_forward runs
+ *           with its lanes along the rows) first write the packed patch matrix there -- bit words, 1/16 or
+ *           1/32 of the float im2col matrix -- and multiply it as a plain matrix, which is faster for them
+ *           than gathering inside the kernel; other layers, and calls without a workspace, gather.  Contents
+ *           unspecified afterwards.  Same results either way (to the rounding of the float64 sums).
  *   Y       DEVICE, N*Po floats (Po = B*Ho*Wo), channel-major like the input map, fully overwritten.
  * The _requant form ends with the next layer's quantizer as apb_forward_requant does and writes the
  * packed output map (apb_acts_bytes(N, Po, bits_out) bytes), which a following 3 x 3 layer with C = N and
@@ -199,10 +205,10 @@ int apb_forward_requant(const apb_layer* layer, const void* packed, int M, int b
  * if stride is neither 1 nor 2, if B*H*W >= 2^28 or if one bit-plane of the map reaches 2^31 bytes.
  * Asynchronous on `stream`. */
 int apb_forward_conv3x3(const apb_layer* layer, const void* fmap, int B, int H, int W, int stride, int bits, float step,
-                        float* Y, void* stream);
+                        void* workspace, size_t workspace_bytes, float* Y, void* stream);
 int apb_forward_conv3x3_requant(const apb_layer* layer, const void* fmap, int B, int H, int W, int stride, int bits,
                                 float step, const float* scale, const float* shift, int bits_out, float step_out,
-                                void* fmap_out, void* stream);
+                                void* workspace, size_t workspace_bytes, void* fmap_out, void* stream);
 
 /* Test hook: the integer part D (N*M int32, row-major, DEVICE) alone, computed by the stand-alone
  * matrix-core kernel (the same bit expansion and matrix instruction as apb_forward's first

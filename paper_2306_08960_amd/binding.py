@@ -77,9 +77,9 @@ def load() -> ctypes.CDLL:
     lib.apb_quantize_forward_is_one_kernel.restype = ci
     lib.apb_forward_requant.argtypes = [vp, vp, ci, ci, cf, vp, vp, ci, cf, vp, vp]
     lib.apb_forward_requant.restype = ci
-    lib.apb_forward_conv3x3.argtypes = [vp, vp, ci, ci, ci, ci, ci, cf, vp, vp]
+    lib.apb_forward_conv3x3.argtypes = [vp, vp, ci, ci, ci, ci, ci, cf, vp, ctypes.c_size_t, vp, vp]
     lib.apb_forward_conv3x3.restype = ci
-    lib.apb_forward_conv3x3_requant.argtypes = [vp, vp, ci, ci, ci, ci, ci, cf, vp, vp, ci, cf, vp, vp]
+    lib.apb_forward_conv3x3_requant.argtypes = [vp, vp, ci, ci, ci, ci, ci, cf, vp, vp, ci, cf, vp, ctypes.c_size_t, vp, vp]
     lib.apb_forward_conv3x3_requant.restype = ci
     lib.apb_forward_int.argtypes = [vp, vp, ci, ci, vp, vp]
     lib.apb_forward_int.restype = ci
@@ -318,6 +318,13 @@ def apb_forward_requant(layer: ApbLayer, packed: torch.Tensor, M: int, bits: int
     return packed_out
 
 
+def _workspace(t: Optional[torch.Tensor]):
+    """(pointer, bytes) of an optional scratch tensor."""
+    if t is None:
+        return None, 0
+    return _dev_ptr(t, torch.int32, "workspace"), t.numel() * t.element_size()
+
+
 def _check_fmap(layer: ApbLayer, fmap: torch.Tensor, B: int, H: int, W: int, bits: int, stride: int) -> Tuple[int, int]:
     """(N, output pixels B*Ho*Wo) after checking the size of the input map's buffer."""
     i = apb_layer_info(layer)
@@ -334,15 +341,17 @@ def _check_fmap(layer: ApbLayer, fmap: torch.Tensor, B: int, H: int, W: int, bit
 
 def apb_forward_conv3x3(layer: ApbLayer, fmap: torch.Tensor, B: int, H: int, W: int, bits: int, step: float,
                         Y: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None,
-                        stride: int = 1) -> torch.Tensor:
-    """3x3 convolution (padding 1) over a packed feature map [C, B*H*W]; Y is [N, B*Ho*Wo]."""
+                        stride: int = 1, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """3x3 convolution (padding 1) over a packed feature map [C, B*H*W]; Y is [N, B*Ho*Wo].  `workspace`: an
+    optional int32 scratch tensor (see the header)."""
     N, P = _check_fmap(layer, fmap, B, H, W, bits, stride)
     if Y is None:
         Y = torch.empty((N, P), dtype=torch.float32, device=fmap.device)
     elif tuple(Y.shape) != (N, P):
         raise ValueError("Y must be [N, B*Ho*Wo]")
     _check(load().apb_forward_conv3x3(layer.handle, _dev_ptr(fmap, torch.int32, "fmap"), int(B), int(H), int(W), int(stride),
-                                      int(bits), float(step), _dev_ptr(Y, torch.float32, "Y"), _stream(stream)),
+                                      int(bits), float(step), *_workspace(workspace), _dev_ptr(Y, torch.float32, "Y"),
+                                      _stream(stream)),
            "apb_forward_conv3x3")
     return Y
 
@@ -350,7 +359,8 @@ def apb_forward_conv3x3(layer: ApbLayer, fmap: torch.Tensor, B: int, H: int, W: 
 def apb_forward_conv3x3_requant(layer: ApbLayer, fmap: torch.Tensor, B: int, H: int, W: int, bits: int, step: float,
                                 bits_out: int, step_out: float, scale: Optional[torch.Tensor] = None,
                                 shift: Optional[torch.Tensor] = None, fmap_out: Optional[torch.Tensor] = None,
-                                stream: Optional[torch.cuda.Stream] = None, stride: int = 1) -> torch.Tensor:
+                                stream: Optional[torch.cuda.Stream] = None, stride: int = 1,
+                                workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     N, P = _check_fmap(layer, fmap, B, H, W, bits, stride)
     if (scale is None) != (shift is None):
         raise ValueError("scale and shift go together")
@@ -365,7 +375,7 @@ def apb_forward_conv3x3_requant(layer: ApbLayer, fmap: torch.Tensor, B: int, H: 
         layer.handle, _dev_ptr(fmap, torch.int32, "fmap"), int(B), int(H), int(W), int(stride), int(bits), float(step),
         None if scale is None else _dev_ptr(scale, torch.float32, "scale"),
         None if shift is None else _dev_ptr(shift, torch.float32, "shift"), int(bits_out), float(step_out),
-        _dev_ptr(fmap_out, torch.int32, "fmap_out"), _stream(stream)), "apb_forward_conv3x3_requant")
+        *_workspace(workspace), _dev_ptr(fmap_out, torch.int32, "fmap_out"), _stream(stream)), "apb_forward_conv3x3_requant")
     return fmap_out
 
 

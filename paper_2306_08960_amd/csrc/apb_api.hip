@@ -454,24 +454,48 @@ static int conv_shape(const LayerDev& d, int B, int H, int W, int stride, ConvSh
     return APB_OK;
 }
 
+// With a workspace, layers on which the rows-in-lanes kernel applies write the packed patch matrix there first and
+// run the plain-matrix kernels on it; `patches` is null otherwise.
+static int conv_patches(const LayerDev& d, const uint32_t* planes, const int32_t* pixsum, int P, int bits,
+                        const ConvShape& conv, void* workspace, size_t workspace_bytes, hipStream_t s,
+                        const uint32_t** patches, const int32_t** colsum) {
+    *patches = nullptr;
+    *colsum = nullptr;
+    const size_t Pp = (size_t)kWave * (((size_t)P + kWave - 1) / kWave);
+    const size_t need = sizeof(uint32_t) * Pp * ((size_t)bits * d.Kw + 1);
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15u) != 0) return APB_OK;
+    if (!forward_rows_applies(d, P, bits)) return APB_OK;
+    uint32_t* out = static_cast<uint32_t*>(workspace);
+    const int rc = launch_pack_patches(d, planes, pixsum, P, bits, conv, out, s);
+    if (rc != APB_OK) return rc;
+    *patches = out;
+    *colsum = reinterpret_cast<const int32_t*>(out + (size_t)bits * d.Kw * Pp);
+    return APB_OK;
+}
+
 int apb_forward_conv3x3(const apb_layer* layer, const void* fmap, int B, int H, int W, int stride, int bits, float step,
-                        float* Y, void* stream) {
+                        void* workspace, size_t workspace_bytes, float* Y, void* stream) {
     if (!layer || !fmap || !Y) return APB_ERR_NULL;
     const LayerDev& d = layer->d;
     ConvShape conv;
     int P;
-    const int rc = conv_shape(d, B, H, W, stride, conv, P);
+    int rc = conv_shape(d, B, H, W, stride, conv, P);
     if (rc != APB_OK) return rc;
     if (bits != 1 && bits != 2) return APB_ERR_BITS;
     if (!std::isfinite(step) || !(step > 0.0f)) return APB_ERR_VALUE;
+    hipStream_t s = as_stream(stream);
     const uint32_t* planes = static_cast<const uint32_t*>(fmap);
     const int32_t* pixsum = reinterpret_cast<const int32_t*>(planes + (size_t)bits * (conv.C / 32) * conv.Pp_in);
-    return launch_forward(d, planes, pixsum, P, bits, step, &conv, Y, as_stream(stream));
+    const uint32_t* patches;
+    const int32_t* colsum;
+    if ((rc = conv_patches(d, planes, pixsum, P, bits, conv, workspace, workspace_bytes, s, &patches, &colsum)) != APB_OK) return rc;
+    if (patches) return launch_forward_best(d, patches, colsum, P, bits, step, Y, s);
+    return launch_forward(d, planes, pixsum, P, bits, step, &conv, Y, s);
 }
 
 int apb_forward_conv3x3_requant(const apb_layer* layer, const void* fmap, int B, int H, int W, int stride, int bits,
                                 float step, const float* scale, const float* shift, int bits_out, float step_out,
-                                void* fmap_out, void* stream) {
+                                void* workspace, size_t workspace_bytes, void* fmap_out, void* stream) {
     if (!layer || !fmap || !fmap_out || (scale == nullptr) != (shift == nullptr)) return APB_ERR_NULL;
     const LayerDev& d = layer->d;
     ConvShape conv;
@@ -484,6 +508,11 @@ int apb_forward_conv3x3_requant(const apb_layer* layer, const void* fmap, int B,
     const int32_t* pixsum = reinterpret_cast<const int32_t*>(planes + (size_t)bits * (conv.C / 32) * conv.Pp_in);
     hipStream_t s = as_stream(stream);
     uint32_t* out = static_cast<uint32_t*>(fmap_out);
+    const uint32_t* patches;
+    const int32_t* colsum;
+    if ((rc = conv_patches(d, planes, pixsum, P, bits, conv, workspace, workspace_bytes, s, &patches, &colsum)) != APB_OK) return rc;
+    if (patches)
+        return launch_forward_requant(d, patches, colsum, P, bits, step, nullptr, scale, shift, bits_out, 1.0f / step_out, out, s);
     return launch_forward_requant(d, planes, pixsum, P, bits, step, &conv, scale, shift, bits_out, 1.0f / step_out, out, s);
 }
 

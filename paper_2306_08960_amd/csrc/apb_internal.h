@@ -121,6 +121,9 @@ struct ConvShape {
 };
 int launch_forward(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                    const ConvShape* conv, float* Y, hipStream_t s);
+// the packed patch matrix of a convolution (9 * C x M, as apb_quantize_acts lays a matrix out) written into `out`
+int launch_pack_patches(const LayerDev& L, const uint32_t* planes, const int32_t* pixsum, int M, int bits,
+                        const ConvShape& conv, uint32_t* out, hipStream_t s);
 const char* forward_kernel_name(const LayerDev& L, int M, int bits);
 // quantize + forward in one kernel, from the float matrix X (K x M): same Y, bit for bit, as launch_quantize +
 // launch_forward; only where forward_float_applies says so (APB_ERR_SHAPE otherwise)

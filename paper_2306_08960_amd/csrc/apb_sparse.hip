@@ -718,6 +718,41 @@ __global__ __launch_bounds__(kWave* kChunkWords) __attribute__((amdgpu_waves_per
     write_rows<BITS>(acc, slot0, m, perm, slot_valsum, scale, shift, out, p);
 }
 
+
+// The packed patch matrix of a convolution written out: word row tap * Cw + cw of column m (an output pixel) is
+// word row cw of the map at the pixel shifted by the tap, or zero outside the image; the column sum is the sum
+// of the per-pixel sums over the valid taps.  Bit words only -- 1/16 (2-bit) or 1/32 (1-bit) of the float im2col
+// matrix.  For layers that run faster on the plain-matrix kernel with the lanes along the rows (apb_rows.hip) than
+// on the implicit gather.  Thread = one column, blockIdx.y = a slab of kPatchRows word rows.
+constexpr int kPatchRows = 8;
+
+template <int BITS>
+__global__ __launch_bounds__(256) void k_pack_patches(const uint32_t* __restrict__ planes, const int32_t* __restrict__ pixsum,
+                                                     uint32_t* __restrict__ out, int32_t* __restrict__ out_colsum,
+                                                     const SparseParams p) {
+    const int m = blockIdx.x * 256 + threadIdx.x;               // < Mp: the grid tiles Mp (a multiple of 64) in 256s
+    if (m >= p.Mp) return;
+    int pin = 0;
+    const uint32_t vm = conv_pixel(m, p, pin);
+    const size_t in_stride = (size_t)p.conv_Cw * p.conv_Mp, out_stride = (size_t)p.Kw * p.Mp;
+    const int j0 = blockIdx.y * kPatchRows, j1 = min(p.Kw, j0 + kPatchRows);
+    for (int j = j0; j < j1; ++j) {
+        const int tap = tap_of_row(j, p);
+        const int cw = j - tap * p.conv_Cw;
+        const bool ok = (vm >> tap) & 1u;
+        const size_t at = (size_t)cw * p.conv_Mp + (size_t)(pin + tap_shift(tap, p.conv_W));
+#pragma unroll
+        for (int pl = 0; pl < BITS; ++pl) out[pl * out_stride + (size_t)j * p.Mp + m] = ok ? planes[pl * in_stride + at] : 0u;
+    }
+    if (blockIdx.y == 0) {
+        int cs = 0;
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+            if ((vm >> t) & 1u) cs += pixsum[pin + tap_shift(t, p.conv_W)];
+        out_colsum[m] = cs;
+    }
+}
+
 template <int KS>
 constexpr int ksplit_lds_bytes() {
     constexpr int tables = KS * kTableBytes;
@@ -872,10 +907,34 @@ int launch_any(const LayerDev& L, const uint32_t* planes, const int32_t* colsum,
 }  // namespace
 
 // conv == nullptr: `planes` is the packed K x M matrix.  Otherwise it is a packed feature map of conv->C
-// channels (L.K = 9 * C, C a multiple of 64) and M = B * H * W pixels, read through the implicit im2col.
+// channels (L.K = 9 * C, C a multiple of 32) and M = B * Ho * Wo output pixels, read through the implicit im2col.
 int launch_forward(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                    const ConvShape* conv, float* Y, hipStream_t s) {
     return launch_any(L, planes, colsum, M, bits, step, conv, OutArgs{nullptr, nullptr, Y}, 0, 0.0f, s);
+}
+
+// conv -> the packed K x M patch matrix in `out` (planes, then column sums: apb_acts_bytes(9 * C, M, bits) bytes)
+int launch_pack_patches(const LayerDev& L, const uint32_t* planes, const int32_t* pixsum, int M, int bits,
+                        const ConvShape& conv, uint32_t* out, hipStream_t s) {
+    const int Mp = kWave * ((M + kWave - 1) / kWave);
+    SparseParams p{};
+    p.Kw = L.Kw;
+    p.Mp = Mp;
+    p.M = M;
+    p.conv_Cw = conv.C / 32;
+    p.conv_H = conv.H;
+    p.conv_W = conv.W;
+    p.conv_Ho = conv.Ho;
+    p.conv_Wo = conv.Wo;
+    p.conv_stride = conv.stride;
+    p.conv_Mp = conv.Pp_in;
+    p.conv_inv_Cw = 1.0f / (float)(conv.C / 32);
+    int32_t* out_colsum = reinterpret_cast<int32_t*>(out + (size_t)bits * L.Kw * Mp);
+    const dim3 grid((unsigned)((Mp + 255) / 256), (unsigned)((L.Kw + kPatchRows - 1) / kPatchRows));
+    if (bits == 1) hipLaunchKernelGGL(k_pack_patches<1>, grid, dim3(256), 0, s, planes, pixsum, out, out_colsum, p);
+    else hipLaunchKernelGGL(k_pack_patches<2>, grid, dim3(256), 0, s, planes, pixsum, out, out_colsum, p);
+    APB_HIP(hipGetLastError());
+    return APB_OK;
 }
 
 // Quantize + forward in one kernel applies when one workgroup holds every row of the layer (so that no

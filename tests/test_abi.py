@@ -69,8 +69,8 @@ def test_argument_errors_without_touching_the_gpu():
     assert lib.apb_quantize_forward(None, fake, 4, 1, 1.0, fake, fake, None) == b.APB_ERR_NULL
     assert lib.apb_quantize_forward_is_one_kernel(None, 4, 1) == 0
     assert lib.apb_forward_requant(None, fake, 4, 1, 1.0, None, None, 2, 1.0, fake, None) == b.APB_ERR_NULL
-    assert lib.apb_forward_conv3x3(None, fake, 1, 4, 4, 1, 2, 1.0, fake, None) == b.APB_ERR_NULL
-    assert lib.apb_forward_conv3x3_requant(None, fake, 1, 4, 4, 1, 2, 1.0, None, None, 2, 1.0, fake, None) == b.APB_ERR_NULL
+    assert lib.apb_forward_conv3x3(None, fake, 1, 4, 4, 1, 2, 1.0, None, 0, fake, None) == b.APB_ERR_NULL
+    assert lib.apb_forward_conv3x3_requant(None, fake, 1, 4, 4, 1, 2, 1.0, None, None, 2, 1.0, None, 0, fake, None) == b.APB_ERR_NULL
     assert lib.apb_layer_info(None, None, None, None, None, None) == b.APB_ERR_NULL
     assert lib.apb_layer_export(None, None, None, None, None, None, None) == b.APB_ERR_NULL
     lib.apb_layer_free(None)

@@ -78,6 +78,13 @@ def test_conv_matches_oracle(b, N, C, B, H, W, stride, bits):
     assert Y.shape == (N, P)
     ref = F["Y"].astype(np.float64)
     assert np.all(np.abs(Y.astype(np.float64) - ref) <= REL_TOL * np.abs(ref))
+    # with a workspace (layers with many residuals per row then multiply the written-out packed patch matrix;
+    # the others ignore it): the same bar, and a workspace that is too small is ignored as well
+    ws = b.alloc_packed(9 * C, P, bits)
+    for w in (ws, ws[: max(1, ws.numel() // 2)]):
+        w.fill_(-1)
+        Yw = b.apb_forward_conv3x3(layer, fmap, B, H, W, bits, float(step), stride=stride, workspace=w).cpu().numpy()
+        assert np.all(np.abs(Yw.astype(np.float64) - ref) <= REL_TOL * np.abs(ref))
 
     # packed output map, then a second 3x3 layer on it (only where N can be a channel count)
     step_out = np.float32(0.03 * np.sqrt(9 * C))
@@ -95,6 +102,17 @@ def test_conv_matches_oracle(b, N, C, B, H, W, stride, bits):
         code, pixsum = unpack(out.cpu().numpy().view(np.uint32), N, P, 2)
         assert np.array_equal(pixsum[:P], code.sum(axis=0))
         compare_codes(code, want, L["alpha"], step, F["D"], F["R"], 2, step_out, sc, sh)
+        out_w = b.alloc_packed(N, P, 2)
+        out_w.fill_(-1)
+        ws.fill_(-1)
+        b.apb_forward_conv3x3_requant(layer, fmap, B, H, W, bits, float(step), 2, float(step_out),
+                                      None if sc is None else torch.from_numpy(sc).cuda(),
+                                      None if sh is None else torch.from_numpy(sh).cuda(), fmap_out=out_w, stride=stride,
+                                      workspace=ws)
+        torch.cuda.synchronize()
+        code_w, pixsum_w = unpack(out_w.cpu().numpy().view(np.uint32), N, P, 2)
+        assert np.array_equal(pixsum_w[:P], code_w.sum(axis=0))
+        compare_codes(code_w, want, L["alpha"], step, F["D"], F["R"], 2, step_out, sc, sh)
     if N % 32 == 0:
         # (the output map is B images of Ho x Wo pixels; the second layer runs on it with stride 1)
         W2, delta2, _, _ = synth.random_case(N + 1, 24, 9 * N, 1, 2, rho=0.02)
@@ -124,7 +142,7 @@ def test_shape_errors(b):
     Y = torch.empty((8, 16), device="cuda")
     lib = b.load()
     for stride in (0, 3, -1):                                           # only strides 1 and 2
-        rc = lib.apb_forward_conv3x3(layer.handle, fmap.data_ptr(), 1, 4, 4, stride, 2, 0.75, Y.data_ptr(), None)
+        rc = lib.apb_forward_conv3x3(layer.handle, fmap.data_ptr(), 1, 4, 4, stride, 2, 0.75, None, 0, Y.data_ptr(), None)
         assert rc == b.APB_ERR_SHAPE
     layer.free()
 
@@ -155,6 +173,11 @@ def test_full_size_conv_layers_equal_the_explicit_route(b, name, B, H, W):
     out = b.apb_forward_conv3x3_requant(layer, fmap, B, H, W, bits, float(step), 2, 1.0)
     out_explicit = b.apb_forward_requant(layer, packed, P, bits, float(step), 2, 1.0)
     assert torch.equal(out, out_explicit)
+    ws = torch.full_like(packed, -1)
+    assert torch.equal(b.apb_forward_conv3x3(layer, fmap, B, H, W, bits, float(step), workspace=ws), Y)
+    if b.apb_forward_kernel_name(layer, P, bits).startswith("k_forward_rows"):
+        assert torch.equal(ws, packed)                        # the packed patch matrix, word for word
+    assert torch.equal(b.apb_forward_conv3x3_requant(layer, fmap, B, H, W, bits, float(step), 2, 1.0, workspace=ws), out)
     # sampled pixels against the oracle (image corners and edges included)
     L = o.compress(Wt, delta, alpha=np.float32(layer.info()["alpha"]))
     pix = np.unique(np.concatenate([[0, W - 1, (H - 1) * W, H * W - 1, P - 1, P - W],
@@ -193,6 +216,14 @@ def test_full_size_stride_2_layers_equal_the_explicit_route(b, N, C, B, H, W, bi
     assert torch.equal(Y, b.apb_forward(layer, packed, P, bits, float(step)))
     out = b.apb_forward_conv3x3_requant(layer, fmap, B, H, W, bits, float(step), 2, 1.0, stride=2)
     assert torch.equal(out, b.apb_forward_requant(layer, packed, P, bits, float(step), 2, 1.0))
+    # with a workspace: the packed patch matrix written there equals the quantized explicit matrix word for word
+    # wherever the layer takes that route, and the outputs stay the same
+    ws = torch.full_like(packed, -1)
+    Yw = b.apb_forward_conv3x3(layer, fmap, B, H, W, bits, float(step), stride=2, workspace=ws)
+    assert torch.equal(Yw, Y)
+    if b.apb_forward_kernel_name(layer, P, bits).startswith("k_forward_rows"):
+        assert torch.equal(ws, packed)
+    assert torch.equal(b.apb_forward_conv3x3_requant(layer, fmap, B, H, W, bits, float(step), 2, 1.0, stride=2, workspace=ws), out)
     L = o.compress(Wt, delta, alpha=np.float32(layer.info()["alpha"]))
     pix = np.unique(np.concatenate([[0, Wo - 1, (Ho - 1) * Wo, Ho * Wo - 1, P - 1, P - Wo],
                                     np.random.default_rng(7).choice(P, 40, replace=False)]))
