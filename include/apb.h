@@ -197,7 +197,8 @@ int apb_forward_requant(const apb_layer* layer, const void* packed, int M, int b
  *           with its lanes along the rows) first write the packed patch matrix there -- bit words, 1/16 or
  *           1/32 of the float im2col matrix -- and multiply it as a plain matrix, which is faster for them
  *           than gathering inside the kernel; other layers, and calls without a workspace, gather.  Contents
- *           unspecified afterwards.  Same results either way (to the rounding of the float64 sums).
+ *           unspecified afterwards; must not overlap fmap, Y or fmap_out.  Same results either way (to the
+ *           rounding of the float64 sums).
  *   Y       DEVICE, N*Po floats (Po = B*Ho*Wo), channel-major like the input map, fully overwritten.
  * The _requant form ends with the next layer's quantizer as apb_forward_requant does and writes the
  * packed output map (apb_acts_bytes(N, Po, bits_out) bytes), which a following 3 x 3 layer with C = N and

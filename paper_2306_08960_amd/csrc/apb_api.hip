@@ -457,8 +457,8 @@ static int conv_shape(const LayerDev& d, int B, int H, int W, int stride, ConvSh
 // With a workspace, layers on which the rows-in-lanes kernel applies write the packed patch matrix there first and
 // run the plain-matrix kernels on it; `patches` is null otherwise.
 static int conv_patches(const LayerDev& d, const uint32_t* planes, const int32_t* pixsum, int P, int bits,
-                        const ConvShape& conv, void* workspace, size_t workspace_bytes, hipStream_t s,
-                        const uint32_t** patches, const int32_t** colsum) {
+                        const ConvShape& conv, void* workspace, size_t workspace_bytes, uint32_t* clear, size_t clear_words,
+                        hipStream_t s, const uint32_t** patches, const int32_t** colsum) {
     *patches = nullptr;
     *colsum = nullptr;
     const size_t Pp = (size_t)kWave * (((size_t)P + kWave - 1) / kWave);
@@ -466,7 +466,7 @@ static int conv_patches(const LayerDev& d, const uint32_t* planes, const int32_t
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15u) != 0) return APB_OK;
     if (!forward_rows_applies(d, P, bits)) return APB_OK;
     uint32_t* out = static_cast<uint32_t*>(workspace);
-    const int rc = launch_pack_patches(d, planes, pixsum, P, bits, conv, out, s);
+    const int rc = launch_pack_patches(d, planes, pixsum, P, bits, conv, out, clear, clear_words, s);
     if (rc != APB_OK) return rc;
     *patches = out;
     *colsum = reinterpret_cast<const int32_t*>(out + (size_t)bits * d.Kw * Pp);
@@ -488,7 +488,8 @@ int apb_forward_conv3x3(const apb_layer* layer, const void* fmap, int B, int H, 
     const int32_t* pixsum = reinterpret_cast<const int32_t*>(planes + (size_t)bits * (conv.C / 32) * conv.Pp_in);
     const uint32_t* patches;
     const int32_t* colsum;
-    if ((rc = conv_patches(d, planes, pixsum, P, bits, conv, workspace, workspace_bytes, s, &patches, &colsum)) != APB_OK) return rc;
+    if ((rc = conv_patches(d, planes, pixsum, P, bits, conv, workspace, workspace_bytes, nullptr, 0, s, &patches, &colsum)) != APB_OK)
+        return rc;
     if (patches) return launch_forward_best(d, patches, colsum, P, bits, step, Y, s);
     return launch_forward(d, planes, pixsum, P, bits, step, &conv, Y, s);
 }
@@ -510,9 +511,14 @@ int apb_forward_conv3x3_requant(const apb_layer* layer, const void* fmap, int B,
     uint32_t* out = static_cast<uint32_t*>(fmap_out);
     const uint32_t* patches;
     const int32_t* colsum;
-    if ((rc = conv_patches(d, planes, pixsum, P, bits, conv, workspace, workspace_bytes, s, &patches, &colsum)) != APB_OK) return rc;
+    // (the kernel that follows the packed patch matrix ORs its bits into the output: cleared by the same launch)
+    const size_t Pp = (size_t)kWave * (((size_t)P + kWave - 1) / kWave);
+    const size_t out_words = ((size_t)bits_out * ((d.N + 31) / 32) + 1) * Pp;
+    if ((rc = conv_patches(d, planes, pixsum, P, bits, conv, workspace, workspace_bytes, out, out_words, s, &patches, &colsum)) != APB_OK)
+        return rc;
     if (patches)
-        return launch_forward_requant(d, patches, colsum, P, bits, step, nullptr, scale, shift, bits_out, 1.0f / step_out, out, s);
+        return launch_forward_requant(d, patches, colsum, P, bits, step, nullptr, scale, shift, bits_out, 1.0f / step_out, out, s,
+                                      true);
     return launch_forward_requant(d, planes, pixsum, P, bits, step, &conv, scale, shift, bits_out, 1.0f / step_out, out, s);
 }
 

@@ -122,8 +122,9 @@ struct ConvShape {
 int launch_forward(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                    const ConvShape* conv, float* Y, hipStream_t s);
 // the packed patch matrix of a convolution (9 * C x M, as apb_quantize_acts lays a matrix out) written into `out`
+// (and, on the side, `clear_words` words at `clear` set to zero)
 int launch_pack_patches(const LayerDev& L, const uint32_t* planes, const int32_t* pixsum, int M, int bits,
-                        const ConvShape& conv, uint32_t* out, hipStream_t s);
+                        const ConvShape& conv, uint32_t* out, uint32_t* clear, size_t clear_words, hipStream_t s);
 const char* forward_kernel_name(const LayerDev& L, int M, int bits);
 // quantize + forward in one kernel, from the float matrix X (K x M): same Y, bit for bit, as launch_quantize +
 // launch_forward; only where forward_float_applies says so (APB_ERR_SHAPE otherwise)
@@ -133,7 +134,8 @@ int launch_forward_float(const LayerDev& L, const float* X, int M, int bits, flo
 // the codes packed into `packed_out` (K = L.N, same M), fully overwritten
 int launch_forward_requant(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                            const ConvShape* conv, const float* scale, const float* shift, int bits_out,
-                           float inv_step_out, uint32_t* packed_out, hipStream_t s);
+                           float inv_step_out, uint32_t* packed_out, hipStream_t s, bool out_cleared = false);
+// (out_cleared: packed_out is known to be all zero already -- only the kernels that OR into it care)
 
 // true while K * max_weight * max_code < 2^24: the float accumulators of the matrix instruction then hold
 // every partial sum exactly (launchers return APB_ERR_SHAPE otherwise)
@@ -149,7 +151,7 @@ int launch_forward_rows(const LayerDev& L, const uint32_t* planes, const int32_t
 bool forward_rows_requant_applies(const LayerDev& L, const uint32_t* planes, int M, int bits);
 int launch_forward_rows_requant(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
                                 float step, const float* scale, const float* shift, int bits_out, float inv_step_out,
-                                uint32_t* packed_out, hipStream_t s);
+                                uint32_t* packed_out, hipStream_t s, bool out_cleared = false);
 // launch_quantize + launch_forward_best through the scratch buffer planes / colsum (the step of layers that do
 // not run as one kernel); what `colsum` holds afterwards is unspecified
 int launch_quantize_then_forward(const LayerDev& L, const float* X, int M, int bits, float step, uint32_t* planes,

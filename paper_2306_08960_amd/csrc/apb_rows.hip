@@ -495,7 +495,7 @@ bool forward_rows_requant_applies(const LayerDev& L, const uint32_t* planes, int
 
 int launch_forward_rows_requant(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits,
                                 float step, const float* scale, const float* shift, int bits_out, float inv_step_out,
-                                uint32_t* packed_out, hipStream_t s) {
+                                uint32_t* packed_out, hipStream_t s, bool out_cleared) {
     RowsParams p;
     int waves;
     int rc = rows_params(L, planes, M, bits, step, p, waves);
@@ -505,8 +505,10 @@ int launch_forward_rows_requant(const LayerDev& L, const uint32_t* planes, const
     p.out_inv_step = inv_step_out;
     // the workgroups OR their bits into the buffer: cleared here (a fill kernel, not a memset node: the call may
     // be recorded into a graph)
-    rc = launch_zero_words(packed_out, ((size_t)bits_out * p.out_Kw + 1) * p.Mp, s);
-    if (rc != APB_OK) return rc;
+    if (!out_cleared) {
+        rc = launch_zero_words(packed_out, ((size_t)bits_out * p.out_Kw + 1) * p.Mp, s);
+        if (rc != APB_OK) return rc;
+    }
     float* out = reinterpret_cast<float*>(packed_out);
     return bits == 1 ? launch_rows<1, true>(L, planes, colsum, scale, shift, out, p, waves, s)
                      : launch_rows<2, true>(L, planes, colsum, scale, shift, out, p, waves, s);

@@ -723,28 +723,44 @@ __global__ __launch_bounds__(kWave* kChunkWords) __attribute__((amdgpu_waves_per
 // word row cw of the map at the pixel shifted by the tap, or zero outside the image; the column sum is the sum
 // of the per-pixel sums over the valid taps.  Bit words only -- 1/16 (2-bit) or 1/32 (1-bit) of the float im2col
 // matrix.  For layers that run faster on the plain-matrix kernel with the lanes along the rows (apb_rows.hip) than
-// on the implicit gather.  Thread = one column, blockIdx.y = a slab of kPatchRows word rows.
+// on the implicit gather.  Thread = one column of one tap and a slab of kPatchRows word rows of the map.
 constexpr int kPatchRows = 8;
 
 template <int BITS>
-__global__ __launch_bounds__(256) void k_pack_patches(const uint32_t* __restrict__ planes, const int32_t* __restrict__ pixsum,
+__global__ __launch_bounds__(128) void k_pack_patches(const uint32_t* __restrict__ planes, const int32_t* __restrict__ pixsum,
                                                      uint32_t* __restrict__ out, int32_t* __restrict__ out_colsum,
-                                                     const SparseParams p) {
-    const int m = blockIdx.x * 256 + threadIdx.x;               // < Mp: the grid tiles Mp (a multiple of 64) in 256s
+                                                     uint32_t* __restrict__ clear, size_t clear_words, const SparseParams p) {
+    // On the side: clear `clear_words` words at `clear` (the packed output buffer of a kernel that ORs into it --
+    // one launch less than a fill kernel of its own).
+    {
+        const size_t threads = (size_t)gridDim.x * gridDim.y * gridDim.z * 128;
+        const size_t me = (((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 128 + threadIdx.x;
+        for (size_t i = me; i < clear_words; i += threads) clear[i] = 0u;
+    }
+    // blockIdx.y = tap, blockIdx.z = slab of kPatchRows word rows of the map: validity and shift are computed once
+    const int m = blockIdx.x * 128 + threadIdx.x;               // < Mp: the grid tiles Mp (a multiple of 64) in 128s
     if (m >= p.Mp) return;
     int pin = 0;
     const uint32_t vm = conv_pixel(m, p, pin);
+    const int tap = blockIdx.y;
+    const bool ok = (vm >> tap) & 1u;
     const size_t in_stride = (size_t)p.conv_Cw * p.conv_Mp, out_stride = (size_t)p.Kw * p.Mp;
-    const int j0 = blockIdx.y * kPatchRows, j1 = min(p.Kw, j0 + kPatchRows);
-    for (int j = j0; j < j1; ++j) {
-        const int tap = tap_of_row(j, p);
-        const int cw = j - tap * p.conv_Cw;
-        const bool ok = (vm >> tap) & 1u;
-        const size_t at = (size_t)cw * p.conv_Mp + (size_t)(pin + tap_shift(tap, p.conv_W));
+    const int cw0 = blockIdx.z * kPatchRows, cw1 = min(p.conv_Cw, cw0 + kPatchRows);
+    const uint32_t* src = planes + (ok ? (size_t)(pin + tap_shift(tap, p.conv_W)) : 0);
+    uint32_t* dst = out + (size_t)tap * p.conv_Cw * p.Mp + m;
+    uint32_t w[kPatchRows][BITS];                               // all loads of the slab in flight, then the stores
 #pragma unroll
-        for (int pl = 0; pl < BITS; ++pl) out[pl * out_stride + (size_t)j * p.Mp + m] = ok ? planes[pl * in_stride + at] : 0u;
-    }
-    if (blockIdx.y == 0) {
+    for (int i = 0; i < kPatchRows; ++i)
+#pragma unroll
+        for (int pl = 0; pl < BITS; ++pl)
+            w[i][pl] = ok ? src[pl * in_stride + (size_t)min(cw0 + i, cw1 - 1) * p.conv_Mp] : 0u;
+#pragma unroll
+    for (int i = 0; i < kPatchRows; ++i)
+        if (cw0 + i < cw1) {
+#pragma unroll
+            for (int pl = 0; pl < BITS; ++pl) dst[pl * out_stride + (size_t)(cw0 + i) * p.Mp] = w[i][pl];
+        }
+    if (tap == 0 && blockIdx.z == 0) {
         int cs = 0;
 #pragma unroll
         for (int t = 0; t < 9; ++t)
@@ -913,9 +929,10 @@ int launch_forward(const LayerDev& L, const uint32_t* planes, const int32_t* col
     return launch_any(L, planes, colsum, M, bits, step, conv, OutArgs{nullptr, nullptr, Y}, 0, 0.0f, s);
 }
 
-// conv -> the packed K x M patch matrix in `out` (planes, then column sums: apb_acts_bytes(9 * C, M, bits) bytes)
+// conv -> the packed K x M patch matrix in `out` (planes, then column sums: apb_acts_bytes(9 * C, M, bits) bytes);
+// clears `clear_words` words at `clear` as well (nullptr, 0: nothing)
 int launch_pack_patches(const LayerDev& L, const uint32_t* planes, const int32_t* pixsum, int M, int bits,
-                        const ConvShape& conv, uint32_t* out, hipStream_t s) {
+                        const ConvShape& conv, uint32_t* out, uint32_t* clear, size_t clear_words, hipStream_t s) {
     const int Mp = kWave * ((M + kWave - 1) / kWave);
     SparseParams p{};
     p.Kw = L.Kw;
@@ -930,9 +947,11 @@ int launch_pack_patches(const LayerDev& L, const uint32_t* planes, const int32_t
     p.conv_Mp = conv.Pp_in;
     p.conv_inv_Cw = 1.0f / (float)(conv.C / 32);
     int32_t* out_colsum = reinterpret_cast<int32_t*>(out + (size_t)bits * L.Kw * Mp);
-    const dim3 grid((unsigned)((Mp + 255) / 256), (unsigned)((L.Kw + kPatchRows - 1) / kPatchRows));
-    if (bits == 1) hipLaunchKernelGGL(k_pack_patches<1>, grid, dim3(256), 0, s, planes, pixsum, out, out_colsum, p);
-    else hipLaunchKernelGGL(k_pack_patches<2>, grid, dim3(256), 0, s, planes, pixsum, out, out_colsum, p);
+    const dim3 grid((unsigned)((Mp + 127) / 128), 9u, (unsigned)((p.conv_Cw + kPatchRows - 1) / kPatchRows));
+    if (bits == 1)
+        hipLaunchKernelGGL(k_pack_patches<1>, grid, dim3(128), 0, s, planes, pixsum, out, out_colsum, clear, clear_words, p);
+    else
+        hipLaunchKernelGGL(k_pack_patches<2>, grid, dim3(128), 0, s, planes, pixsum, out, out_colsum, clear, clear_words, p);
     APB_HIP(hipGetLastError());
     return APB_OK;
 }
@@ -969,10 +988,10 @@ const char* forward_kernel_name(const LayerDev& L, int M, int bits) {
 // packed_out: the next layer's packed activation buffer (K = L.N), fully overwritten.
 int launch_forward_requant(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                            const ConvShape* conv, const float* scale, const float* shift, int bits_out,
-                           float inv_step_out, uint32_t* packed_out, hipStream_t s) {
+                           float inv_step_out, uint32_t* packed_out, hipStream_t s, bool out_cleared) {
     if (!conv && forward_rows_requant_applies(L, planes, M, bits))
         return launch_forward_rows_requant(L, planes, colsum, M, bits, step, scale, shift, bits_out, inv_step_out, packed_out,
-                                           s);
+                                           s, out_cleared);
     return launch_any(L, planes, colsum, M, bits, step, conv, OutArgs{scale, shift, reinterpret_cast<float*>(packed_out)},
                       bits_out, inv_step_out, s);
 }
