@@ -360,16 +360,21 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 4))) voi
         }
         __syncthreads();
         uint32_t* words = reinterpret_cast<uint32_t*>(Y);
+        // merged row i / 16 = word row of the packed output (planes one after the other), column i % 16.  One
+        // row group (the workgroup holds every row of its columns): plain stores of every word, zero or not --
+        // nothing to clear beforehand, no atomics.
+        const bool exclusive = p.row_groups == 1;
         for (int i = threadIdx.x; i < nwords; i += blockDim.x) {
             const uint32_t w = merged[i];
-            // merged row i / 16 = word row of the packed output (planes one after the other), column i % 16
-            if (w) __hip_atomic_fetch_or(words + (size_t)(i / T) * p.Mp + m0 + (i % T), w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            uint32_t* at = words + (size_t)(i / T) * p.Mp + m0 + (i % T);
+            if (exclusive) *at = w;
+            else if (w) __hip_atomic_fetch_or(at, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         if (threadIdx.x < T) {
             const uint32_t tot = merged[nwords + threadIdx.x];
-            if (tot)
-                __hip_atomic_fetch_add(words + (size_t)p.out_bits * p.out_Kw * p.Mp + m0 + threadIdx.x, tot, __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
+            uint32_t* at = words + (size_t)p.out_bits * p.out_Kw * p.Mp + m0 + threadIdx.x;
+            if (exclusive) *at = tot;
+            else if (tot) __hip_atomic_fetch_add(at, tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         return;
     }
@@ -503,9 +508,12 @@ int launch_forward_rows_requant(const LayerDev& L, const uint32_t* planes, const
     p.out_bits = bits_out;
     p.out_Kw = (L.N + 31) / 32;
     p.out_inv_step = inv_step_out;
-    // the workgroups OR their bits into the buffer: cleared here (a fill kernel, not a memset node: the call may
-    // be recorded into a graph)
-    if (!out_cleared) {
+    // one row group: nothing clears the buffer, so the column groups cover the padding columns up to Mp as well
+    // (their codes are zero)
+    if (p.row_groups == 1) p.tasks = p.Mp / T;
+    // several row groups: the workgroups OR their bits into the buffer, cleared here (a fill kernel, not a memset
+    // node: the call may be recorded into a graph); one row group stores every word itself
+    if (!out_cleared && p.row_groups > 1) {
         rc = launch_zero_words(packed_out, ((size_t)bits_out * p.out_Kw + 1) * p.Mp, s);
         if (rc != APB_OK) return rc;
     }
