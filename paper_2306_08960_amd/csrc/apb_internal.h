@@ -77,6 +77,15 @@ inline bool bad_shape_acts(int K, int M) {
 __device__ __forceinline__ uint32_t code2(float x, float inv_step) {
     return (uint32_t)(int)fminf(3.0f, fmaxf(0.0f, rintf(x * inv_step)));
 }
+// The same code as the two low bits of the result (the bits above are not zero): clamping first and rounding
+// second gives the same p (rounding is monotone and 0, 3 are integers), and adding 2^23 to a float in [0, 3]
+// IS the rounding to the nearest integer, ties to even, with p left in the low mantissa bits -- four vector
+// instructions instead of five, and no conversion.
+__device__ __forceinline__ uint32_t code2_low_bits(float x, float inv_step) {
+    return __float_as_uint(fminf(3.0f, fmaxf(0.0f, x * inv_step)) + 8388608.0f);
+}
+// Shift a word right by one and put bit 0 of `bits` on top: after 32 calls the first bit sits at position 0.
+__device__ __forceinline__ uint32_t push_bit(uint32_t word, uint32_t bits) { return __builtin_amdgcn_alignbit(bits, word, 1); }
 
 #define APB_HIP(expr)                                 \
     do {                                              \

@@ -93,9 +93,10 @@ __global__ __launch_bounds__(kWave* kMaxWaves) void k_quantize_pack(const float*
                     if (BITS == 1) {
                         w0[q] |= (xs[q] >= 0.0f ? 1u : 0u) << bit;
                     } else {
-                        const uint32_t p = code2(xs[q], inv_step);
-                        w0[q] |= (p & 1u) << bit;
-                        w1[q] |= (p >> 1) << bit;
+                        // (the values of k arrive in order: each pushes its two bits on top of the words)
+                        const uint32_t p = code2_low_bits(xs[q], inv_step);
+                        w0[q] = push_bit(w0[q], p);
+                        w1[q] = push_bit(w1[q], p >> 1);
                     }
                 }
             }

@@ -448,9 +448,9 @@ __device__ __forceinline__ void quantize_strip(const float* __restrict__ X, cons
                 if (BITS == 1) {
                     w0 |= (xv[i] >= 0.0f ? 1u : 0u) << i;
                 } else {
-                    const uint32_t c = code2(xv[i], p.in_inv_step);
-                    w0 |= (c & 1u) << i;
-                    w1 |= (c >> 1) << i;
+                    const uint32_t c = code2_low_bits(xv[i], p.in_inv_step);
+                    w0 = push_bit(w0, c);
+                    w1 = push_bit(w1, c >> 1);
                 }
             }
             const int valid = p.K - k0;
