@@ -791,7 +791,13 @@ def routine_peaks(args):
                  "mfma_i8": (5.0e15, "op/s (2 per multiply-add), dense int8"),
                  "and_bcnt": (VALU_LANE_OPS_PER_S, "32-bit vector lane-ops/s (256 CUs x 64 lanes x 2.4 GHz)"),
                  "fma_f64": (VALU_LANE_OPS_PER_S, "float64 multiply-add lane-ops/s (78.6 TFLOP/s / 2)"),
-                 "lds_u8": (256 * 32 * 2.4e9, "LDS lane-reads/s at 32 banks per compute unit and cycle")}
+                 "lds_u8": (256 * 32 * 2.4e9, "LDS lane-reads/s at 32 banks per compute unit and cycle"),
+                 "lds_b128": (256 * 128 * 2.4e9, "LDS bytes/s read 16 bytes per lane, against 128 bytes per compute unit and cycle"),
+                 "mfma_fp4_lds": (MFMA_FP4_PEAK_TFLOPS * 1e12, "flop/s, one operand of every matrix instruction read from LDS"),
+                 "mfma_fp4_lds_barrier": (MFMA_FP4_PEAK_TFLOPS * 1e12,
+                                          "flop/s, ... plus an LDS write and a workgroup barrier per four matrix instructions"),
+                 "mfma_fp4_lds_barrier_valu": (MFMA_FP4_PEAK_TFLOPS * 1e12,
+                                               "flop/s, ... plus 32 vector instructions per four matrix instructions")}
     rows = []
     for name, kind in b.PROBES.items():
         iters = 2048

@@ -312,7 +312,11 @@ enum {
     APB_PROBE_MFMA_I8 = 1,    /* v_mfma_i32_32x32x32_i8                                               */
     APB_PROBE_AND_BCNT = 2,   /* v_and_b32 + v_bcnt_u32_b32: the popcount formulation's pair           */
     APB_PROBE_FMA_F64 = 3,    /* v_fma_f64: the residual part's multiply-add                          */
-    APB_PROBE_LDS_U8 = 4      /* ds_read_u8 from a 260-byte-pitch table, one column for all lanes      */
+    APB_PROBE_LDS_U8 = 4,     /* ds_read_u8 from a 260-byte-pitch table, one column for all lanes      */
+    APB_PROBE_LDS_B128 = 5,   /* four 16-byte LDS reads per lane and pass (work = bytes)               */
+    APB_PROBE_MFMA_FP4_LDS = 6,               /* ... feeding four FP4 matrix instructions              */
+    APB_PROBE_MFMA_FP4_LDS_BARRIER = 7,       /* ... plus an LDS write and a workgroup barrier per pass */
+    APB_PROBE_MFMA_FP4_LDS_BARRIER_VALU = 8   /* ... plus 32 vector-ALU instructions per pass          */
 };
 size_t apb_probe_out_bytes(void);
 int apb_probe_rate(int kind, int iters, void* out, double* work_per_launch, void* stream);

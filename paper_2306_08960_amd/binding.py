@@ -498,7 +498,8 @@ def apb_gemm_2_2(w2: ApbW2, packed: torch.Tensor, M: int, step_a: float, Y: Opti
 
 # ----------------------------------------------------------------------------- instruction-rate probes
 
-PROBES = {"mfma_fp4": 0, "mfma_i8": 1, "and_bcnt": 2, "fma_f64": 3, "lds_u8": 4}
+PROBES = {"mfma_fp4": 0, "mfma_i8": 1, "and_bcnt": 2, "fma_f64": 3, "lds_u8": 4, "lds_b128": 5, "mfma_fp4_lds": 6,
+          "mfma_fp4_lds_barrier": 7, "mfma_fp4_lds_barrier_valu": 8}
 
 
 def apb_probe_out_bytes() -> int:

@@ -110,6 +110,66 @@ __global__ __launch_bounds__(kThreads) void k_probe_lds_u8(int iters, int seed, 
     out[blockIdx.x * kThreads + threadIdx.x] = s;
 }
 
+
+// The loop skeleton of the matrix-core kernel whose waves share an operand through LDS, piece by piece:
+//   kLds            four 16-byte LDS reads per lane and pass, nothing else (bytes / s)
+//   kLdsMfma        those reads feed four FP4 matrix instructions
+//   kLdsMfmaBarrier ... and every pass ends with a 16-byte LDS write and a workgroup barrier
+//   kLdsMfmaBarrierValu ... with 32 vector-ALU instructions (the operand expansion's mix) in the shadow as well
+enum LdsMode { kLds = 0, kLdsMfma = 1, kLdsMfmaBarrier = 2, kLdsMfmaBarrierValu = 3 };
+
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void k_probe_mfma_lds(int iters, int seed, uint32_t* out) {
+    typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+    __shared__ v4u buf[4][4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int i = threadIdx.x; i < 4 * 4 * 64; i += kThreads)
+        (&buf[0][0][0])[i] = v4u{(uint32_t)(i * 7 + seed) & kNib, (uint32_t)i & kNib, 0u, kNib};
+    __syncthreads();
+    v16f c[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) c[t][r] = 0.0f;
+    v8i a;
+#pragma unroll
+    for (int d = 0; d < 8; ++d) a[d] = d < 4 ? (int)((seed * 0x9e3779b9u + threadIdx.x * 7u + d) & kNib) : 0;
+    uint32_t x[8], acc = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) x[j] = lane * 77u + j + seed;
+    for (int it = 0; it < iters; ++it) {
+        int idx = it & 3;
+        asm volatile("" : "+v"(idx));                           // (keeps the reads inside the loop)
+        v4u b[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) b[u] = buf[idx][u][lane];
+        if (MODE == kLdsMfmaBarrierValu) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) x[j & 7] = ((x[j & 7] >> 1) & kNib) | (x[(j + 1) & 7] & (kNib << 1));
+        }
+        if (MODE >= kLdsMfmaBarrier) buf[(idx + 1) & 3][wave][lane] = v4u{x[0], x[1], x[2], x[3]};
+        if (MODE == kLds) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc ^= b[u][0] ^ b[u][1] ^ b[u][2] ^ b[u][3];
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const v8i fb = {(int)b[u][0], (int)b[u][1], (int)b[u][2], (int)b[u][3], 0, 0, 0, 0};
+                c[u] = mfma_fp4(a, fb, c[u]);
+            }
+        }
+        if (MODE >= kLdsMfmaBarrier) __syncthreads();
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += c[t][r];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc ^= x[j];
+    out[blockIdx.x * kThreads + threadIdx.x] = acc ^ (uint32_t)s;
+}
+
 }  // namespace
 }  // namespace apb
 
@@ -144,6 +204,24 @@ int apb_probe_rate(int kind, int iters, void* out, double* work_per_launch, void
         case APB_PROBE_LDS_U8:
             hipLaunchKernelGGL(k_probe_lds_u8, dim3(kBlocks), dim3(kThreads), 0, s, iters, 9, static_cast<uint32_t*>(out));
             *work_per_launch = lanes * iters * 16.0;
+            break;
+        case APB_PROBE_LDS_B128:
+            hipLaunchKernelGGL(k_probe_mfma_lds<kLds>, dim3(kBlocks), dim3(kThreads), 0, s, iters, 7, static_cast<uint32_t*>(out));
+            *work_per_launch = lanes * iters * 4.0 * 16.0;                       // bytes
+            break;
+        case APB_PROBE_MFMA_FP4_LDS:
+            hipLaunchKernelGGL(k_probe_mfma_lds<kLdsMfma>, dim3(kBlocks), dim3(kThreads), 0, s, iters, 7, static_cast<uint32_t*>(out));
+            *work_per_launch = waves * iters * 4.0 * 2.0 * 32 * 32 * 64;
+            break;
+        case APB_PROBE_MFMA_FP4_LDS_BARRIER:
+            hipLaunchKernelGGL(k_probe_mfma_lds<kLdsMfmaBarrier>, dim3(kBlocks), dim3(kThreads), 0, s, iters, 7,
+                               static_cast<uint32_t*>(out));
+            *work_per_launch = waves * iters * 4.0 * 2.0 * 32 * 32 * 64;
+            break;
+        case APB_PROBE_MFMA_FP4_LDS_BARRIER_VALU:
+            hipLaunchKernelGGL(k_probe_mfma_lds<kLdsMfmaBarrierValu>, dim3(kBlocks), dim3(kThreads), 0, s, iters, 7,
+                               static_cast<uint32_t*>(out));
+            *work_per_launch = waves * iters * 4.0 * 2.0 * 32 * 32 * 64;
             break;
         default:
             return APB_ERR_VALUE;
