@@ -288,3 +288,58 @@ def test_three_chained_convolutions_in_a_captured_graph(b):
         assert torch.equal(Y, y_ref)
     for layer in layers:
         layer.free()
+
+
+def test_chain_on_the_rows_kernel_with_a_workspace_in_a_captured_graph(b):
+    """Layers with many residuals per row: conv + requant through the packed patch matrix in a workspace (stride 2,
+    then stride 1), then a fully-connected chained layer -- all on the rows-in-lanes kernel with its packed-output
+    epilogue (LDS merge + atomics into a buffer cleared by a fill kernel or by the patch-packing launch).  Recorded
+    into a graph and replayed with eager work in between: every replay must reproduce the eager result."""
+    B, H, W = 3, 10, 9
+    Ho, Wo = 5, 5
+    P0, P1 = B * H * W, B * Ho * Wo
+    layers = []
+    for i, (N, C) in enumerate([(256, 64), (320, 256)]):
+        Wt, delta, _, _ = synth.random_case(700 + i, N, 9 * C, 1, 2, rho=0.05)
+        layers.append(b.apb_compress(torch.from_numpy(Wt).cuda(), float(delta)))
+    Wt, delta, _, _ = synth.random_case(702, 512, 320, 1, 2, rho=0.05)
+    fc = b.apb_compress(torch.from_numpy(Wt).cuda(), float(delta))
+    for layer, P in ((layers[0], P1), (layers[1], P1), (fc, P1)):
+        assert b.apb_forward_kernel_name(layer, P, 2).startswith("k_forward_rows")
+    Xmap = torch.from_numpy(np.maximum(np.random.default_rng(10).standard_normal((64, P0)), 0).astype(np.float32)).cuda()
+    f0, f1, f2, f3 = b.alloc_packed(64, P0, 2), b.alloc_packed(256, P1, 2), b.alloc_packed(320, P1, 2), b.alloc_packed(512, P1, 2)
+    ws = b.alloc_packed(9 * 256, P1, 2)                       # (the larger of the two patch matrices)
+    Y = torch.empty((512, P1), dtype=torch.float32, device="cuda")
+
+    def net():
+        b.apb_quantize_acts(Xmap, 2, 0.75, packed=f0)
+        b.apb_forward_conv3x3_requant(layers[0], f0, B, H, W, 2, 0.75, 2, 0.6, fmap_out=f1, stride=2, workspace=ws)
+        b.apb_forward_conv3x3_requant(layers[1], f1, B, Ho, Wo, 2, 0.6, 2, 0.9, fmap_out=f2, workspace=ws)
+        b.apb_forward_requant(fc, f2, P1, 2, 0.9, 2, 1.1, packed_out=f3)
+        b.apb_forward(fc, f2, P1, 2, 0.9, Y=Y)
+
+    net()
+    torch.cuda.synchronize()
+    y_ref, f3_ref = Y.clone(), f3.clone()
+    assert f3_ref.any() and y_ref.abs().max() > 0
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        net()
+    torch.cuda.current_stream().wait_stream(side)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        net()
+    for _ in range(3):
+        Y.zero_()
+        for t in (f1, f2, f3, ws):
+            t.fill_(-1)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(f3, f3_ref) and torch.equal(Y, y_ref)
+        net()
+        torch.cuda.synchronize()
+        assert torch.equal(Y, y_ref)
+    for layer in layers + [fc]:
+        layer.free()
