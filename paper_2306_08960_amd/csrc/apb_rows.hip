@@ -67,6 +67,7 @@ struct RowsParams {
     int nblocks;                                                 // row blocks of 64 slots
     int row_groups;                                              // ceil(nblocks / waves per workgroup)
     int tasks;                                                   // row_groups * column groups
+    int split;                                                   // waves that share one block of 64 rows (1, 2 or 4): the SPLIT of the kernel launched
     int lds_main_bytes;                                          // LDS up to the waves' partial column sums
     // REQ kernels: the output is the packed activation buffer of the next layer (its K = this layer's N)
     int out_bits, out_Kw;                                        // 1 or 2; ceil(N / 32)
@@ -101,7 +102,7 @@ __device__ __forceinline__ void accumulate16(double (&acc)[T], v2i& m, const v2u
 
 // REQ: instead of Y the kernel writes the packed codes of the next layer's quantizer applied to
 // scale[n] * Y + shift[n] (see the epilogue); Y then points to that buffer, zero-filled before the launch.
-template <int BITS, bool REQ>
+template <int BITS, bool REQ, int SPLIT>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 4))) void k_forward_rows(
     const uint32_t* __restrict__ planes, const int32_t* __restrict__ colsum, const int32_t* __restrict__ rowsum,
     const int32_t* __restrict__ rperm, const int32_t* __restrict__ blk, const uint32_t* __restrict__ ek,
@@ -118,7 +119,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 4))) voi
     if ((p.tasks & 7) == 0) task = (blockIdx.x & 7) * (p.tasks >> 3) + (blockIdx.x >> 3);
     const int rg = task % p.row_groups;
     const int cg = task / p.row_groups;
-    const int b = rg * waves + wave;                             // this wave's block of 64 rows
+    // Launches with few tasks (few columns) let p.split waves share a block of 64 rows: each takes a contiguous
+    // part of the block's matrix steps and of its residual steps, and part 0 adds the partial results up in a
+    // fixed order (integers for the binary part, float64 sums in the order of the parts).
+    constexpr int split = SPLIT;                                 // (1: every wave has a block of its own)
+    const int part = wave % split;
+    const int b = rg * (waves / split) + wave / split;           // this wave's block of 64 rows
     const bool active = b < p.nblocks;                           // (the last row group may have idle waves)
     const int m0 = cg * T;
     const int slot = b * kWave + lane;
@@ -193,16 +199,18 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 4))) voi
                     c[t] = mfma_fp4_16(fa, fb, c[t]);
                 }
             };
+            const int steps_per_part = (steps + split - 1) / split;
+            const int s_begin = min(steps, part * steps_per_part), s_end = min(steps, s_begin + steps_per_part);
 #pragma unroll
-            for (int q = 0; q < kRing; ++q) load_words(q, aw[q]);
-            int s0 = 0;
-            for (; s0 + kRing <= steps; s0 += kRing) {
+            for (int q = 0; q < kRing; ++q) load_words(s_begin + q, aw[q]);
+            int s0 = s_begin;
+            for (; s0 + kRing <= s_end; s0 += kRing) {
 #pragma unroll
                 for (int q = 0; q < kRing; ++q) one_step(s0 + q, q);
             }
 #pragma unroll
             for (int q = 0; q < kRing - 1; ++q)
-                if (s0 + q < steps) one_step(s0 + q, q);
+                if (s0 + q < s_end) one_step(s0 + q, q);
         }
         __syncthreads();                                         // every wave is done with the staged operands
         // C layout of a 16 x 16 tile: lane (i, g), register r -> row 4*g + r, column i.  Through LDS, so that
@@ -215,10 +223,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 4))) voi
         __syncthreads();
         const int n = active ? rperm[slot] : -1;
         const int rs = BITS == 1 && n >= 0 ? rowsum[n] : 0;
-        const double a0 = p.alpha * (BITS == 1 ? 0.5 : 1.0);
+        const double a0 = part == 0 ? p.alpha * (BITS == 1 ? 0.5 : 1.0) : 0.0;     // (the other parts start at zero)
+        const int32_t* tiles_of_block = reinterpret_cast<const int32_t*>(lds) + (wave - part) * (kWave * T);
 #pragma unroll
         for (int cc = 0; cc < T; ++cc) {
-            const int P = tile[lane * T + cc];
+            int P = 0;
+            for (int pp = 0; pp < split; ++pp) P += tiles_of_block[pp * (kWave * T) + lane * T + cc];
             int cs = 0;
             if (colsum) {
                 cs = colsum[m0 + cc];                            // m0 + 15 < Mp: Mp is a multiple of 64
@@ -271,12 +281,14 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 4))) voi
         }
     }
     __syncthreads();
-    if (!REQ && !active) return;                                 // (REQ: every wave meets again in the epilogue)
+    if (!REQ && split == 1 && !active) return;                   // (otherwise every wave meets again below)
 
     // ---- residual part: steps e0 .. e1 of this block; entries fetched kAhead steps ahead, the table row of
     // the next step read while the multiply-adds of this one issue.
     if (active) {
-        const int e0 = blk[b], e1 = blk[b + 1];
+        const int steps_of_block = blk[b + 1] - blk[b], steps_per_part = (steps_of_block + split - 1) / split;
+        const int e0 = blk[b] + min(steps_of_block, part * steps_per_part);
+        const int e1 = min(blk[b + 1], e0 + steps_per_part);
         const int n_steps = e1 - e0;
         // Entry loads are buffer loads: descriptor = this block's part of the lists, the step in the scalar
         // offset, the lane in a constant vector offset -- no address arithmetic on the vector ALU.
@@ -324,6 +336,26 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 4))) voi
         }
     }
 
+    // ---- several waves per block: the partial sums of parts 1.. go through LDS (where the table was) to part 0,
+    // which adds them in the order of the parts
+    const bool owner = active && part == 0;
+    if (split > 1) {
+        __syncthreads();                                         // every wave is done with the table
+        double* red = reinterpret_cast<double*>(lds);            // [blocks of the workgroup][split - 1][16][64]
+        const int bw = wave / split;
+        if (part > 0) {
+#pragma unroll
+            for (int cc = 0; cc < T; ++cc) red[((size_t)(bw * (split - 1) + part - 1) * T + cc) * kWave + lane] = acc[cc];
+        }
+        __syncthreads();
+        if (part == 0) {
+            for (int pp = 1; pp < split; ++pp)
+#pragma unroll
+                for (int cc = 0; cc < T; ++cc) acc[cc] += red[((size_t)(bw * (split - 1) + pp - 1) * T + cc) * kWave + lane];
+        }
+        if (!REQ && !owner) return;
+    }
+
     // ---- epilogue.  REQ: z = scale[n] * y + shift[n] (float64, rounded once to float; z = y without scale) is
     // quantized exactly as apb_quantize_acts does and its code bits go into word n / 32 of column m of the next
     // layer's buffer (planes [out_bits][out_Kw][Mp], then the column sums [Mp]).  The rows of a workgroup are
@@ -337,7 +369,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 4))) voi
         __syncthreads();                                         // every wave is done with the table
         for (int i = threadIdx.x; i < nwords + T; i += blockDim.x) merged[i] = 0u;
         __syncthreads();
-        const int n = active ? rperm[slot] : -1;
+        const int n = owner ? rperm[slot] : -1;
         const double vs = BITS == 1 && n >= 0 ? valsumR[slot] : 0.0;
         const double sc = scale && n >= 0 ? (double)scale[n] : 1.0, sh = scale && n >= 0 ? (double)shift[n] : 0.0;
         const uint32_t bit = 1u << (n & 31);
@@ -410,21 +442,23 @@ constexpr size_t kColsumBytes = 8 * T * sizeof(int32_t);      // partial column 
 constexpr int kMaxLdsBytes = kRowsMaxTableBytes + 1024 + (int)kColsumBytes;
 static_assert(kMaxLdsBytes <= 160 * 1024, "LDS of one compute unit");
 
-size_t rows_lds_bytes(const LayerDev& L, int waves) {
+size_t rows_lds_bytes(const LayerDev& L, int waves, int split) {
     // the code table; before it, in the same place, the staged activation operands (16 bytes per step and lane)
     // and the tiles of the binary product
     const size_t table = (size_t)32 * L.Kw * kRowBytes, stage = (size_t)(L.rows_Kw4 / 4) * kWave * 16;
     const size_t tiles = (size_t)waves * kWave * T * 4;
-    return (std::max(table, std::max(stage, tiles)) + 15) & ~(size_t)15;
+    // (and the partial float64 sums of waves that share a block)
+    const size_t partial = (size_t)(waves / split) * (split - 1) * kWave * T * 8;
+    return (std::max(std::max(table, partial), std::max(stage, tiles)) + 15) & ~(size_t)15;
 }
 
 // bytes of LDS the packed-output epilogue needs for a layer of N rows (both planes) -- it reuses the table's place
 size_t rows_merge_bytes(int N) { return ((size_t)2 * ((N + 31) / 32) * T + T) * sizeof(uint32_t); }
 
-template <int BITS, bool REQ>
-int launch_rows(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, const float* scale, const float* shift,
-                float* Y, const RowsParams& p, int waves, hipStream_t s) {
-    size_t lds = rows_lds_bytes(L, waves) + kColsumBytes;
+template <int BITS, bool REQ, int SPLIT>
+int launch_rows_split(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, const float* scale, const float* shift,
+                      float* Y, const RowsParams& p, int waves, hipStream_t s) {
+    size_t lds = rows_lds_bytes(L, waves, SPLIT) + kColsumBytes;
     if (REQ) lds = std::max(lds, rows_merge_bytes(L.N));
     if (lds > (size_t)kMaxLdsBytes) return APB_ERR_SHAPE;
     if (lds > 64 * 1024) {                                      // more LDS than a launch gets without asking
@@ -433,16 +467,27 @@ int launch_rows(const LayerDev& L, const uint32_t* planes, const int32_t* colsum
         APB_HIP(hipGetDevice(&dev));
         if (dev < 0 || dev >= kMaxDevices) return APB_ERR_SHAPE;
         if (asked[dev].load(std::memory_order_acquire) < lds) {
-            APB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_forward_rows<BITS, REQ>),
+            APB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_forward_rows<BITS, REQ, SPLIT>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
             asked[dev].store((size_t)kMaxLdsBytes, std::memory_order_release);
         }
     }
-    hipLaunchKernelGGL((k_forward_rows<BITS, REQ>), dim3((unsigned)p.tasks), dim3(kWave * waves), lds, s, planes, colsum,
+    hipLaunchKernelGGL((k_forward_rows<BITS, REQ, SPLIT>), dim3((unsigned)p.tasks), dim3(kWave * waves), lds, s, planes, colsum,
                        L.rowsum, L.rows_perm, L.rows_blk, L.rows_ek, L.rows_ev, L.rows_sign, L.rows_valsum, scale, shift, Y,
                        p);
     APB_HIP(hipGetLastError());
     return APB_OK;
+}
+
+template <int BITS, bool REQ>
+int launch_rows(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, const float* scale, const float* shift,
+                float* Y, const RowsParams& p, int waves, hipStream_t s) {
+    switch (p.split) {
+        case 1: return launch_rows_split<BITS, REQ, 1>(L, planes, colsum, scale, shift, Y, p, waves, s);
+        case 2: return launch_rows_split<BITS, REQ, 2>(L, planes, colsum, scale, shift, Y, p, waves, s);
+        case 4: return launch_rows_split<BITS, REQ, 4>(L, planes, colsum, scale, shift, Y, p, waves, s);
+        default: return APB_ERR_SHAPE;
+    }
 }
 
 // Fills the launch parameters; APB_ERR_SHAPE where the kernel does not apply.
@@ -460,11 +505,18 @@ int rows_params(const LayerDev& L, const uint32_t* planes, int M, int bits, floa
     p.Mp = Mp;
     p.M = M;
     p.nblocks = L.rows_Nr / kWave;
-    p.row_groups = (p.nblocks + waves - 1) / waves;
-    const long long tasks = (long long)p.row_groups * ((M + T - 1) / T);
+    // Few columns (at most 32 groups of 16: fully connected layers at small batch) and few tasks: let 2 or 4 waves
+    // share a block of rows, until there are 2048 waves or so.  (Measured: 4096 x 4096 x 256 2 % faster, 1024 x 4096
+    // x 64 a third; on shapes with more columns sharing loses, 5-15 %.)
+    const long long col_groups = (M + T - 1) / T;
+    p.split = 1;
+    while (col_groups <= 32 && p.split < waves && (long long)p.nblocks * col_groups * p.split < 2048) p.split *= 2;
+    const int blocks_per_group = waves / p.split;
+    p.row_groups = (p.nblocks + blocks_per_group - 1) / blocks_per_group;
+    const long long tasks = (long long)p.row_groups * col_groups;
     if (tasks > 0x7fffffffLL || (long long)Mp * 8 >= (1LL << 31)) return APB_ERR_SHAPE;
     p.tasks = (int)tasks;
-    p.lds_main_bytes = (int)rows_lds_bytes(L, waves);
+    p.lds_main_bytes = (int)rows_lds_bytes(L, waves, p.split);
     p.out_bits = 0;
     p.out_Kw = 0;
     p.out_inv_step = 0.0f;
