@@ -19,10 +19,6 @@ namespace apb {
 namespace {
 
 constexpr int kMaxWaves = 16;
-#ifndef APB_NOSUM_GROUPS
-#define APB_NOSUM_GROUPS 192
-#endif
-constexpr int kNoSumGroups = APB_NOSUM_GROUPS;
 
 __global__ __launch_bounds__(256) void k_zero_words(uint32_t* __restrict__ p, size_t count) {
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (size_t)gridDim.x * 256) p[i] = 0u;
@@ -167,9 +163,9 @@ int launch_quantize(const float* X, int K, int M, int bits, float inv_step, uint
     const int strips = (Mp + strip - 1) / strip;
     // Few strips: split K into slabs as well, until three quarters of the 256 compute units have a workgroup
     // (and there are 1024 waves) or a slab is down to 4 words.  (Measured: 128 strips -> 2 slabs gains a fifth;
-    // splitting 196 strips further loses to the extra fill launch and the atomics.)  Without column sums
-    // (colsum == nullptr) a split costs neither: then until every compute unit has kNoSumGroups workgroups.
-    const long long min_groups = colsum ? 192 : kNoSumGroups;
+    // splitting 196 strips further loses -- with column sums to the extra fill launch and the atomics, and
+    // without them (colsum == nullptr) 384 or 768 workgroups were still 3 % slower than 196.)
+    const long long min_groups = 192;
     int slabs = 1;
     while (((long long)strips * slabs < min_groups || (long long)strips * kMaxWaves * slabs < 1024) &&
            (Kw + 2 * slabs - 1) / (2 * slabs) >= 4)
