@@ -68,6 +68,8 @@ struct RowsParams {
     int row_groups;                                              // ceil(nblocks / waves per workgroup)
     int tasks;                                                   // row_groups * column groups
     int split;                                                   // waves that share one block of 64 rows (1, 2 or 4): the SPLIT of the kernel launched
+    int tail_tasks, tail_cg0;                                    // k_forward_rows_tailed: tasks of the finer-grained tail, its first column group
+    int exclusive;                                               // REQ: one workgroup holds every row of its columns (plain stores)
     int lds_main_bytes;                                          // LDS up to the waves' partial column sums
     // REQ kernels: the output is the packed activation buffer of the next layer (its K = this layer's N)
     int out_bits, out_Kw;                                        // 1 or 2; ceil(N / 32)
@@ -102,23 +104,20 @@ __device__ __forceinline__ void accumulate16(double (&acc)[T], v2i& m, const v2u
 
 // REQ: instead of Y the kernel writes the packed codes of the next layer's quantizer applied to
 // scale[n] * Y + shift[n] (see the epilogue); Y then points to that buffer, zero-filled before the launch.
+// The work of one workgroup: task `task` of a range of column groups that starts at cg0 and has `row_groups` row
+// groups per column group (waves / SPLIT blocks of 64 rows each).
 template <int BITS, bool REQ, int SPLIT>
-__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 4))) void k_forward_rows(
+__device__ __forceinline__ void rows_task(
     const uint32_t* __restrict__ planes, const int32_t* __restrict__ colsum, const int32_t* __restrict__ rowsum,
     const int32_t* __restrict__ rperm, const int32_t* __restrict__ blk, const uint32_t* __restrict__ ek,
     const double* __restrict__ ev, const uint32_t* __restrict__ signR, const double* __restrict__ valsumR,
-    const float* __restrict__ scale, const float* __restrict__ shift, float* __restrict__ Y, const RowsParams p) {
-    extern __shared__ __align__(16) uint8_t lds[];
+    const float* __restrict__ scale, const float* __restrict__ shift, float* __restrict__ Y, const RowsParams& p,
+    uint8_t* lds, int task, int row_groups, int cg0) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int waves = blockDim.x / kWave;
-
-    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of tasks so that the
-    // row groups of one column group share an L2.
-    int task = blockIdx.x;
-    if ((p.tasks & 7) == 0) task = (blockIdx.x & 7) * (p.tasks >> 3) + (blockIdx.x >> 3);
-    const int rg = task % p.row_groups;
-    const int cg = task / p.row_groups;
+    const int rg = task % row_groups;
+    const int cg = cg0 + task / row_groups;
     // Launches with few tasks (few columns) let p.split waves share a block of 64 rows: each takes a contiguous
     // part of the block's matrix steps and of its residual steps, and part 0 adds the partial results up in a
     // fixed order (integers for the binary part, float64 sums in the order of the parts).
@@ -395,7 +394,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 4))) voi
         // merged row i / 16 = word row of the packed output (planes one after the other), column i % 16.  One
         // row group (the workgroup holds every row of its columns): plain stores of every word, zero or not --
         // nothing to clear beforehand, no atomics.
-        const bool exclusive = p.row_groups == 1;
+        const bool exclusive = p.exclusive != 0;
         for (int i = threadIdx.x; i < nwords; i += blockDim.x) {
             const uint32_t w = merged[i];
             uint32_t* at = words + (size_t)(i / T) * p.Mp + m0 + (i % T);
@@ -432,11 +431,49 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 4))) voi
     }
 }
 
+// Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of tasks so that the row
+// groups of one column group share an L2.
+__device__ __forceinline__ int xcd_contiguous(int block, int tasks) {
+    return (tasks & 7) == 0 ? (block & 7) * (tasks >> 3) + (block >> 3) : block;
+}
+
+template <int BITS, bool REQ, int SPLIT>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 4))) void k_forward_rows(
+    const uint32_t* __restrict__ planes, const int32_t* __restrict__ colsum, const int32_t* __restrict__ rowsum,
+    const int32_t* __restrict__ rperm, const int32_t* __restrict__ blk, const uint32_t* __restrict__ ek,
+    const double* __restrict__ ev, const uint32_t* __restrict__ signR, const double* __restrict__ valsumR,
+    const float* __restrict__ scale, const float* __restrict__ shift, float* __restrict__ Y, const RowsParams p) {
+    extern __shared__ __align__(16) uint8_t lds[];
+    rows_task<BITS, REQ, SPLIT>(planes, colsum, rowsum, rperm, blk, ek, ev, signR, valsumR, scale, shift, Y, p, lds,
+                                xcd_contiguous(blockIdx.x, p.tasks), p.row_groups, 0);
+}
+
+// The same with a finer-grained TAIL.  A launch whose tasks are a little more than a whole number per compute unit
+// ends with a few compute units running one more workgroup, alone and therefore slowly, while the others idle
+// (measured on 512 x 4608: 1536 tasks 92 us, 1568 tasks 103 us).  Here the column groups of that remainder are
+// cut into four times as many tasks -- one block of 64 rows each, shared by the four waves as in the SPLIT = 4
+// kernel -- which come last in the grid and spread over four times as many compute units.
+template <int BITS, bool REQ>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 4))) void k_forward_rows_tailed(
+    const uint32_t* __restrict__ planes, const int32_t* __restrict__ colsum, const int32_t* __restrict__ rowsum,
+    const int32_t* __restrict__ rperm, const int32_t* __restrict__ blk, const uint32_t* __restrict__ ek,
+    const double* __restrict__ ev, const uint32_t* __restrict__ signR, const double* __restrict__ valsumR,
+    const float* __restrict__ scale, const float* __restrict__ shift, float* __restrict__ Y, const RowsParams p) {
+    extern __shared__ __align__(16) uint8_t lds[];
+    if ((int)blockIdx.x < p.tasks)
+        rows_task<BITS, REQ, 1>(planes, colsum, rowsum, rperm, blk, ek, ev, signR, valsumR, scale, shift, Y, p, lds,
+                                xcd_contiguous(blockIdx.x, p.tasks), p.row_groups, 0);
+    else
+        rows_task<BITS, REQ, 4>(planes, colsum, rowsum, rperm, blk, ek, ev, signR, valsumR, scale, shift, Y, p, lds,
+                                (int)blockIdx.x - p.tasks, p.nblocks, p.tail_cg0);
+}
+
 int rows_waves(const LayerDev& L) {
     const int nb = L.rows_Nr / kWave;
     return nb >= 4 ? 4 : (nb >= 2 ? 2 : 1);
 }
 
+constexpr int kComputeUnits = 256;                             // of the MI355X
 constexpr size_t kColsumBytes = 8 * T * sizeof(int32_t);      // partial column sums of up to 8 waves
 // the largest table, the staged operands of a K rounded up to whole steps, the partial sums
 constexpr int kMaxLdsBytes = kRowsMaxTableBytes + 1024 + (int)kColsumBytes;
@@ -480,8 +517,33 @@ int launch_rows_split(const LayerDev& L, const uint32_t* planes, const int32_t* 
 }
 
 template <int BITS, bool REQ>
+int launch_rows_tailed(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, const float* scale,
+                       const float* shift, float* Y, const RowsParams& p, hipStream_t s) {
+    size_t lds = p.lds_main_bytes + kColsumBytes;               // (rows_params sized it for both task shapes)
+    if (REQ) lds = std::max(lds, rows_merge_bytes(L.N));
+    if (lds > (size_t)kMaxLdsBytes) return APB_ERR_SHAPE;
+    if (lds > 64 * 1024) {
+        static std::atomic<size_t> asked[kMaxDevices];
+        int dev = 0;
+        APB_HIP(hipGetDevice(&dev));
+        if (dev < 0 || dev >= kMaxDevices) return APB_ERR_SHAPE;
+        if (asked[dev].load(std::memory_order_acquire) < lds) {
+            APB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_forward_rows_tailed<BITS, REQ>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
+            asked[dev].store((size_t)kMaxLdsBytes, std::memory_order_release);
+        }
+    }
+    hipLaunchKernelGGL((k_forward_rows_tailed<BITS, REQ>), dim3((unsigned)(p.tasks + p.tail_tasks)), dim3(kWave * 4), lds, s,
+                       planes, colsum, L.rowsum, L.rows_perm, L.rows_blk, L.rows_ek, L.rows_ev, L.rows_sign, L.rows_valsum,
+                       scale, shift, Y, p);
+    APB_HIP(hipGetLastError());
+    return APB_OK;
+}
+
+template <int BITS, bool REQ>
 int launch_rows(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, const float* scale, const float* shift,
                 float* Y, const RowsParams& p, int waves, hipStream_t s) {
+    if (p.tail_tasks > 0) return launch_rows_tailed<BITS, REQ>(L, planes, colsum, scale, shift, Y, p, s);
     switch (p.split) {
         case 1: return launch_rows_split<BITS, REQ, 1>(L, planes, colsum, scale, shift, Y, p, waves, s);
         case 2: return launch_rows_split<BITS, REQ, 2>(L, planes, colsum, scale, shift, Y, p, waves, s);
@@ -517,6 +579,21 @@ int rows_params(const LayerDev& L, const uint32_t* planes, int M, int bits, floa
     if (tasks > 0x7fffffffLL || (long long)Mp * 8 >= (1LL << 31)) return APB_ERR_SHAPE;
     p.tasks = (int)tasks;
     p.lds_main_bytes = (int)rows_lds_bytes(L, waves, p.split);
+    p.tail_tasks = 0;
+    p.tail_cg0 = 0;
+    p.exclusive = 0;
+    // A remainder of at most half a task per compute unit after four whole ones or more: the column groups of
+    // the remainder become the finer tail of k_forward_rows_tailed (4-wave workgroups only).
+    if (waves == 4 && p.split == 1 && p.row_groups > 1) {
+        const long long whole = tasks / kComputeUnits, rest = tasks % kComputeUnits;
+        if (whole >= 4 && rest > 0 && rest <= kComputeUnits / 2) {
+            const long long tail_groups = std::min<long long>(col_groups, (rest + p.row_groups - 1) / p.row_groups);
+            p.tail_cg0 = (int)(col_groups - tail_groups);
+            p.tasks = (int)((long long)p.row_groups * p.tail_cg0);
+            p.tail_tasks = (int)(tail_groups * p.nblocks);
+            p.lds_main_bytes = (int)std::max(rows_lds_bytes(L, waves, 1), rows_lds_bytes(L, waves, 4));
+        }
+    }
     p.out_bits = 0;
     p.out_Kw = 0;
     p.out_inv_step = 0.0f;
@@ -562,7 +639,10 @@ int launch_forward_rows_requant(const LayerDev& L, const uint32_t* planes, const
     p.out_inv_step = inv_step_out;
     // one row group: nothing clears the buffer, so the column groups cover the padding columns up to Mp as well
     // (their codes are zero)
-    if (p.row_groups == 1) p.tasks = p.Mp / T;
+    if (p.row_groups == 1) {
+        p.tasks = p.Mp / T;
+        p.exclusive = 1;
+    }
     // several row groups: the workgroups OR their bits into the buffer, cleared here (a fill kernel, not a memset
     // node: the call may be recorded into a graph); one row group stores every word itself
     if (!out_cleared && p.row_groups > 1) {

@@ -69,7 +69,10 @@ def check(b, W, delta, X, bits, step, tag, expect_rows=True):
 
 
 SHAPES = [(256, 128, 16), (257, 100, 1), (300, 97, 15), (320, 1000, 17), (513, 300, 100), (640, 4100, 70),
-          (1000, 257, 1000), (256, 2304, 333)]
+          (1000, 257, 1000), (256, 2304, 333),
+          # a little more than four tasks per compute unit: the remainder's column groups run as the finer tail
+          # (2 and 3 row groups, the last one with idle waves, ragged M)
+          (512, 300, 8310), (600, 200, 5590)]
 
 
 @pytest.mark.parametrize("bits", [1, 2])
