@@ -413,7 +413,7 @@ int apb_forward_requant(const apb_layer* layer, const void* packed, int M, int b
 
 const char* apb_forward_kernel_name(const apb_layer* layer, int M, int bits) {
     if (!layer || M <= 0 || (bits != 1 && bits != 2)) return "";
-    if (forward_rows_applies(layer->d, M, bits)) return bits == 1 ? "k_forward_rows<1>" : "k_forward_rows<2>";
+    if (forward_rows_applies(layer->d, M, bits)) return forward_rows_kernel_name(layer->d, M, bits);
     return forward_kernel_name(layer->d, M, bits);
 }
 

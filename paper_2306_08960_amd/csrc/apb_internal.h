@@ -153,6 +153,7 @@ bool mfma_sum_exact(int K, int max_weight, int max_code);
 // the rows-in-lanes forward kernel (apb_rows.hip): same Y as launch_forward for a plain K x M matrix;
 // forward_rows_applies says whether the layer has row lists and the launch is worth it
 bool forward_rows_applies(const LayerDev& L, int M, int bits);
+const char* forward_rows_kernel_name(const LayerDev& L, int M, int bits);
 // colsum == nullptr: the kernel adds the code sums of its columns up from the packed words
 int launch_forward_rows(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                         float* Y, hipStream_t s);

@@ -610,6 +610,19 @@ bool forward_rows_applies(const LayerDev& L, int M, int bits) {
     return L.rows_steps > 0 && M > 0 && L.rows_Nr >= 4 * kWave;
 }
 
+// The name a profiler shows for the kernel launch_forward_rows launches (float output).
+const char* forward_rows_kernel_name(const LayerDev& L, int M, int bits) {
+    RowsParams p;
+    int waves;
+    if (rows_params(L, reinterpret_cast<const uint32_t*>(uintptr_t{16}), M, bits, 1.0f, p, waves) != APB_OK) return "";
+    if (p.tail_tasks > 0) return bits == 1 ? "k_forward_rows_tailed<1, false>" : "k_forward_rows_tailed<2, false>";
+    switch (p.split) {
+        case 1: return bits == 1 ? "k_forward_rows<1, false, 1>" : "k_forward_rows<2, false, 1>";
+        case 2: return bits == 1 ? "k_forward_rows<1, false, 2>" : "k_forward_rows<2, false, 2>";
+        default: return bits == 1 ? "k_forward_rows<1, false, 4>" : "k_forward_rows<2, false, 4>";
+    }
+}
+
 int launch_forward_rows(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, int M, int bits, float step,
                         float* Y, hipStream_t s) {
     RowsParams p;
