@@ -582,11 +582,12 @@ int rows_params(const LayerDev& L, const uint32_t* planes, int M, int bits, floa
     p.tail_tasks = 0;
     p.tail_cg0 = 0;
     p.exclusive = 0;
-    // A remainder of at most half a task per compute unit after four whole ones or more: the column groups of
-    // the remainder become the finer tail of k_forward_rows_tailed (4-wave workgroups only).
-    if (waves == 4 && p.split == 1 && p.row_groups > 1) {
+    // A remainder of at most half a task per compute unit after one whole one or more: the column groups of the
+    // remainder become the finer tail of k_forward_rows_tailed (4-wave workgroups only).  (Measured on 512 x 4608:
+    // 288 tasks 39 -> 31 us, 544 tasks 51 -> 44 us, 784 tasks 63 -> 54 us, 1568 tasks 110 -> 104 us.)
+    if (waves == 4 && p.split == 1) {
         const long long whole = tasks / kComputeUnits, rest = tasks % kComputeUnits;
-        if (whole >= 4 && rest > 0 && rest <= kComputeUnits / 2) {
+        if (whole >= 1 && rest > 0 && rest <= kComputeUnits / 2) {
             const long long tail_groups = std::min<long long>(col_groups, (rest + p.row_groups - 1) / p.row_groups);
             p.tail_cg0 = (int)(col_groups - tail_groups);
             p.tasks = (int)((long long)p.row_groups * p.tail_cg0);
@@ -654,6 +655,7 @@ int launch_forward_rows_requant(const LayerDev& L, const uint32_t* planes, const
     // (their codes are zero)
     if (p.row_groups == 1) {
         p.tasks = p.Mp / T;
+        p.tail_tasks = 0;                                       // (the tail's tasks would share columns: no plain stores)
         p.exclusive = 1;
     }
     // several row groups: the workgroups OR their bits into the buffer, cleared here (a fill kernel, not a memset

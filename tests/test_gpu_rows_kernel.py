@@ -72,7 +72,10 @@ SHAPES = [(256, 128, 16), (257, 100, 1), (300, 97, 15), (320, 1000, 17), (513, 3
           (1000, 257, 1000), (256, 2304, 333),
           # a little more than four tasks per compute unit: the remainder's column groups run as the finer tail
           # (2 and 3 row groups, the last one with idle waves, ragged M)
-          (512, 300, 8310), (600, 200, 5590)]
+          (512, 300, 8310), (600, 200, 5590),
+          # the same with one task per compute unit and a few more: one row group (whose packed-output form stores
+          # plainly and takes no tail) and two
+          (256, 128, 4340), (300, 97, 2200)]
 
 
 @pytest.mark.parametrize("bits", [1, 2])
