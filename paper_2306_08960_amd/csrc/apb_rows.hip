@@ -142,17 +142,30 @@ __device__ __forceinline__ void rows_task(
         const size_t plane_stride = (size_t)p.Kw * p.Mp;
         v4u* stage = reinterpret_cast<v4u*>(lds);
         int my_cs = 0;
-        for (int it = threadIdx.x; it < steps * kWave; it += blockDim.x) {
-            const int l = it & (kWave - 1), s = it >> 6;
-            // word rows past Kw: the sign words there are zero padding; the activation load re-reads the last
-            // row and is multiplied by those zeros
-            const int row = 4 * s + (l >> 4);
-            const uint32_t* brow = planes + (size_t)min(row, p.Kw - 1) * p.Mp + m0 + (l & 15);
-            const uint32_t w0 = brow[0], w1 = BITS == 2 ? brow[plane_stride] : 0u;
-            if (row < p.Kw) my_cs += __builtin_popcount(w0) + 2 * __builtin_popcount(w1);
-            v8i fb;
-            expand_words<BITS>(w0, w1, fb);
-            stage[it] = v4u{(uint32_t)fb[0], (uint32_t)fb[1], (uint32_t)fb[2], (uint32_t)fb[3]};
+        // kBatch items per thread at a time: all their loads leave together (one round trip per batch, not per item)
+        constexpr int kBatch = 8;
+        const int items = steps * kWave;
+        for (int it0 = threadIdx.x; it0 < items; it0 += kBatch * blockDim.x) {
+            uint32_t w0[kBatch], w1[kBatch];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const int it = min(it0 + u * (int)blockDim.x, items - 1);        // (past the end: re-read, unused)
+                const int l = it & (kWave - 1), s = it >> 6;
+                const uint32_t* brow = planes + (size_t)min(4 * s + (l >> 4), p.Kw - 1) * p.Mp + m0 + (l & 15);
+                w0[u] = brow[0];
+                w1[u] = BITS == 2 ? brow[plane_stride] : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const int it = it0 + u * (int)blockDim.x;
+                if (it < items) {
+                    const int row = 4 * (it >> 6) + ((it & (kWave - 1)) >> 4);
+                    if (row < p.Kw) my_cs += __builtin_popcount(w0[u]) + 2 * __builtin_popcount(w1[u]);
+                    v8i fb;
+                    expand_words<BITS>(w0[u], w1[u], fb);
+                    stage[it] = v4u{(uint32_t)fb[0], (uint32_t)fb[1], (uint32_t)fb[2], (uint32_t)fb[3]};
+                }
+            }
         }
         if (colsum == nullptr) {
             my_cs += __shfl_xor(my_cs, 16);
