@@ -580,12 +580,17 @@ int rows_params(const LayerDev& L, const uint32_t* planes, int M, int bits, floa
     p.Mp = Mp;
     p.M = M;
     p.nblocks = L.rows_Nr / kWave;
-    // Few columns (at most 32 groups of 16: fully connected layers at small batch) and few tasks: let 2 or 4 waves
-    // share a block of rows, until there are 2048 waves or so.  (Measured: 4096 x 4096 x 256 2 % faster, 1024 x 4096
-    // x 64 a third; on shapes with more columns sharing loses, 5-15 %.)
+    // Few columns (at most 32 groups of 16: fully connected layers at small batch) and fewer workgroups than
+    // compute units: let 2 or 4 waves share a block of rows until every compute unit has one.  Long rows
+    // (K >= 4096) in at most 16 column groups pay for one doubling more, to two workgroups per unit.  (Measured: 1024 x 4096 x 64 a third
+    // faster than unshared; 4096 x 4096 x 128 25 -> 21 us and 2048 x 4096 x 256 22 -> 19 us against sharing up to
+    // two workgroups per unit; from one to two per unit: K = 4096 2-8 % faster, K = 9216 7 %, K = 2048 5 % slower,
+    // K = 1024 15 %, 25 column groups 6 % slower.  On shapes with more columns sharing loses, 5-15 %.)
     const long long col_groups = (M + T - 1) / T;
+    const long long blocks_total = (long long)p.nblocks * col_groups;
     p.split = 1;
-    while (col_groups <= 32 && p.split < waves && (long long)p.nblocks * col_groups * p.split < 2048) p.split *= 2;
+    while (col_groups <= 32 && p.split < waves && blocks_total * p.split < 4 * kComputeUnits) p.split *= 2;
+    if (col_groups <= 16 && p.split == 1 && waves >= 2 && L.K >= 4096 && blocks_total < 8 * kComputeUnits) p.split = 2;
     const int blocks_per_group = waves / p.split;
     p.row_groups = (p.nblocks + blocks_per_group - 1) / blocks_per_group;
     const long long tasks = (long long)p.row_groups * col_groups;

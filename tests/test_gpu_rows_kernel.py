@@ -75,7 +75,10 @@ SHAPES = [(256, 128, 16), (257, 100, 1), (300, 97, 15), (320, 1000, 17), (513, 3
           (512, 300, 8310), (600, 200, 5590),
           # the same with one task per compute unit and a few more: one row group (whose packed-output form stores
           # plainly and takes no tail) and two
-          (256, 128, 4340), (300, 97, 2200)]
+          (256, 128, 4340), (300, 97, 2200),
+          # few column groups: one workgroup per compute unit already (no sharing), two waves per block of rows to
+          # get there, and the doubling more that long rows take
+          (4100, 500, 250), (4100, 300, 120), (4100, 4100, 250)]
 
 
 @pytest.mark.parametrize("bits", [1, 2])
