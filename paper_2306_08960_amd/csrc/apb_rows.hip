@@ -582,15 +582,21 @@ int rows_params(const LayerDev& L, const uint32_t* planes, int M, int bits, floa
     p.nblocks = L.rows_Nr / kWave;
     // Few columns (at most 32 groups of 16: fully connected layers at small batch) and fewer workgroups than
     // compute units: let 2 or 4 waves share a block of rows until every compute unit has one.  Long rows
-    // (K >= 4096) in at most 16 column groups pay for one doubling more, to two workgroups per unit.  (Measured: 1024 x 4096 x 64 a third
-    // faster than unshared; 4096 x 4096 x 128 25 -> 21 us and 2048 x 4096 x 256 22 -> 19 us against sharing up to
-    // two workgroups per unit; from one to two per unit: K = 4096 2-8 % faster, K = 9216 7 %, K = 2048 5 % slower,
-    // K = 1024 15 %, 25 column groups 6 % slower.  On shapes with more columns sharing loses, 5-15 %.)
+    // (K >= 4096) in at most 16 column groups pay for one doubling more -- in 8-wave workgroups, one per unit with
+    // one table for four blocks, where that fills the units evenly; else two 4-wave ones per unit.
+    // (Measured, same box each: 1024 x 4096 x 64 a third faster than unshared; 4096 x 4096 x 128 25 -> 21 us and
+    // 2048 x 4096 x 256 22 -> 19 us against sharing up to two workgroups per unit; the doubling more: K = 4096
+    // 2-8 % faster, K = 9216 7 %, K = 2048 5 % slower, K = 1024 15 %, 25 column groups 6 % slower; 8 waves:
+    // 4096 x 4096 x 256 27.8 -> 26.4 us, 4096 x 9216 x 256 51 -> 45, but 6144 x 4096 x 256 -- one and a half
+    // workgroups per unit -- 35 -> 38.  On shapes with more columns sharing loses, 5-15 %.)
     const long long col_groups = (M + T - 1) / T;
     const long long blocks_total = (long long)p.nblocks * col_groups;
     p.split = 1;
     while (col_groups <= 32 && p.split < waves && blocks_total * p.split < 4 * kComputeUnits) p.split *= 2;
-    if (col_groups <= 16 && p.split == 1 && waves >= 2 && L.K >= 4096 && blocks_total < 8 * kComputeUnits) p.split = 2;
+    if (col_groups <= 16 && p.split == 1 && waves == 4 && L.K >= 4096 && blocks_total < 8 * kComputeUnits) {
+        p.split = 2;
+        if (p.nblocks % 4 == 0 && (blocks_total / 4) % kComputeUnits == 0) waves = 8;
+    }
     const int blocks_per_group = waves / p.split;
     p.row_groups = (p.nblocks + blocks_per_group - 1) / blocks_per_group;
     const long long tasks = (long long)p.row_groups * col_groups;
