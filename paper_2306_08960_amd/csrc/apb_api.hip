@@ -19,7 +19,8 @@ hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 void free_layer_buffers(LayerDev& d) {
     void* ptrs[] = {d.sign, d.signT, d.perm, d.row_ptr, d.col_idx, d.val, d.rowsum, d.chunk_ptr, d.slot_valsum, d.vald, d.signC,
-                    d.seg_ptr, d.ent, d.rows_perm, d.rows_blk, d.rows_ek, d.rows_ev, d.rows_sign, d.rows_valsum};
+                    d.seg_ptr, d.ent, d.rows_perm, d.rows_blk, d.rows_ek, d.rows_ev, d.rows_sign, d.rows_valsum,
+                    d.rowsw_perm, d.rowsw_blk, d.rowsw_ek, d.rowsw_ev, d.rowsw_sign, d.rowsw_valsum};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     d = LayerDev{};
@@ -114,19 +115,23 @@ void build_tile_runs(const std::vector<int32_t>& perm, const std::vector<int32_t
 // longest row, shorter rows are padded with (offset 0, value 0).
 void build_row_lists(const std::vector<int32_t>& row_ptr, const std::vector<int32_t>& col, const std::vector<float>& val,
                      std::vector<int32_t>& perm, std::vector<int32_t>& blk, std::vector<uint32_t>& ek,
-                     std::vector<double>& ev, std::vector<double>& valsum) {
+                     std::vector<double>& ev, std::vector<double>& valsum, int group_rows) {
+    // group_rows: rows are sorted by length inside groups of that many consecutive rows (a multiple of 64; every
+    // group but the last fills whole blocks), or over the whole layer (0)
     const int N = (int)row_ptr.size() - 1;
     const int nb = (N + kWave - 1) / kWave, Nr = nb * kWave;
-    std::vector<int32_t> order(N);
-    std::iota(order.begin(), order.end(), 0);
-    std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
-        return row_ptr[a + 1] - row_ptr[a] > row_ptr[b + 1] - row_ptr[b];
-    });
+    const int G = group_rows > 0 ? group_rows : std::max(N, 1);
     perm.assign(Nr, -1);
-    std::copy(order.begin(), order.end(), perm.begin());
+    for (int g0 = 0; g0 < N; g0 += G) {
+        const int g1 = std::min(N, g0 + G);
+        std::iota(perm.begin() + g0, perm.begin() + g1, g0);
+        std::stable_sort(perm.begin() + g0, perm.begin() + g1, [&](int a, int b) {
+            return row_ptr[a + 1] - row_ptr[a] > row_ptr[b + 1] - row_ptr[b];
+        });
+    }
     blk.assign(nb + 1, 0);
     for (int b = 0; b < nb; ++b) {
-        const int n0 = perm[(size_t)b * kWave];                    // longest row of the block
+        const int n0 = perm[(size_t)b * kWave];                    // longest row of the block (its first slot is a row)
         blk[b + 1] = blk[b] + (row_ptr[n0 + 1] - row_ptr[n0]);
     }
     ek.assign((size_t)blk[nb] * kWave, 0u);
@@ -251,7 +256,7 @@ int compress_impl(const float* W, int N, int K, float delta, float alpha, hipStr
     std::vector<uint32_t> rek;
     std::vector<double> rev, rvalsum;
     if ((long long)32 * d.Kw * kRowsRowBytes <= kRowsMaxTableBytes && nnz >= (long long)4 * N) {
-        build_row_lists(hrow_ptr, hcol, hval, rperm, rblk, rek, rev, rvalsum);
+        build_row_lists(hrow_ptr, hcol, hval, rperm, rblk, rek, rev, rvalsum, 0);
         const long long steps = rblk.back();
         if (steps * kWave <= 2 * nnz) {                   // at most half of the list entries are padding
             d.rows_Nr = (int)rperm.size();
@@ -270,6 +275,28 @@ int compress_impl(const float* W, int N, int K, float delta, float alpha, hipStr
             APB_HIP(hipMemcpyAsync(d.rows_valsum, rvalsum.data(), rvalsum.size() * sizeof(double), hipMemcpyHostToDevice, s));
             if ((rc = launch_slot_major_signs(d.sign, d.rows_perm, d.rows_Nr, d.Kw, d.rows_Kw4, d.rows_sign, s)) != APB_OK)
                 return rc;
+            // the word-aligned lists beside them (more than one group of rows; the same padding rule)
+            if (N > kRowsGroupRows) {
+                APB_HIP(hipStreamSynchronize(s));              // the staging vectors above are reused
+                build_row_lists(hrow_ptr, hcol, hval, rperm, rblk, rek, rev, rvalsum, kRowsGroupRows);
+                const long long wsteps = rblk.back();
+                if (wsteps * kWave <= 2 * nnz) {
+                    d.rowsw_steps = wsteps;
+                    if ((rc = dev_alloc(&d.rowsw_perm, rperm.size())) != APB_OK) return rc;
+                    if ((rc = dev_alloc(&d.rowsw_blk, rblk.size())) != APB_OK) return rc;
+                    if ((rc = dev_alloc(&d.rowsw_ek, rek.size())) != APB_OK) return rc;
+                    if ((rc = dev_alloc(&d.rowsw_ev, rev.size())) != APB_OK) return rc;
+                    if ((rc = dev_alloc(&d.rowsw_valsum, rvalsum.size())) != APB_OK) return rc;
+                    if ((rc = dev_alloc(&d.rowsw_sign, (size_t)d.rows_Kw4 * d.rows_Nr)) != APB_OK) return rc;
+                    APB_HIP(hipMemcpyAsync(d.rowsw_perm, rperm.data(), rperm.size() * sizeof(int32_t), hipMemcpyHostToDevice, s));
+                    APB_HIP(hipMemcpyAsync(d.rowsw_blk, rblk.data(), rblk.size() * sizeof(int32_t), hipMemcpyHostToDevice, s));
+                    APB_HIP(hipMemcpyAsync(d.rowsw_ek, rek.data(), rek.size() * sizeof(uint32_t), hipMemcpyHostToDevice, s));
+                    APB_HIP(hipMemcpyAsync(d.rowsw_ev, rev.data(), rev.size() * sizeof(double), hipMemcpyHostToDevice, s));
+                    APB_HIP(hipMemcpyAsync(d.rowsw_valsum, rvalsum.data(), rvalsum.size() * sizeof(double), hipMemcpyHostToDevice, s));
+                    if ((rc = launch_slot_major_signs(d.sign, d.rowsw_perm, d.rows_Nr, d.Kw, d.rows_Kw4, d.rowsw_sign, s)) != APB_OK)
+                        return rc;
+                }
+            }
         }
     }
     APB_HIP(hipStreamSynchronize(s));                 // host staging vectors go out of scope after this

@@ -56,9 +56,21 @@ struct LayerDev {
     double* rows_ev = nullptr;     // [steps][64] residual * 2^kEntValScaleLog2
     uint32_t* rows_sign = nullptr; // [Kw4][Nr]   sign words, slot-major in this order (pad rows and slots zero)
     double* rows_valsum = nullptr; // [Nr]        sum of the residuals of the slot's row (float64, CSR order)
+    // The same lists with the rows sorted by residual count only inside groups of kRowsGroupRows consecutive rows
+    // (whole 32-row words of a packed output): a workgroup of the packed-output epilogue that takes one such group
+    // owns its output words -- plain stores, nothing to clear, no atomics.  Built for layers of more than one
+    // group (otherwise the lists above already are of this kind); rowsw_steps == 0 when not built.
+    long long rowsw_steps = 0;
+    int32_t* rowsw_perm = nullptr;
+    int32_t* rowsw_blk = nullptr;
+    uint32_t* rowsw_ek = nullptr;
+    double* rowsw_ev = nullptr;
+    uint32_t* rowsw_sign = nullptr;
+    double* rowsw_valsum = nullptr;
 };
 
 constexpr int kRowsCols = 16;            // output columns one workgroup of the rows-in-lanes kernel covers
+constexpr int kRowsGroupRows = 256;      // rows of one group of the word-aligned lists: 4 blocks of 64, 8 output words
 constexpr int kRowsRowBytes = 8;         // bytes of its code table per value of k (4 bits per column)
 constexpr int kRowsMaxTableBytes = 144 * 1024;   // the whole table (all of K) has to fit on chip
 

@@ -70,6 +70,7 @@ struct RowsParams {
     int split;                                                   // waves that share one block of 64 rows (1, 2 or 4): the SPLIT of the kernel launched
     int tail_tasks, tail_cg0;                                    // k_forward_rows_tailed: tasks of the finer-grained tail, its first column group
     int exclusive;                                               // REQ: one workgroup holds every row of its columns (plain stores)
+    int aligned_lists;                                           // host side: launch with the word-aligned lists
     int lds_main_bytes;                                          // LDS up to the waves' partial column sums
     // REQ kernels: the output is the packed activation buffer of the next layer (its K = this layer's N)
     int out_bits, out_Kw;                                        // 1 or 2; ceil(N / 32)
@@ -112,7 +113,7 @@ __device__ __forceinline__ void rows_task(
     const int32_t* __restrict__ rperm, const int32_t* __restrict__ blk, const uint32_t* __restrict__ ek,
     const double* __restrict__ ev, const uint32_t* __restrict__ signR, const double* __restrict__ valsumR,
     const float* __restrict__ scale, const float* __restrict__ shift, float* __restrict__ Y, const RowsParams& p,
-    uint8_t* lds, int task, int row_groups, int cg0) {
+    uint8_t* lds, int task, int row_groups, int cg0, int exclusive) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int waves = blockDim.x / kWave;
@@ -376,8 +377,13 @@ __device__ __forceinline__ void rows_task(
     // non-zero word and one atomic add per column; integer OR and add commute, so the order between
     // workgroups does not matter.
     if (REQ) {
-        uint32_t* merged = reinterpret_cast<uint32_t*>(lds);
-        const int nwords = p.out_bits * p.out_Kw * T;
+        // exclusive 0: every word of the columns may hold rows of this workgroup and of others; 1: one row group,
+        // the workgroup holds all rows; 2: word-aligned lists, the rows of row group rg are those of
+        // kRowsGroupRows / 32 words
+        const int w_lo = exclusive == 2 ? rg * (kRowsGroupRows / 32) : 0;
+        const int nW = exclusive == 2 ? min(p.out_Kw - w_lo, kRowsGroupRows / 32) : p.out_Kw;
+        uint32_t* merged = reinterpret_cast<uint32_t*>(lds);     // [out_bits][nW][16] words, then 16 column sums
+        const int nwords = p.out_bits * nW * T;
         __syncthreads();                                         // every wave is done with the table
         for (int i = threadIdx.x; i < nwords + T; i += blockDim.x) merged[i] = 0u;
         __syncthreads();
@@ -385,8 +391,8 @@ __device__ __forceinline__ void rows_task(
         const double vs = BITS == 1 && n >= 0 ? valsumR[slot] : 0.0;
         const double sc = scale && n >= 0 ? (double)scale[n] : 1.0, sh = scale && n >= 0 ? (double)shift[n] : 0.0;
         const uint32_t bit = 1u << (n & 31);
-        uint32_t* w0_at = merged + (size_t)(max(n, 0) >> 5) * T;
-        uint32_t* w1_at = w0_at + (size_t)p.out_Kw * T;
+        uint32_t* w0_at = merged + (size_t)max((n >> 5) - w_lo, 0) * T;
+        uint32_t* w1_at = w0_at + (size_t)nW * T;
 #pragma unroll
         for (int cc = 0; cc < T; ++cc) {
             const double sum = acc[cc] * col_unscale(cc);
@@ -404,20 +410,21 @@ __device__ __forceinline__ void rows_task(
         }
         __syncthreads();
         uint32_t* words = reinterpret_cast<uint32_t*>(Y);
-        // merged row i / 16 = word row of the packed output (planes one after the other), column i % 16.  One
-        // row group (the workgroup holds every row of its columns): plain stores of every word, zero or not --
-        // nothing to clear beforehand, no atomics.
-        const bool exclusive = p.exclusive != 0;
+        // merged word i: plane i / (nW * 16), word row w_lo + (i / 16) % nW, column i % 16.  Where the workgroup
+        // owns its words (exclusive 1 and 2) it stores every one of them plainly, zero or not: nothing to clear
+        // beforehand, no atomics.
         for (int i = threadIdx.x; i < nwords; i += blockDim.x) {
             const uint32_t w = merged[i];
-            uint32_t* at = words + (size_t)(i / T) * p.Mp + m0 + (i % T);
-            if (exclusive) *at = w;
+            const int plane = i / (nW * T), r = i - plane * (nW * T);
+            uint32_t* at = words + ((size_t)plane * p.out_Kw + w_lo + r / T) * p.Mp + m0 + (r % T);
+            if (exclusive != 0) *at = w;
             else if (w) __hip_atomic_fetch_or(at, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
+        // column sums: stored by the one row group, added up over several (cleared before the launch)
         if (threadIdx.x < T) {
             const uint32_t tot = merged[nwords + threadIdx.x];
             uint32_t* at = words + (size_t)p.out_bits * p.out_Kw * p.Mp + m0 + threadIdx.x;
-            if (exclusive) *at = tot;
+            if (exclusive == 1) *at = tot;
             else if (tot) __hip_atomic_fetch_add(at, tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         return;
@@ -458,7 +465,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 4))) voi
     const float* __restrict__ scale, const float* __restrict__ shift, float* __restrict__ Y, const RowsParams p) {
     extern __shared__ __align__(16) uint8_t lds[];
     rows_task<BITS, REQ, SPLIT>(planes, colsum, rowsum, rperm, blk, ek, ev, signR, valsumR, scale, shift, Y, p, lds,
-                                xcd_contiguous(blockIdx.x, p.tasks), p.row_groups, 0);
+                                xcd_contiguous(blockIdx.x, p.tasks), p.row_groups, 0, p.exclusive);
 }
 
 // The same with a finer-grained TAIL.  A launch whose tasks are a little more than a whole number per compute unit
@@ -475,10 +482,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 4))) voi
     extern __shared__ __align__(16) uint8_t lds[];
     if ((int)blockIdx.x < p.tasks)
         rows_task<BITS, REQ, 1>(planes, colsum, rowsum, rperm, blk, ek, ev, signR, valsumR, scale, shift, Y, p, lds,
-                                xcd_contiguous(blockIdx.x, p.tasks), p.row_groups, 0);
-    else
+                                xcd_contiguous(blockIdx.x, p.tasks), p.row_groups, 0, p.exclusive);
+    else                                                         // (a tail task holds one block of rows: it shares its words)
         rows_task<BITS, REQ, 4>(planes, colsum, rowsum, rperm, blk, ek, ev, signR, valsumR, scale, shift, Y, p, lds,
-                                (int)blockIdx.x - p.tasks, p.nblocks, p.tail_cg0);
+                                (int)blockIdx.x - p.tasks, p.nblocks, p.tail_cg0, 0);
+}
+
+// Clears columns c0 .. Mp of `rows` rows of Mp words and all of the row after them (the column sums).
+__global__ __launch_bounds__(256) void k_zero_columns(uint32_t* __restrict__ words, size_t rows, int Mp, int c0) {
+    for (size_t r = blockIdx.x; r <= rows; r += gridDim.x)
+        for (int c = (r < rows ? c0 : 0) + (int)threadIdx.x; c < Mp; c += 256) words[r * Mp + c] = 0u;
 }
 
 int rows_waves(const LayerDev& L) {
@@ -522,9 +535,11 @@ int launch_rows_split(const LayerDev& L, const uint32_t* planes, const int32_t* 
             asked[dev].store((size_t)kMaxLdsBytes, std::memory_order_release);
         }
     }
+    const bool w = p.aligned_lists != 0;
     hipLaunchKernelGGL((k_forward_rows<BITS, REQ, SPLIT>), dim3((unsigned)p.tasks), dim3(kWave * waves), lds, s, planes, colsum,
-                       L.rowsum, L.rows_perm, L.rows_blk, L.rows_ek, L.rows_ev, L.rows_sign, L.rows_valsum, scale, shift, Y,
-                       p);
+                       L.rowsum, w ? L.rowsw_perm : L.rows_perm, w ? L.rowsw_blk : L.rows_blk, w ? L.rowsw_ek : L.rows_ek,
+                       w ? L.rowsw_ev : L.rows_ev, w ? L.rowsw_sign : L.rows_sign, w ? L.rowsw_valsum : L.rows_valsum, scale,
+                       shift, Y, p);
     APB_HIP(hipGetLastError());
     return APB_OK;
 }
@@ -546,9 +561,11 @@ int launch_rows_tailed(const LayerDev& L, const uint32_t* planes, const int32_t*
             asked[dev].store((size_t)kMaxLdsBytes, std::memory_order_release);
         }
     }
+    const bool w = p.aligned_lists != 0;
     hipLaunchKernelGGL((k_forward_rows_tailed<BITS, REQ>), dim3((unsigned)(p.tasks + p.tail_tasks)), dim3(kWave * 4), lds, s,
-                       planes, colsum, L.rowsum, L.rows_perm, L.rows_blk, L.rows_ek, L.rows_ev, L.rows_sign, L.rows_valsum,
-                       scale, shift, Y, p);
+                       planes, colsum, L.rowsum, w ? L.rowsw_perm : L.rows_perm, w ? L.rowsw_blk : L.rows_blk,
+                       w ? L.rowsw_ek : L.rows_ek, w ? L.rowsw_ev : L.rows_ev, w ? L.rowsw_sign : L.rows_sign,
+                       w ? L.rowsw_valsum : L.rows_valsum, scale, shift, Y, p);
     APB_HIP(hipGetLastError());
     return APB_OK;
 }
@@ -606,6 +623,7 @@ int rows_params(const LayerDev& L, const uint32_t* planes, int M, int bits, floa
     p.tail_tasks = 0;
     p.tail_cg0 = 0;
     p.exclusive = 0;
+    p.aligned_lists = 0;
     // A remainder of at most half a task per compute unit after one whole one or more: the column groups of the
     // remainder become the finer tail of k_forward_rows_tailed (4-wave workgroups only).  (Measured on 512 x 4608:
     // 288 tasks 39 -> 31 us, 544 tasks 51 -> 44 us, 784 tasks 63 -> 54 us, 1568 tasks 110 -> 104 us.)
@@ -675,17 +693,32 @@ int launch_forward_rows_requant(const LayerDev& L, const uint32_t* planes, const
     p.out_bits = bits_out;
     p.out_Kw = (L.N + 31) / 32;
     p.out_inv_step = inv_step_out;
-    // one row group: nothing clears the buffer, so the column groups cover the padding columns up to Mp as well
-    // (their codes are zero)
+    // One row group, or row groups that are whole words of the output (the word-aligned lists, four blocks of rows
+    // to a workgroup): the workgroups own their words and store them plainly, nothing clears those beforehand.
+    const bool aligned = p.row_groups > 1 && L.rowsw_steps > 0 && waves / p.split == kRowsGroupRows / kWave;
+    const size_t plane_rows = (size_t)bits_out * p.out_Kw;
     if (p.row_groups == 1) {
+        // (the column groups cover the padding columns up to Mp as well -- their codes are zero -- and there is no
+        // finer tail: its tasks would share words)
         p.tasks = p.Mp / T;
-        p.tail_tasks = 0;                                       // (the tail's tasks would share columns: no plain stores)
+        p.tail_tasks = 0;
+        p.lds_main_bytes = (int)rows_lds_bytes(L, waves, p.split);
         p.exclusive = 1;
-    }
-    // several row groups: the workgroups OR their bits into the buffer, cleared here (a fill kernel, not a memset
-    // node: the call may be recorded into a graph); one row group stores every word itself
-    if (!out_cleared && p.row_groups > 1) {
-        rc = launch_zero_words(packed_out, ((size_t)bits_out * p.out_Kw + 1) * p.Mp, s);
+    } else if (aligned) {
+        p.exclusive = 2;
+        p.aligned_lists = 1;
+        // The column groups of a finer tail, whose tasks hold one block of rows each, still OR their bits into the
+        // buffer: those columns -- and the padding columns behind them -- are cleared, and so are the column sums,
+        // which the row groups add up (a fill kernel, not a memset node: the call may be recorded into a graph).
+        const int c0 = p.tail_tasks > 0 ? p.tail_cg0 * T : (int)(((long long)M + T - 1) / T) * T;
+        if (!out_cleared) {
+            hipLaunchKernelGGL(k_zero_columns, dim3((unsigned)std::min<size_t>(plane_rows + 1, 65535)), dim3(256), 0, s,
+                               packed_out, plane_rows, p.Mp, c0);
+            APB_HIP(hipGetLastError());
+        }
+    } else if (!out_cleared) {
+        // several row groups OR their bits into the buffer and add their column sums up in it
+        rc = launch_zero_words(packed_out, (plane_rows + 1) * p.Mp, s);
         if (rc != APB_OK) return rc;
     }
     float* out = reinterpret_cast<float*>(packed_out);
