@@ -376,6 +376,63 @@ __device__ __forceinline__ void rows_task(
     // was: [out_bits][out_Kw][16] words and 16 partial column sums -- and then leave as one atomic OR per
     // non-zero word and one atomic add per column; integer OR and add commute, so the order between
     // workgroups does not matter.
+    if (REQ && exclusive != 0) {
+        // The workgroup holds whole words of the output: all rows (exclusive 1: at most kRowsGroupRows of them) or,
+        // with the word-aligned lists, the kRowsGroupRows rows of row group rg (exclusive 2).  Every lane packs the
+        // codes of its row -- two bits per column -- into one word and leaves it in LDS at the row's place in the
+        // group; read back in row order, a wave holds the 64 rows of two output words, and the ballot over bit b of
+        // those code words IS the pair of output words of column b / 2, plane b % 2.  No atomics on the way.
+        const int w_lo = exclusive == 2 ? rg * (kRowsGroupRows / 32) : 0;
+        uint32_t* codes = reinterpret_cast<uint32_t*>(lds);      // [kRowsGroupRows] code words, then 16 column sums
+        __syncthreads();                                         // every wave is done with the table
+        for (int i = threadIdx.x; i < kRowsGroupRows + T; i += blockDim.x) codes[i] = 0u;
+        __syncthreads();
+        const int n = owner ? rperm[slot] : -1;
+        const double vs = BITS == 1 && n >= 0 ? valsumR[slot] : 0.0;
+        const double sc = scale && n >= 0 ? (double)scale[n] : 1.0, sh = scale && n >= 0 ? (double)shift[n] : 0.0;
+        uint32_t cw = 0;
+#pragma unroll
+        for (int cc = 0; cc < T; ++cc) {
+            const double sum = acc[cc] * col_unscale(cc);
+            double z = (BITS == 1 ? 2.0 * sum - vs : sum) * p.step;
+            if (scale) z = fma(sc, z, sh);
+            const float zf = (float)z;
+            const uint32_t code = p.out_bits == 1 ? (zf >= 0.0f ? 1u : 0u) : code2(zf, p.out_inv_step);
+            if (m0 + cc < p.M) cw |= code << (2 * cc);           // (the columns behind M keep their zeros)
+        }
+        if (n >= 0) codes[n - 32 * w_lo] = cw;
+        __syncthreads();
+        uint32_t* words = reinterpret_cast<uint32_t*>(Y);
+        for (int t0 = threadIdx.x; t0 < kRowsGroupRows; t0 += blockDim.x) {      // (whole waves: 64 divides both)
+            const uint32_t mine = codes[t0];
+            uint32_t wa = 0, wb = 0;                             // lane b: output words 2 * (t0 / 64) and + 1 of bit b
+#pragma unroll
+            for (int bb = 0; bb < 32; ++bb) {
+                const unsigned long long mask = __ballot(((mine >> bb) & 1u) != 0);
+                if (lane == bb) {
+                    wa = (uint32_t)mask;
+                    wb = (uint32_t)(mask >> 32);
+                }
+            }
+            const int col = lane >> 1, plane = lane & 1, wr = w_lo + 2 * (t0 / kWave);
+            if (lane < 32 && plane < p.out_bits) {
+                uint32_t* at = words + ((size_t)plane * p.out_Kw + wr) * p.Mp + m0 + col;
+                if (wr < p.out_Kw) at[0] = wa;
+                if (wr + 1 < p.out_Kw) at[p.Mp] = wb;
+                const uint32_t cnt = (uint32_t)(__builtin_popcount(wa) + __builtin_popcount(wb)) << plane;
+                if (cnt) __hip_atomic_fetch_add(codes + kRowsGroupRows + col, cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+        }
+        __syncthreads();
+        // column sums: stored by the one row group, added up over several (cleared before the launch)
+        if (threadIdx.x < T) {
+            const uint32_t tot = codes[kRowsGroupRows + threadIdx.x];
+            uint32_t* at = words + (size_t)p.out_bits * p.out_Kw * p.Mp + m0 + threadIdx.x;
+            if (exclusive == 1) *at = tot;
+            else if (tot) __hip_atomic_fetch_add(at, tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        return;
+    }
     if (REQ) {
         // exclusive 0: every word of the columns may hold rows of this workgroup and of others; 1: one row group,
         // the workgroup holds all rows; 2: word-aligned lists, the rows of row group rg are those of
