@@ -175,6 +175,11 @@ __device__ __forceinline__ void rows_task(
         }
     }
     __syncthreads();
+    if (colsum == nullptr && wave == 0 && lane < T) {            // the waves' partial sums become one sum per column,
+        int tot = 0;                                             // read below after two more barriers
+        for (int w = 0; w < waves; ++w) tot += cs_part[w * T + lane];
+        cs_part[lane] = tot;
+    }
     double acc[T];
     {
         const int i = lane & 15, g = lane >> 4;
@@ -242,12 +247,7 @@ __device__ __forceinline__ void rows_task(
         for (int cc = 0; cc < T; ++cc) {
             int P = 0;
             for (int pp = 0; pp < split; ++pp) P += tiles_of_block[pp * (kWave * T) + lane * T + cc];
-            int cs = 0;
-            if (colsum) {
-                cs = colsum[m0 + cc];                            // m0 + 15 < Mp: Mp is a multiple of 64
-            } else {
-                for (int w = 0; w < waves; ++w) cs += cs_part[w * T + cc];
-            }
+            const int cs = colsum ? colsum[m0 + cc] : cs_part[cc];          // m0 + 15 < Mp: Mp is a multiple of 64
             const int d = BITS == 1 ? 4 * P - rs - 2 * cs : 2 * P - cs;
             acc[cc] = a0 * (double)d * col_scale(cc);  // in the scaled domain of column cc's products
         }
