@@ -87,6 +87,43 @@ __device__ __forceinline__ uint32_t codes4(uint32_t x0, uint32_t x1, int d) {
     return t;
 }
 
+// Operands of this kernel's matrix steps.  A sign word is expanded once per wave, tile and step, the activation
+// words once per workgroup and step, so the weight side gets the cheap form: dword d of the weight operand is the
+// word masked IN PLACE -- bit d of every nibble, i.e. the FP4 numbers 0.5 (d = 0), 1 (d = 1), 2 (d = 2); only
+// d = 3, whose bit would be the sign, is shifted first (to bit 2: the number 2) -- five instructions a word instead
+// of seven.  The activation side makes up for the scales: its dword d holds code * 2 (d = 0: the FP4 numbers 2,
+// 4, 6), code (d = 1: 1, 2, 3) or code / 2 (d = 2, 3: 0.5, 1, 1.5), so that every product is bit * code and the
+// float accumulator holds P = sum_k bit * code itself (exact below 2^24).  Nibble t of dword d <-> bit d + 4t of
+// the word on both sides, as in apb_fp4_expand.h.
+__device__ __forceinline__ void expand_signs_scaled(uint32_t w, v8i& f) {
+    f[0] = (int)(w & kNib);
+    f[1] = (int)(w & (kNib << 1));
+    f[2] = (int)(w & (kNib << 2));
+    f[3] = (int)((w >> 1) & (kNib << 2));
+}
+template <int BITS>
+__device__ __forceinline__ void expand_acts_scaled(uint32_t w0, uint32_t w1, v8i& f) {
+    if (BITS == 1) {                                             // code = bit: 2, 1, 0.5, 0.5
+        f[0] = (int)((w0 << 2) & (kNib << 2));
+        f[1] = (int)(w0 & (kNib << 1));
+        f[2] = (int)((w0 >> 2) & kNib);
+        f[3] = (int)((w0 >> 3) & kNib);
+    } else {
+        // x0, x1: the plane bits of dword d at the bottom of every nibble
+        {   // d = 0: code * 2 = 0b0100, 0b0110, 0b0111 for codes 1, 2, 3: bit 2 = x0 | x1, bit 1 = x1, bit 0 = x0 & x1
+            const uint32_t x0 = w0 & kNib, x1 = w1 & kNib;
+            f[0] = (int)(((x0 | x1) << 2) | (x1 << 1) | (x0 & x1));
+        }
+        {   // d = 1: code = 0b0010, 0b0100, 0b0101: bit 2 = x1, bit 1 = x0 & ~x1, bit 0 = x0 & x1
+            const uint32_t x0 = (w0 >> 1) & kNib, x1 = (w1 >> 1) & kNib, both = x0 & x1;
+            f[1] = (int)((x1 << 2) | ((x0 ^ both) << 1) | both);
+        }
+#pragma unroll
+        for (int d = 2; d < 4; ++d)                              // code / 2: bit 1 = x1, bit 0 = x0
+            f[d] = (int)(((w1 >> (d - 1)) & (kNib << 1)) | ((w0 >> d) & kNib));
+    }
+}
+
 __device__ __forceinline__ v4f mfma_fp4_16(const v8i& a, const v8i& b, const v4f& c) {
     return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 4, 4, 0, kScaleOne, 0, kScaleOne);
 }
@@ -163,7 +200,7 @@ __device__ __forceinline__ void rows_task(
                     const int row = 4 * (it >> 6) + ((it & (kWave - 1)) >> 4);
                     if (row < p.Kw) my_cs += __builtin_popcount(w0[u]) + 2 * __builtin_popcount(w1[u]);
                     v8i fb;
-                    expand_words<BITS>(w0[u], w1[u], fb);
+                    expand_acts_scaled<BITS>(w0[u], w1[u], fb);
                     stage[it] = v4u{(uint32_t)fb[0], (uint32_t)fb[1], (uint32_t)fb[2], (uint32_t)fb[3]};
                 }
             }
@@ -213,7 +250,7 @@ __device__ __forceinline__ void rows_task(
                 for (int d = 0; d < 4; ++d) fb[d] = (int)bq[d];
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
-                    expand_words<1>(a[t], 0u, fa);
+                    expand_signs_scaled(a[t], fa);
                     c[t] = mfma_fp4_16(fa, fb, c[t]);
                 }
             };
@@ -237,7 +274,7 @@ __device__ __forceinline__ void rows_task(
 #pragma unroll
         for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) tile[(16 * t + 4 * g + r) * T + i] = (int)(c[t][r] * 4.0f);
+            for (int r = 0; r < 4; ++r) tile[(16 * t + 4 * g + r) * T + i] = (int)c[t][r];
         __syncthreads();
         const int n = active ? rperm[slot] : -1;
         const int rs = BITS == 1 && n >= 0 ? rowsum[n] : 0;
