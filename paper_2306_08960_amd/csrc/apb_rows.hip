@@ -128,6 +128,13 @@ __device__ __forceinline__ v4f mfma_fp4_16(const v8i& a, const v8i& b, const v4f
     return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 4, 4, 0, kScaleOne, 0, kScaleOne);
 }
 
+// The code table starts at LDS address 0 (the kernels here have no static LDS, which the launchers check), so a
+// list entry -- the byte offset of its table row -- IS the address: read through a pointer made from the number,
+// the read needs no address arithmetic at all (through the kernel's shared array the compiler adds the array's
+// link-time base, one vector instruction per step).
+typedef __attribute__((address_space(3))) const v2u lds_table_row;
+__device__ __forceinline__ v2u table_row(uint32_t offset) { return *reinterpret_cast<lds_table_row*>(offset); }
+
 // acc[c] += v * code(column c of the table row q) * 2^(col_bit(c) - 1042), c = 0..15.  `m` is a register pair whose
 // low half stays zero: the masked nibble in its high half makes it the float64 multiplicand.
 __device__ __forceinline__ void accumulate16(double (&acc)[T], v2i& m, const v2u& q, double v) {
@@ -363,14 +370,14 @@ __device__ __forceinline__ void rows_task(
         }
         v2i m = v2i{0, 0};
         // kq[a], vq[a]: the entry of step j + a; q: the table row of the step about to be processed
-        v2u q = *reinterpret_cast<const v2u*>(lds + kq[0]);     // (offset 0 for an empty list: in bounds)
+        v2u q = table_row(kq[0]);     // (offset 0 for an empty list: in bounds)
         int j = 0;
         for (; j + kAhead <= n_steps; j += kAhead) {
 #pragma unroll
             for (int a = 0; a < kAhead; ++a) {
                 const v2u qc = q;
                 // the row of step j + a + 1 (slot 0 was refilled kAhead - 1 steps ago)
-                q = *reinterpret_cast<const v2u*>(lds + kq[(a + 1) % kAhead]);
+                q = table_row(kq[(a + 1) % kAhead]);
                 // the slot is refilled before its old value is consumed (measured faster than after: the loads
                 // get a full kAhead steps of lead)
                 const double vcur = vq[a];
@@ -381,7 +388,7 @@ __device__ __forceinline__ void rows_task(
             }
         }
         for (int a = 0; j < n_steps; ++j, ++a) {                 // at most kAhead - 1 steps left, all in the queue
-            const v2u qc = a == 0 ? q : *reinterpret_cast<const v2u*>(lds + kq[a]);
+            const v2u qc = a == 0 ? q : table_row(kq[a]);
             accumulate16(acc, m, qc, vq[a]);
         }
     }
@@ -639,12 +646,27 @@ size_t rows_lds_bytes(const LayerDev& L, int waves, int split) {
 // bytes of LDS the packed-output epilogue needs for a layer of N rows (both planes) -- it reuses the table's place
 size_t rows_merge_bytes(int N) { return ((size_t)2 * ((N + 31) / 32) * T + T) * sizeof(uint32_t); }
 
+// The kernels address their code table from LDS address 0 (table_row): true while they have no static LDS in
+// front of the dynamic array.  Checked once per kernel and process, from the kernel's own attributes.
+int check_no_static_lds(const void* kernel, std::atomic<int>& state) {
+    int st = state.load(std::memory_order_acquire);
+    if (st == 0) {
+        hipFuncAttributes attr;
+        APB_HIP(hipFuncGetAttributes(&attr, kernel));
+        st = attr.sharedSizeBytes == 0 ? 1 : -1;
+        state.store(st, std::memory_order_release);
+    }
+    return st == 1 ? APB_OK : APB_ERR_SHAPE;
+}
+
 template <int BITS, bool REQ, int SPLIT>
 int launch_rows_split(const LayerDev& L, const uint32_t* planes, const int32_t* colsum, const float* scale, const float* shift,
                       float* Y, const RowsParams& p, int waves, hipStream_t s) {
     size_t lds = rows_lds_bytes(L, waves, SPLIT) + kColsumBytes;
     if (REQ) lds = std::max(lds, rows_merge_bytes(L.N));
     if (lds > (size_t)kMaxLdsBytes) return APB_ERR_SHAPE;
+    static std::atomic<int> no_static_lds{0};
+    if (const int rc = check_no_static_lds(reinterpret_cast<const void*>(&k_forward_rows<BITS, REQ, SPLIT>), no_static_lds)) return rc;
     if (lds > 64 * 1024) {                                      // more LDS than a launch gets without asking
         static std::atomic<size_t> asked[kMaxDevices];          // largest size asked for, per device and kernel
         int dev = 0;
@@ -671,6 +693,8 @@ int launch_rows_tailed(const LayerDev& L, const uint32_t* planes, const int32_t*
     size_t lds = p.lds_main_bytes + kColsumBytes;               // (rows_params sized it for both task shapes)
     if (REQ) lds = std::max(lds, rows_merge_bytes(L.N));
     if (lds > (size_t)kMaxLdsBytes) return APB_ERR_SHAPE;
+    static std::atomic<int> no_static_lds{0};
+    if (const int rc = check_no_static_lds(reinterpret_cast<const void*>(&k_forward_rows_tailed<BITS, REQ>), no_static_lds)) return rc;
     if (lds > 64 * 1024) {
         static std::atomic<size_t> asked[kMaxDevices];
         int dev = 0;
