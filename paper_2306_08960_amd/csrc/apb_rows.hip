@@ -360,8 +360,11 @@ __device__ __forceinline__ void rows_task(
             return __builtin_bit_cast(double, r);
         };
         constexpr int kAhead = 4;
+        // The offsets wait in kAhead registers (a slot is free once its table row has been read, one step before its
+        // value is used); the values in twice as many, used as two halves in turn, so that the load for step
+        // j + kAhead never lands in the register the multiply-adds of step j still read -- no copies.
         uint32_t kq[kAhead];
-        double vq[kAhead];
+        double vq[2 * kAhead];
 #pragma unroll
         for (int a = 0; a < kAhead; ++a) {
             const int j = min(a, max(n_steps - 1, 0));
@@ -369,27 +372,39 @@ __device__ __forceinline__ void rows_task(
             vq[a] = n_steps > 0 ? load_v(j) : 0.0;
         }
         v2i m = v2i{0, 0};
-        // kq[a], vq[a]: the entry of step j + a; q: the table row of the step about to be processed
-        v2u q = table_row(kq[0]);     // (offset 0 for an empty list: in bounds)
+        // kq[a], vq[half * kAhead + a]: the entry of step j + a; q: the table row of the step about to be processed
+        v2u q = table_row(kq[0]);                               // (offset 0 for an empty list: in bounds)
         int j = 0;
-        for (; j + kAhead <= n_steps; j += kAhead) {
+        // kAhead steps on one half of vq, refilling the other (the slots are refilled before the multiply-adds:
+        // measured faster than after, the loads get a full kAhead steps of lead)
+        auto four_steps = [&](int half) {
 #pragma unroll
             for (int a = 0; a < kAhead; ++a) {
                 const v2u qc = q;
-                // the row of step j + a + 1 (slot 0 was refilled kAhead - 1 steps ago)
                 q = table_row(kq[(a + 1) % kAhead]);
-                // the slot is refilled before its old value is consumed (measured faster than after: the loads
-                // get a full kAhead steps of lead)
-                const double vcur = vq[a];
                 const int jn = min(j + a + kAhead, n_steps - 1); // past the end: the last entry again, never used
                 kq[a] = load_k(jn);
-                vq[a] = load_v(jn);
-                accumulate16(acc, m, qc, vcur);
+                if (half == 0) vq[kAhead + a] = load_v(jn); else vq[a] = load_v(jn);
+                accumulate16(acc, m, qc, half == 0 ? vq[a] : vq[kAhead + a]);
             }
+            j += kAhead;
+        };
+        while (j + 2 * kAhead <= n_steps) {
+            four_steps(0);
+            four_steps(1);
         }
-        for (int a = 0; j < n_steps; ++j, ++a) {                 // at most kAhead - 1 steps left, all in the queue
-            const v2u qc = a == 0 ? q : table_row(kq[a]);
-            accumulate16(acc, m, qc, vq[a]);
+        // fewer than 2 kAhead steps left: kAhead more if there are, then what waits in the queue
+        if (j + kAhead <= n_steps) {
+            four_steps(0);
+            for (int a = 0; j < n_steps; ++j, ++a) {
+                const v2u qc = a == 0 ? q : table_row(kq[a]);
+                accumulate16(acc, m, qc, vq[kAhead + a]);
+            }
+        } else {
+            for (int a = 0; j < n_steps; ++j, ++a) {
+                const v2u qc = a == 0 ? q : table_row(kq[a]);
+                accumulate16(acc, m, qc, vq[a]);
+            }
         }
     }
 
