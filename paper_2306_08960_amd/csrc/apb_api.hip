@@ -255,7 +255,7 @@ int compress_impl(const float* W, int N, int K, float delta, float alpha, hipStr
     std::vector<int32_t> rperm, rblk;
     std::vector<uint32_t> rek;
     std::vector<double> rev, rvalsum;
-    if ((long long)32 * d.Kw * kRowsRowBytes <= kRowsMaxTableBytes && nnz >= (long long)4 * N) {
+    if ((long long)32 * d.Kw * kRowsStageBytesPerK <= kRowsMaxTableBytes && nnz >= (long long)4 * N) {
         build_row_lists(hrow_ptr, hcol, hval, rperm, rblk, rek, rev, rvalsum, 0);
         const long long steps = rblk.back();
         if (steps * kWave <= 2 * nnz) {                   // at most half of the list entries are padding
