@@ -71,7 +71,7 @@ struct LayerDev {
 
 constexpr int kRowsCols = 16;            // output columns one workgroup of the rows-in-lanes kernel covers
 constexpr int kRowsGroupRows = 256;      // rows of one group of the word-aligned lists: 4 blocks of 64, 8 output words
-constexpr int kRowsRowBytes = 4;         // bytes of its code table per value of k (2 bits per column)
+constexpr int kRowsRowBytes = 8;         // bytes of its code table per value of k (two dwords of 8 columns x 2 bits)
 constexpr int kRowsStageBytesPerK = 8;   // LDS per value of k of its staged activation operand (16 columns x FP4)
 constexpr int kRowsMaxTableBytes = 144 * 1024;   // the staged operand of all of K, and the table after it, have to fit on chip
 

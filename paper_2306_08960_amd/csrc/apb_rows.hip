@@ -6,20 +6,21 @@
 // convolution with 3 % residuals.)  Here a lane owns one row of the sparse matrix and kRowsCols = 16 output
 // columns:
 //   * a workgroup (up to 8 waves = 512 rows) takes one group of 16 columns and keeps the code table of those
-//     columns for ALL of K in LDS, two bits per activation, 4 bytes per value of k -- built once, shared by
+//     columns for ALL of K in LDS, two bits per activation in 8 bytes per value of k -- built once, shared by
 //     every row, no walk over chunks of K and no barrier inside the residual loop;
 //   * a step of the residual loop: the lane loads its next residual (table offset of its column, value) from
 //     the row lists laid out at compress time ([step][lane], so the loads are contiguous), reads the 16 codes
-//     of that column with ONE 4-byte LDS read and does 16 x (field mask + float64 multiply-add) into 16
+//     of that column with ONE 8-byte LDS read and does 16 x (field mask + float64 multiply-add) into 16
 //     accumulators it keeps in registers.  Nothing is wave-uniform, so there is no scalar traffic, no index
 //     register and no out-of-order counter shared between entry loads and table reads: the entry loads are
 //     vector loads (in-order counter), fetched several steps ahead.
 // Per residual and output that is 2 vector-ALU instructions and 1/16 of an LDS read.
 // The binary part runs first on the matrix cores exactly as in the other kernels (apb_fp4_expand.h), here
 // with the 16x16x128 FP4 instruction: a wave computes its 64 rows x 16 columns as four tiles.
-// A table row is 4 bytes: the 16 codes of one k, two bits each.  A code becomes a float64 multiplicand by masking
-// its two bits in place inside the high half of a register pair (a subnormal number; see col_bit); the residuals
-// are stored times 2^895 so that the products are ordinary numbers, and all scales are powers of two.
+// A table row is two dwords: the 16 codes of one k, two bits each, eight to a dword (its low half).  A code becomes
+// a float64 multiplicand by masking its two bits in place inside the high half of a register pair (a subnormal
+// number; see col_bit); the residuals are stored times 2^895 so that the products are ordinary numbers, and all
+// scales are powers of two.
 #include <algorithm>
 #include <atomic>
 
@@ -33,29 +34,26 @@ namespace {
 constexpr int T = kRowsCols;
 constexpr int kMaxDevices = 64;
 constexpr int kBufferFlags = 0x00020000;                        // fourth word of a raw buffer descriptor: 32-bit data, no swizzle
-constexpr int kRowBytes = kRowsRowBytes;                        // table bytes per value of k: 16 columns x 2 bits
+constexpr int kRowBytes = kRowsRowBytes;                        // table bytes per value of k: two dwords of 8 columns x 2 bits
 
-// Column c of a table row sits at bits 2c and 2c + 1.  Its multiplicand is that field left where it is in an
-// otherwise zero high half of a float64 -- a subnormal number, code * 2^(P - 1042) with P the bit position -- so
-// no shift and no conversion is needed for the ten columns that lie in the mantissa field (bits 0..19); the other
-// six are taken from the row shifted right by 12.  Every column thus carries its own power-of-two scale, which
-// commutes with rounding and is taken out at the end.
-__host__ __device__ constexpr bool col_shifted(int c) { return c >= 10; }
-__host__ __device__ constexpr int col_bit(int c) { return 2 * c - (col_shifted(c) ? 12 : 0); }
+// Column c of a table row sits in dword c / 8 at bits 2 * (c % 8) and the bit above.  Its multiplicand is that
+// field left where it is in an otherwise zero high half of a float64 -- a subnormal number, code * 2^(P - 1042)
+// with P the bit position; all eight fields of a dword lie in the mantissa part (bits 0..19) of that half, so a
+// multiplicand costs one AND: no shift, no conversion.  Every column thus carries its own power-of-two scale,
+// which commutes with rounding and is taken out at the end.
+__host__ __device__ constexpr int col_bit(int c) { return 2 * (c & 7); }
 static_assert(kEntValScaleLog2 == 895, "col_unscale undoes 2^895 * 2^(P - 1042)");
 // 2^(147 - col_bit(c)) and its inverse, by column (literals: nothing to evaluate at run time, and no function
 // call in device code).
 __device__ __forceinline__ double col_unscale(int c) {
-    constexpr double t[16] = {0x1p147, 0x1p145, 0x1p143, 0x1p141, 0x1p139, 0x1p137, 0x1p135, 0x1p133,
-                              0x1p131, 0x1p129, 0x1p139, 0x1p137, 0x1p135, 0x1p133, 0x1p131, 0x1p129};
-    return t[c];
+    constexpr double t[8] = {0x1p147, 0x1p145, 0x1p143, 0x1p141, 0x1p139, 0x1p137, 0x1p135, 0x1p133};
+    return t[c & 7];
 }
 __device__ __forceinline__ double col_scale(int c) {
-    constexpr double t[16] = {0x1p-147, 0x1p-145, 0x1p-143, 0x1p-141, 0x1p-139, 0x1p-137, 0x1p-135, 0x1p-133,
-                              0x1p-131, 0x1p-129, 0x1p-139, 0x1p-137, 0x1p-135, 0x1p-133, 0x1p-131, 0x1p-129};
-    return t[c];
+    constexpr double t[8] = {0x1p-147, 0x1p-145, 0x1p-143, 0x1p-141, 0x1p-139, 0x1p-137, 0x1p-135, 0x1p-133};
+    return t[c & 7];
 }
-static_assert(col_bit(0) == 0 && col_bit(4) == 8 && col_bit(9) == 18 && col_bit(10) == 8 && col_bit(15) == 18,
+static_assert(col_bit(0) == 0 && col_bit(4) == 8 && col_bit(7) == 14 && col_bit(8) == 0 && col_bit(15) == 14,
               "the literals above are 2^(147 - col_bit)");
 static_assert(T == 16, "a table row holds 16 columns");
 
@@ -135,16 +133,15 @@ __device__ __forceinline__ v4f mfma_fp4_16(const v8i& a, const v8i& b, const v4f
 // list entry -- the byte offset of its table row -- IS the address: read through a pointer made from the number,
 // the read needs no address arithmetic at all (through the kernel's shared array the compiler adds the array's
 // link-time base, one vector instruction per step).
-typedef __attribute__((address_space(3))) const uint32_t lds_table_row;
-__device__ __forceinline__ uint32_t table_row(uint32_t offset) { return *reinterpret_cast<lds_table_row*>(offset); }
+typedef __attribute__((address_space(3))) const v2u lds_table_row;
+__device__ __forceinline__ v2u table_row(uint32_t offset) { return *reinterpret_cast<lds_table_row*>(offset); }
 
 // acc[c] += v * code(column c of the table row q) * 2^(col_bit(c) - 1042), c = 0..15.  `m` is a register pair whose
 // low half stays zero: the masked two-bit field in its high half makes it the float64 multiplicand.
-__device__ __forceinline__ void accumulate16(double (&acc)[T], v2i& m, uint32_t q, double v) {
-    const uint32_t sh = q >> 12;
+__device__ __forceinline__ void accumulate16(double (&acc)[T], v2i& m, const v2u& q, double v) {
 #pragma unroll
     for (int c = 0; c < T; ++c) {
-        m.y = (int)((col_shifted(c) ? sh : q) & (0x3u << col_bit(c)));
+        m.y = (int)(q[c >> 3] & (0x3u << col_bit(c)));
         acc[c] = fma(v, __builtin_bit_cast(double, m), acc[c]);
     }
 }
@@ -300,10 +297,10 @@ __device__ __forceinline__ void rows_task(
         __syncthreads();                                         // the tiles are read; the table may overwrite them
     }
 
-    // ---- code table of the 16 columns for all of K: table[k] = 4 bytes, column c at bits 2c, 2c + 1.  Thread ->
-    // (word row j, quad d of its 32 values of k): it reads the 16 columns' words of row j (64 contiguous bytes per
-    // plane), takes nibble d of each and writes the four finished table rows k = 32*j + 4*d + 0..3 -- 16
-    // contiguous bytes -- with one store.
+    // ---- code table of the 16 columns for all of K: table[k] = two dwords, column c in dword c / 8 at bits
+    // 2 * (c % 8).  Thread -> (word row j, quad d of its 32 values of k): it reads the 16 columns' words of row j
+    // (64 contiguous bytes per plane), takes nibble d of each and writes the four finished table rows
+    // k = 32*j + 4*d + 0..3 -- 32 contiguous bytes -- with two 16-byte stores.
     {
         const int items = p.Kw * 8;
         const size_t plane_stride = (size_t)p.Kw * p.Mp;
@@ -312,7 +309,7 @@ __device__ __forceinline__ void rows_task(
             const v4u* src0 = reinterpret_cast<const v4u*>(planes + (size_t)j * p.Mp + m0);
             const v4u* src1 = reinterpret_cast<const v4u*>(planes + plane_stride + (size_t)j * p.Mp + m0);
             // u[g], g = 0..3: byte q of u[g] holds the codes of columns 4g .. 4g+3 for k = 32*j + 4*d + q,
-            // i.e. byte g of table row q
+            // i.e. byte g % 2 of dword g / 2 of table row q
             uint32_t u[4];
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
@@ -321,15 +318,12 @@ __device__ __forceinline__ void rows_task(
                 u[g] = codes4<BITS>(x0[0], x1[0], d) | (codes4<BITS>(x0[1], x1[1], d) << 2) |
                        (codes4<BITS>(x0[2], x1[2], d) << 4) | (codes4<BITS>(x0[3], x1[3], d) << 6);
             }
-            // 4 x 4 byte transpose: row q = { u[0].q, u[1].q, u[2].q, u[3].q }
-            const uint32_t a01 = __builtin_amdgcn_perm(u[1], u[0], 0x05010400u);   // u0.0 u1.0 u0.1 u1.1
-            const uint32_t b01 = __builtin_amdgcn_perm(u[1], u[0], 0x07030602u);   // u0.2 u1.2 u0.3 u1.3
-            const uint32_t a23 = __builtin_amdgcn_perm(u[3], u[2], 0x05010400u);
-            const uint32_t b23 = __builtin_amdgcn_perm(u[3], u[2], 0x07030602u);
-            *reinterpret_cast<v4u*>(lds + (size_t)(32 * j + 4 * d) * kRowBytes) =
-                v4u{__builtin_amdgcn_perm(a23, a01, 0x05040100u),                  // u0.0 u1.0 u2.0 u3.0
-                    __builtin_amdgcn_perm(a23, a01, 0x07060302u), __builtin_amdgcn_perm(b23, b01, 0x05040100u),
-                    __builtin_amdgcn_perm(b23, b01, 0x07060302u)};
+            // table row q = { u[0].q | u[1].q << 8, u[2].q | u[3].q << 8 } (selector byte 0x0c: zero)
+            v4u* dst = reinterpret_cast<v4u*>(lds + (size_t)(32 * j + 4 * d) * kRowBytes);
+            dst[0] = v4u{__builtin_amdgcn_perm(u[1], u[0], 0x0c0c0400u), __builtin_amdgcn_perm(u[3], u[2], 0x0c0c0400u),
+                         __builtin_amdgcn_perm(u[1], u[0], 0x0c0c0501u), __builtin_amdgcn_perm(u[3], u[2], 0x0c0c0501u)};
+            dst[1] = v4u{__builtin_amdgcn_perm(u[1], u[0], 0x0c0c0602u), __builtin_amdgcn_perm(u[3], u[2], 0x0c0c0602u),
+                         __builtin_amdgcn_perm(u[1], u[0], 0x0c0c0703u), __builtin_amdgcn_perm(u[3], u[2], 0x0c0c0703u)};
         }
     }
     __syncthreads();
@@ -368,14 +362,14 @@ __device__ __forceinline__ void rows_task(
         }
         v2i m = v2i{0, 0};
         // kq[a], vq[half * kAhead + a]: the entry of step j + a; q: the table row of the step about to be processed
-        uint32_t q = table_row(kq[0]);                               // (offset 0 for an empty list: in bounds)
+        v2u q = table_row(kq[0]);                               // (offset 0 for an empty list: in bounds)
         int j = 0;
         // kAhead steps on one half of vq, refilling the other (the slots are refilled before the multiply-adds:
         // measured faster than after, the loads get a full kAhead steps of lead)
         auto four_steps = [&](int half) {
 #pragma unroll
             for (int a = 0; a < kAhead; ++a) {
-                const uint32_t qc = q;
+                const v2u qc = q;
                 q = table_row(kq[(a + 1) % kAhead]);
                 const int jn = min(j + a + kAhead, n_steps - 1); // past the end: the last entry again, never used
                 kq[a] = load_k(jn);
@@ -392,12 +386,12 @@ __device__ __forceinline__ void rows_task(
         if (j + kAhead <= n_steps) {
             four_steps(0);
             for (int a = 0; j < n_steps; ++j, ++a) {
-                const uint32_t qc = a == 0 ? q : table_row(kq[a]);
+                const v2u qc = a == 0 ? q : table_row(kq[a]);
                 accumulate16(acc, m, qc, vq[kAhead + a]);
             }
         } else {
             for (int a = 0; j < n_steps; ++j, ++a) {
-                const uint32_t qc = a == 0 ? q : table_row(kq[a]);
+                const v2u qc = a == 0 ? q : table_row(kq[a]);
                 accumulate16(acc, m, qc, vq[a]);
             }
         }
