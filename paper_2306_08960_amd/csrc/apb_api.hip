@@ -253,6 +253,25 @@ int compress_impl(const float* W, int N, int K, float delta, float alpha, hipStr
     // Row lists for the rows-in-lanes kernel: only where K fits its on-chip code table and rows carry
     // enough residuals for the padding of the lists (to the longest row of each block of 64) to stay small.
     std::vector<int32_t> rperm, rblk;
+    // The sign words of a block of 64 slots are stored in the order the matrix tiles take them: the kernel's lane
+    // i (of 16) owns slots i, 16 + i, 32 + i, 48 + i of the block -- row i of its four tiles -- and finds their
+    // words of one word row side by side, position 4 * i + t: one 16-byte load.
+    auto signs_in_tile_order = [&](const std::vector<int32_t>& slot_rows, uint32_t* out) -> int {
+        std::vector<int32_t> order(slot_rows.size());
+        for (size_t s0 = 0; s0 < slot_rows.size(); s0 += kWave)
+            for (int i = 0; i < 16; ++i)
+                for (int t = 0; t < 4; ++t) order[s0 + 4 * i + t] = slot_rows[s0 + 16 * t + i];
+        int32_t* tmp = nullptr;
+        int rc2 = dev_alloc(&tmp, order.size());
+        if (rc2 != APB_OK) return rc2;
+        hipError_t e = hipMemcpyAsync(tmp, order.data(), order.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
+        if (e == hipSuccess) rc2 = launch_slot_major_signs(d.sign, tmp, d.rows_Nr, d.Kw, d.rows_Kw4, out, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);        // `order` and `tmp` are released below
+        (void)hipFree(tmp);
+        if (rc2 != APB_OK) return rc2;
+        APB_HIP(e);
+        return APB_OK;
+    };
     std::vector<uint32_t> rek;
     std::vector<double> rev, rvalsum;
     if ((long long)32 * d.Kw * kRowsStageBytesPerK <= kRowsMaxTableBytes && nnz >= (long long)4 * N) {
@@ -273,8 +292,7 @@ int compress_impl(const float* W, int N, int K, float delta, float alpha, hipStr
             APB_HIP(hipMemcpyAsync(d.rows_ek, rek.data(), rek.size() * sizeof(uint32_t), hipMemcpyHostToDevice, s));
             APB_HIP(hipMemcpyAsync(d.rows_ev, rev.data(), rev.size() * sizeof(double), hipMemcpyHostToDevice, s));
             APB_HIP(hipMemcpyAsync(d.rows_valsum, rvalsum.data(), rvalsum.size() * sizeof(double), hipMemcpyHostToDevice, s));
-            if ((rc = launch_slot_major_signs(d.sign, d.rows_perm, d.rows_Nr, d.Kw, d.rows_Kw4, d.rows_sign, s)) != APB_OK)
-                return rc;
+            if ((rc = signs_in_tile_order(rperm, d.rows_sign)) != APB_OK) return rc;
             // the word-aligned lists beside them (more than one group of rows; the same padding rule)
             if (N > kRowsGroupRows) {
                 APB_HIP(hipStreamSynchronize(s));              // the staging vectors above are reused
@@ -293,8 +311,7 @@ int compress_impl(const float* W, int N, int K, float delta, float alpha, hipStr
                     APB_HIP(hipMemcpyAsync(d.rowsw_ek, rek.data(), rek.size() * sizeof(uint32_t), hipMemcpyHostToDevice, s));
                     APB_HIP(hipMemcpyAsync(d.rowsw_ev, rev.data(), rev.size() * sizeof(double), hipMemcpyHostToDevice, s));
                     APB_HIP(hipMemcpyAsync(d.rowsw_valsum, rvalsum.data(), rvalsum.size() * sizeof(double), hipMemcpyHostToDevice, s));
-                    if ((rc = launch_slot_major_signs(d.sign, d.rowsw_perm, d.rows_Nr, d.Kw, d.rows_Kw4, d.rowsw_sign, s)) != APB_OK)
-                        return rc;
+                    if ((rc = signs_in_tile_order(rperm, d.rowsw_sign)) != APB_OK) return rc;
                 }
             }
         }

@@ -54,7 +54,8 @@ struct LayerDev {
     int32_t* rows_blk = nullptr;   // [Nr/64 + 1]
     uint32_t* rows_ek = nullptr;   // [steps][64] kRowsRowBytes * column: byte offset of the column's row in the code table
     double* rows_ev = nullptr;     // [steps][64] residual * 2^kEntValScaleLog2
-    uint32_t* rows_sign = nullptr; // [Kw4][Nr]   sign words, slot-major in this order (pad rows and slots zero)
+    uint32_t* rows_sign = nullptr; // [Kw4][Nr]   sign words of the slots (pad rows and slots zero); inside a block of 64
+                                   //             slots, slot 16 * t + i sits at position 4 * i + t (the order the matrix tiles take them)
     double* rows_valsum = nullptr; // [Nr]        sum of the residuals of the slot's row (float64, CSR order)
     // The same lists with the rows sorted by residual count only inside groups of kRowsGroupRows consecutive rows
     // (whole 32-row words of a packed output): a workgroup of the packed-output epilogue that takes one such group

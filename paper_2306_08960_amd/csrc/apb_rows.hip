@@ -237,14 +237,16 @@ __device__ __forceinline__ void rows_task(
             for (int d = 4; d < 8; ++d) fa[d] = fb[d] = 0;
             // Sign words are fetched kRing steps ahead (a ring of register sets indexed by step % kRing), so that
             // the expansion and the matrix instructions of a step never wait for that step's own loads.
-            const uint32_t* arow = signR + (size_t)g * p.Nr + (size_t)b * kWave + i;
+            // (the four tiles' words of this lane's rows lie side by side: see the layout of rows_sign)
+            const uint32_t* arow = signR + (size_t)g * p.Nr + (size_t)b * kWave + 4 * i;
             const v4u* stage = reinterpret_cast<const v4u*>(lds) + lane;
             constexpr int kRing = 4;
             uint32_t aw[kRing][4];
             auto load_words = [&](int s, uint32_t (&a)[4]) {
                 const int ss = min(s, steps - 1);                // past the end: a harmless re-read, never used
+                const v4u w = *reinterpret_cast<const v4u*>(arow + (size_t)(4 * ss) * p.Nr);
 #pragma unroll
-                for (int t = 0; t < 4; ++t) a[t] = arow[(size_t)(4 * ss) * p.Nr + 16 * t];
+                for (int t = 0; t < 4; ++t) a[t] = w[t];
             };
             auto one_step = [&](int s, int q) {
                 uint32_t a[4];
